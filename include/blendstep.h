@@ -1,0 +1,180 @@
+/*
+ * blendstep.h - C ABI of the MI355X blended decoder-layer step.
+ *
+ * One call runs one forward step of one Llama-style decoder layer over a
+ * "dense batch" in the sense of BlendServe (Section 2.2, chunked prefill; Section
+ * 4.2): compute-bound prefill rows and memory-bound decode rows side by side,
+ * the decode rows attending to a paged KV cache whose shared-prefix pages
+ * (Section 2.2, prefix sharing; Appendix A.2, runtime prefix tree) are referenced
+ * once and read once per prefix group.
+ *
+ * Conventions
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *     memory on the context's device.  All buffers are caller-owned unless said
+ *     otherwise; the library keeps only its context workspace.
+ *   - bf16 = bfloat16, row-major, innermost index last.
+ *   - Every function returns 0 (BS_OK) or a negative bs_status; the message of
+ *     the last failure on a context is kept for bs_last_error().  Nothing
+ *     throws or aborts across this boundary.  A batch is validated on the host
+ *     before anything is enqueued: a malformed descriptor is an error code,
+ *     never a GPU fault.
+ *   - bs_blend_step is asynchronous on the given stream and never synchronises
+ *     the device.  Calls on one context must not overlap in time on different
+ *     streams (they share the workspace).
+ */
+#ifndef BLENDSTEP_H
+#define BLENDSTEP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum bs_status {
+  BS_OK = 0,
+  BS_EINVAL = -1, /* bad shape, non-monotone CSR, page id out of range, kv_len beyond
+                     its pages, node pages not matching a member's table, a page that
+                     is written this step while referenced more than once, ... */
+  BS_ENOMEM = -2, /* host or device allocation failed */
+  BS_EHIP = -3,   /* a HIP runtime call failed */
+  BS_EUNSUPPORTED = -4 /* shape outside what the kernels are written for */
+} bs_status;
+
+/* Layer shape.  The paper leaves the layer itself open (Section 2.1 names Q/K/V
+ * projections, GQA, softmax attention, FFN; Section 4.2 "layer normalization,
+ * activation, and position embedding"); the Llama-style choices are:
+ * pre-norm RMSNorm (eps inside the root), rotate-half RoPE pairing (i, i+dh/2)
+ * with angle pos * rope_theta^(-2i/dh), scale 1/sqrt(dh), SwiGLU, two residuals.
+ * Supported: head_dim 64 or 128; page_size 16; n_q_heads a multiple of n_kv_heads
+ * with ratio <= 16; d_model, d_ffn, head_dim multiples of 8. */
+typedef struct bs_layer_cfg {
+  int32_t d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, page_size;
+  float rms_eps, rope_theta;
+  int32_t max_positions; /* RoPE table length; 0 = 16384 */
+} bs_layer_cfg;
+
+/* Weights: device, bf16, caller-owned, "out-features major" like a linear layer's
+ * weight matrix (each output feature's d inputs are contiguous):
+ *   w_qkv     [(Hq + 2 Hkv) * dh, d]   rows: q heads, then k heads, then v heads
+ *   w_o       [d, Hq * dh]
+ *   w_gate_up [2 F, d]                 rows: F gate rows, then F up rows
+ *   w_down    [d, F]
+ *   g_attn, g_ffn [d]                  RMSNorm gains */
+typedef struct bs_weights {
+  const void *w_qkv, *w_o, *w_gate_up, *w_down, *g_attn, *g_ffn;
+} bs_weights;
+
+/* Batch descriptor (Section 4.2: a batch is a chunk of prefill tokens plus the
+ * decode requests in flight).  All arrays are HOST int32, caller-owned, and are
+ * copied during the call.
+ *
+ * Sequences [0, n_prefill) are prefill segments (one or more rows, causal among
+ * themselves, attending to their cached tokens too); sequences [n_prefill, n_seq)
+ * are decode sequences with exactly one row.  kv_len[i] is the attended length
+ * AFTER this step's rows are appended: rows of sequence i sit at positions
+ * kv_len[i]-q_len[i] .. kv_len[i]-1 and their keys/values are written there.
+ * Token t of sequence i lives at (page_ids[page_start[i] + t / page_size],
+ * t % page_size).  Shared pages repeat the SAME physical id in every sharer's
+ * table.
+ *
+ * Prefix nodes tell the decode-attention kernel which pages to read once for a
+ * whole group: node n owns pages node_page_ids[node_page_start[n] ..
+ * node_page_start[n+1]) and is shared by the contiguous run of DECODE sequences
+ * [node_seq_first[n], node_seq_first[n] + node_seq_count[n]).  Nodes come in DFS
+ * pre-order (parent before child); in every member's page table the pages of
+ * the root..leaf path come first, in that order.  seq_leaf_node[i] is the
+ * deepest node of sequence i or -1.  Prefill segments may reference shared
+ * pages in their tables but are not node members (seq_leaf_node = -1). */
+typedef struct bs_batch {
+  int32_t n_seq, n_prefill, n_rows;
+  const int32_t *row_start;       /* [n_seq + 1] */
+  const int32_t *kv_len;          /* [n_seq]     */
+  const int32_t *page_start;      /* [n_seq + 1] */
+  const int32_t *page_ids;        /* [page_start[n_seq]] */
+  int32_t n_nodes;
+  const int32_t *node_parent;     /* [n_nodes] -1 for roots */
+  const int32_t *node_page_start; /* [n_nodes + 1] */
+  const int32_t *node_page_ids;   /* [node_page_start[n_nodes]] */
+  const int32_t *node_seq_first;  /* [n_nodes] */
+  const int32_t *node_seq_count;  /* [n_nodes] may be 0 (node unused this step) */
+  const int32_t *seq_leaf_node;   /* [n_seq] */
+} bs_batch;
+
+typedef struct bs_ctx bs_ctx;
+
+/* Flags of bs_blend_step. */
+#define BS_FLAG_SERIAL 0u   /* every kernel on the caller's stream, in order */
+#define BS_FLAG_OVERLAP 1u  /* decode attention on a side stream with its own CU set,
+                               concurrent with the prefill rows' GEMMs (Section 2.2,
+                               operator-level overlapping; Appendix A.2, backend engine) */
+
+/* Create a context on `device`; allocates the RoPE table and workspace that
+ * grows on demand.  *out is NULL on failure; bs_last_error(NULL) then returns
+ * the message.  With device = BS_DEVICE_NONE the context is host-only: it makes
+ * no HIP call and serves bs_validate_batch and bs_resolve_rows; the GPU entry
+ * points return BS_EINVAL on it. */
+#define BS_DEVICE_NONE (-1)
+int bs_create(const bs_layer_cfg *cfg, int device, bs_ctx **out);
+void bs_destroy(bs_ctx *ctx);
+const char *bs_last_error(const bs_ctx *ctx);
+
+/* KV pool layout.  The pool is one device array of n_pages pages; a page holds,
+ * per KV head, a K tile [page_size][dh] and a transposed V tile [dh][page_size]:
+ *   element index of K(page, head, slot, e) = ((page*2 + 0)*Hkv + head)*page_size*dh + slot*dh + e
+ *   element index of V(page, head, slot, e) = ((page*2 + 1)*Hkv + head)*page_size*dh + e*page_size + slot
+ * bs_kv_page_bytes returns the bytes of one page.  bs_kv_pack / bs_kv_unpack
+ * convert (on `stream`, device to device) between that layout and two plain
+ * token-major arrays k, v of shape [n_pages][page_size][Hkv][dh] bf16. */
+int64_t bs_kv_page_bytes(const bs_ctx *ctx);
+int bs_kv_pack(bs_ctx *ctx, const void *k, const void *v, void *kv_pool, int64_t n_pages, void *stream);
+int bs_kv_unpack(bs_ctx *ctx, const void *kv_pool, void *k, void *v, int64_t n_pages, void *stream);
+
+/* One blended step of the layer:
+ *   h = rmsnorm(x; g_attn); q,k,v = h W_qkv^T; RoPE on q,k; k,v appended to the pool;
+ *   o = causal softmax attention per sequence over its pages; x1 = x + o W_o^T;
+ *   y = x1 + (silu(h2 W_gate^T) * (h2 W_up^T)) W_down^T with h2 = rmsnorm(x1; g_ffn).
+ * x, y: device bf16 [n_rows, d_model]; y may not alias x.  kv_pool: device,
+ * n_pages pages, read and (for this step's rows) written.  stream: a hipStream_t
+ * (NULL = the default stream). */
+int bs_blend_step(bs_ctx *ctx, const bs_weights *w, const bs_batch *batch,
+                  const void *x, void *y, void *kv_pool, int64_t n_pages,
+                  void *stream, uint32_t flags);
+
+/* Host-only check of a descriptor against a pool of n_pages pages (the same
+ * validation bs_blend_step performs); touches no GPU. */
+int bs_validate_batch(bs_ctx *ctx, const bs_batch *batch, int64_t n_pages);
+
+/* Host-only page resolution, for tests of the indexing: writes, for every row r
+ * of the batch, the physical page and slot its key/value are appended to. */
+int bs_resolve_rows(bs_ctx *ctx, const bs_batch *batch, int32_t *page_out, int32_t *slot_out);
+
+/* Per-kernel timing.  With profiling on, bs_blend_step brackets each kernel
+ * class with HIP events on the stream it runs on; bs_profile_read waits for the
+ * recorded events and returns the accumulated milliseconds and launch count of
+ * class `which` since the last reset.  Off by default (events cost time). */
+enum { BS_K_PREP = 0, BS_K_GEMM_QKV, BS_K_ATTN_PREFILL, BS_K_ATTN_DECODE, BS_K_ATTN_MERGE,
+       BS_K_GEMM_O, BS_K_GEMM_GATE_UP, BS_K_GEMM_DOWN, BS_K_COUNT };
+int bs_profile_enable(bs_ctx *ctx, int on);
+int bs_profile_read(bs_ctx *ctx, int which, double *total_ms, int64_t *launches);
+int bs_profile_reset(bs_ctx *ctx);
+
+/* Tuning knob: pages per chunk of decode-attention work (even, 2..4096; default 32).
+ * Smaller chunks give more parallelism and more partial states to merge. */
+int bs_set_chunk_pages(bs_ctx *ctx, int32_t pages);
+
+/* Stand-alone entry points of the individual operators (the same kernels the
+ * step launches), for per-kernel parity tests and roofline measurements.
+ *   bs_gemm_nt: C[M,N] = A[M,K] * B[N,K]^T, bf16 in, fp32 accumulate, bf16 out;
+ *   K a multiple of 8. */
+int bs_gemm_nt(bs_ctx *ctx, const void *a, const void *b, void *c,
+               int32_t m, int32_t n, int32_t k, void *stream);
+/*   bs_attention: attention alone over an already appended pool.  q: device bf16
+ *   [n_rows, Hq*dh] (after RoPE); out: device bf16 [n_rows, Hq*dh]. */
+int bs_attention(bs_ctx *ctx, const bs_batch *batch, const void *q, void *out,
+                 const void *kv_pool, int64_t n_pages, void *stream, uint32_t flags);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLENDSTEP_H */

@@ -1,0 +1,286 @@
+"""ctypes binding of libblendstep.so: argument marshalling only.
+
+Every step of the layer runs inside the library's HIP kernels; PyTorch is used
+here for device memory and the current stream.  If the shared object is missing
+the import of the library fails loudly: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import re
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+_SO = os.path.join(_HERE, "libblendstep.so")
+_HEADERS = [os.path.join(_ROOT, "include", "blendstep.h"), os.path.join(_ROOT, "include", "blendstep_builder.h")]
+
+_i32p = C.POINTER(C.c_int32)
+
+K_NAMES = ["prep", "gemm_qkv", "attn_prefill", "attn_decode", "attn_merge", "gemm_o", "gemm_gate_up", "gemm_down"]
+FLAG_SERIAL, FLAG_OVERLAP = 0, 1
+
+
+class LayerCfg(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("page_size", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("max_positions", C.c_int32)]
+
+
+class Weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("w_qkv", "w_o", "w_gate_up", "w_down", "g_attn", "g_ffn")]
+
+
+class BatchDesc(C.Structure):
+    _fields_ = [("n_seq", C.c_int32), ("n_prefill", C.c_int32), ("n_rows", C.c_int32),
+                ("row_start", _i32p), ("kv_len", _i32p), ("page_start", _i32p), ("page_ids", _i32p),
+                ("n_nodes", C.c_int32), ("node_parent", _i32p), ("node_page_start", _i32p),
+                ("node_page_ids", _i32p), ("node_seq_first", _i32p), ("node_seq_count", _i32p),
+                ("seq_leaf_node", _i32p)]
+
+
+class BlendStepError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("blendstep error %d: %s" % (code, msg))
+        self.code = code
+
+
+def declared_functions():
+    """Names of the functions the public headers declare."""
+    names = []
+    for h in _HEADERS:
+        if not os.path.exists(h):
+            continue
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names += re.findall(r"\b(bs_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+_lib = None
+
+
+def raw():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_SO):
+            raise ImportError("%s is not built: run `python __graft_entry__.py` (hipcc, gfx950) first" % _SO)
+        lib = C.CDLL(_SO)
+        lib.bs_create.argtypes = [C.POINTER(LayerCfg), C.c_int, C.POINTER(C.c_void_p)]
+        lib.bs_destroy.argtypes = [C.c_void_p]
+        lib.bs_destroy.restype = None
+        lib.bs_last_error.argtypes = [C.c_void_p]
+        lib.bs_last_error.restype = C.c_char_p
+        lib.bs_kv_page_bytes.argtypes = [C.c_void_p]
+        lib.bs_kv_page_bytes.restype = C.c_int64
+        lib.bs_kv_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        lib.bs_kv_unpack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        lib.bs_blend_step.argtypes = [C.c_void_p, C.POINTER(Weights), C.POINTER(BatchDesc), C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_int64, C.c_void_p, C.c_uint32]
+        lib.bs_validate_batch.argtypes = [C.c_void_p, C.POINTER(BatchDesc), C.c_int64]
+        lib.bs_resolve_rows.argtypes = [C.c_void_p, C.POINTER(BatchDesc), _i32p, _i32p]
+        lib.bs_profile_enable.argtypes = [C.c_void_p, C.c_int]
+        lib.bs_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        lib.bs_profile_reset.argtypes = [C.c_void_p]
+        lib.bs_set_chunk_pages.argtypes = [C.c_void_p, C.c_int32]
+        lib.bs_gemm_nt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                   C.c_void_p]
+        lib.bs_attention.argtypes = [C.c_void_p, C.POINTER(BatchDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                     C.c_void_p, C.c_uint32]
+        _lib = lib
+    return _lib
+
+
+def check_symbols():
+    """Every function the headers declare must be exported by the shared object."""
+    lib = raw()
+    missing = [n for n in declared_functions() if not hasattr(lib, n)]
+    if missing:
+        raise ImportError("libblendstep.so lacks: " + ", ".join(missing))
+    return True
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(_i32p)
+
+
+def marshal_batch(b):
+    """Batch (numpy int32 arrays) -> (BatchDesc, keep-alive list)."""
+    arrs = {}
+    for name in ("row_start", "kv_len", "page_start", "page_ids", "node_parent", "node_page_start",
+                 "node_page_ids", "node_seq_first", "node_seq_count", "seq_leaf_node"):
+        a = np.ascontiguousarray(getattr(b, name), dtype=np.int32)
+        if a.size == 0:
+            a = np.zeros(1, dtype=np.int32)
+        arrs[name] = a
+    d = BatchDesc(n_seq=b.n_seq, n_prefill=b.n_prefill, n_rows=b.n_rows, n_nodes=b.n_nodes,
+                  **{k: _ptr(v) for k, v in arrs.items()})
+    return d, arrs
+
+
+@dataclass
+class DeviceState:
+    weights: Weights
+    keep: list
+    x: "object"
+    kv_pool: "object"
+    n_pages: int
+
+
+class Layer:
+    """One decoder layer's context on one GPU."""
+
+    def __init__(self, shape, device: int = 0, max_positions: int = 0):
+        import torch
+        self.torch = torch
+        self.lib = raw()
+        self.shape = shape
+        self.device = device
+        cfg = LayerCfg(shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                       shape.page_size, shape.rms_eps, shape.rope_theta, max_positions)
+        h = C.c_void_p()
+        rc = self.lib.bs_create(C.byref(cfg), device, C.byref(h))
+        if rc != 0:
+            raise BlendStepError(rc, (self.lib.bs_last_error(None) or b"").decode())
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.bs_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != 0:
+            raise BlendStepError(rc, (self.lib.bs_last_error(self.h) or b"").decode())
+
+    def _stream(self, stream=None):
+        s = stream if stream is not None else self.torch.cuda.current_stream(self.device)
+        return C.c_void_p(s.cuda_stream)
+
+    # -- device memory ------------------------------------------------------------
+    def _bf16(self, a: np.ndarray, transpose: bool = False):
+        t = self.torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda:%d" % self.device)
+        if transpose:
+            t = t.t()
+        return t.to(self.torch.bfloat16).contiguous()
+
+    def _bits(self, a: np.ndarray):
+        t = self.torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to("cuda:%d" % self.device)
+        return t.view(self.torch.bfloat16)
+
+    def upload_weights(self, t) -> tuple:
+        w_qkv = self._bf16(t.w_qkv, True)
+        w_o = self._bf16(t.w_o, True)
+        w_gu = self.torch.cat([self._bf16(t.w_gate, True), self._bf16(t.w_up, True)], dim=0).contiguous()
+        w_down = self._bf16(t.w_down, True)
+        g1, g2 = self._bf16(t.g_attn), self._bf16(t.g_ffn)
+        keep = [w_qkv, w_o, w_gu, w_down, g1, g2]
+        w = Weights(*[C.c_void_p(k.data_ptr()) for k in keep])
+        return w, keep
+
+    def pack_pool(self, k_bits: np.ndarray, v_bits: np.ndarray):
+        n_pages = k_bits.shape[0]
+        pool = self.torch.empty(n_pages * self.page_bytes() // 2, dtype=self.torch.bfloat16,
+                                device="cuda:%d" % self.device)
+        k, v = self._bits(k_bits), self._bits(v_bits)
+        self._check(self.lib.bs_kv_pack(self.h, C.c_void_p(k.data_ptr()), C.c_void_p(v.data_ptr()),
+                                        C.c_void_p(pool.data_ptr()), n_pages, self._stream()))
+        self.torch.cuda.current_stream(self.device).synchronize()
+        return pool
+
+    def unpack_pool(self, pool, n_pages: int):
+        s = self.shape
+        shp = (n_pages, s.page_size, s.n_kv_heads, s.head_dim)
+        k = self.torch.empty(shp, dtype=self.torch.bfloat16, device=pool.device)
+        v = self.torch.empty(shp, dtype=self.torch.bfloat16, device=pool.device)
+        self._check(self.lib.bs_kv_unpack(self.h, C.c_void_p(pool.data_ptr()), C.c_void_p(k.data_ptr()),
+                                          C.c_void_p(v.data_ptr()), n_pages, self._stream()))
+        self.torch.cuda.current_stream(self.device).synchronize()
+        return k, v
+
+    def upload(self, t, batch) -> DeviceState:
+        w, keep = self.upload_weights(t)
+        x = self._bf16(t.x)
+        pool = self.pack_pool(t.k_pool, t.v_pool)
+        return DeviceState(w, keep, x, pool, int(t.k_pool.shape[0]))
+
+    def page_bytes(self) -> int:
+        return int(self.lib.bs_kv_page_bytes(self.h))
+
+    # -- calls ----------------------------------------------------------------------
+    def blend_step(self, dev: DeviceState, batch, flags: int = 0, stream=None, y=None, desc=None):
+        d, keep = desc if desc is not None else marshal_batch(batch)
+        if y is None:
+            y = self.torch.empty_like(dev.x)
+        self._check(self.lib.bs_blend_step(self.h, C.byref(dev.weights), C.byref(d), C.c_void_p(dev.x.data_ptr()),
+                                           C.c_void_p(y.data_ptr()), C.c_void_p(dev.kv_pool.data_ptr()),
+                                           dev.n_pages, self._stream(stream), flags))
+        return y
+
+    def attention(self, batch, q, kv_pool, n_pages: int, flags: int = 0, stream=None):
+        d, keep = marshal_batch(batch)
+        out = self.torch.zeros_like(q)
+        self._check(self.lib.bs_attention(self.h, C.byref(d), C.c_void_p(q.data_ptr()), C.c_void_p(out.data_ptr()),
+                                          C.c_void_p(kv_pool.data_ptr()), n_pages, self._stream(stream), flags))
+        return out
+
+    def gemm_nt(self, a, b, stream=None):
+        m, k = a.shape
+        n = b.shape[0]
+        out = self.torch.empty((m, n), dtype=self.torch.bfloat16, device=a.device)
+        self._check(self.lib.bs_gemm_nt(self.h, C.c_void_p(a.data_ptr()), C.c_void_p(b.data_ptr()),
+                                        C.c_void_p(out.data_ptr()), m, n, k, self._stream(stream)))
+        return out
+
+    def validate(self, batch, n_pages: Optional[int] = None) -> int:
+        d, keep = marshal_batch(batch)
+        return int(self.lib.bs_validate_batch(self.h, C.byref(d), batch.n_pages if n_pages is None else n_pages))
+
+    def last_error(self) -> str:
+        return (self.lib.bs_last_error(self.h) or b"").decode()
+
+    def resolve_rows(self, batch):
+        d, keep = marshal_batch(batch)
+        pg = np.zeros(max(1, batch.n_rows), dtype=np.int32)
+        sl = np.zeros(max(1, batch.n_rows), dtype=np.int32)
+        self._check(self.lib.bs_resolve_rows(self.h, C.byref(d), _ptr(pg), _ptr(sl)))
+        return pg[:batch.n_rows], sl[:batch.n_rows]
+
+    def set_chunk_pages(self, pages: int):
+        self._check(self.lib.bs_set_chunk_pages(self.h, pages))
+
+    def profile(self, on: bool):
+        self._check(self.lib.bs_profile_enable(self.h, 1 if on else 0))
+        self._check(self.lib.bs_profile_reset(self.h))
+
+    def profile_read(self):
+        out = {}
+        for i, name in enumerate(K_NAMES):
+            ms, n = C.c_double(), C.c_int64()
+            self._check(self.lib.bs_profile_read(self.h, i, C.byref(ms), C.byref(n)))
+            out[name] = (ms.value, n.value)
+        return out
+
+
+class _Api:
+    Layer = Layer
+    BlendStepError = BlendStepError
+    FLAG_SERIAL = FLAG_SERIAL
+    FLAG_OVERLAP = FLAG_OVERLAP
+    K_NAMES = K_NAMES
+    marshal_batch = staticmethod(marshal_batch)
+    raw = staticmethod(raw)
+
+
+def load():
+    raw()
+    return _Api

@@ -1,0 +1,743 @@
+// C ABI of the blended decoder-layer step: context, descriptor validation, the
+// per-step plan (row tables, decode-attention work items, partial-state slots)
+// and the kernel schedule.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/blendstep.h"
+#include "attn.hpp"
+#include "gemm.hpp"
+#include "misc.hpp"
+
+using namespace bs;
+
+namespace {
+
+constexpr int RING = 4;
+std::string g_create_error;
+
+struct Plan {
+  int n_seq = 0, n_prefill = 0, n_rows = 0, n_decode = 0, n_prefill_rows = 0;
+  long off_row_start = 0, off_kv_len = 0, off_page_start = 0, off_row_pos = 0, off_row_page = 0, off_row_slot = 0,
+       off_part_start = 0, off_pf_work = 0, off_items = 0, off_pages = 0, total_ints = 0;
+  long total_node_pages = 0, n_slots = 0;
+  int n_pf_work = 0;
+  int item_base[3] = {0, 0, 0}, item_count[3] = {0, 0, 0};  // classes of 4, 2, 1 blocks of 16 query rows
+};
+
+}  // namespace
+
+struct bs_ctx {
+  bs_layer_cfg cfg;
+  int device = 0;
+  std::string err;
+  float *rope_cos = nullptr, *rope_sin = nullptr;
+  // activations workspace
+  int cap_rows = 0, ss2_parts = 0;
+  uint16_t *xg = nullptr, *qbuf = nullptr, *attn = nullptr, *x1 = nullptr, *xg2 = nullptr, *act = nullptr;
+  float *ss1 = nullptr, *ss2 = nullptr;
+  long cap_slots = 0;
+  float *part_acc = nullptr, *part_m = nullptr, *part_l = nullptr;
+  // descriptor blob: pinned host ring and one device copy
+  long cap_blob = 0;
+  int32_t *d_blob = nullptr;
+  int32_t *h_blob[RING] = {nullptr, nullptr, nullptr, nullptr};
+  long h_cap[RING] = {0, 0, 0, 0};
+  hipEvent_t h_ev[RING];
+  bool h_ev_live[RING] = {false, false, false, false};
+  int ring_pos = 0;
+  // host scratch reused across calls
+  std::vector<int32_t> refcount, path_pages, path_chunks, members, blob;
+  std::vector<DecodeItem> items[3];
+  std::vector<int32_t> pf_work;
+  // overlap
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  // tunables
+  int chunk_pages = 32;
+  // profiling
+  bool prof = false;
+  struct Span { hipEvent_t a, b; };
+  std::vector<Span> spans[BS_K_COUNT];
+  std::vector<hipEvent_t> free_events;
+  double prof_ms[BS_K_COUNT] = {0};
+  int64_t prof_n[BS_K_COUNT] = {0};
+};
+
+namespace {
+
+int fail(bs_ctx *ctx, int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf; else g_create_error = buf;
+  return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                         \
+  do {                                                                                             \
+    hipError_t e_ = (expr);                                                                        \
+    if (e_ != hipSuccess) return fail(ctx, BS_EHIP, "%s: %s", #expr, hipGetErrorString(e_));        \
+  } while (0)
+
+template <class T>
+int dev_alloc(bs_ctx *ctx, T **p, size_t count) {
+  if (*p) { hipError_t e = hipFree(*p); *p = nullptr; if (e != hipSuccess) return fail(ctx, BS_EHIP, "hipFree: %s", hipGetErrorString(e)); }
+  if (count == 0) return BS_OK;
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(p), count * sizeof(T));
+  if (e != hipSuccess) { *p = nullptr; return fail(ctx, BS_ENOMEM, "hipMalloc of %zu bytes: %s", count * sizeof(T), hipGetErrorString(e)); }
+  return BS_OK;
+}
+
+int ensure_rows(bs_ctx *c, int rows) {
+  if (rows <= c->cap_rows) return BS_OK;
+  const int cap = std::max(rows, 256);
+  const bs_layer_cfg &g = c->cfg;
+  const size_t hd = (size_t)g.n_q_heads * g.head_dim;
+  int rc;
+  c->cap_rows = 0;
+  if ((rc = dev_alloc(c, &c->xg, (size_t)cap * g.d_model))) return rc;
+  if ((rc = dev_alloc(c, &c->qbuf, (size_t)cap * hd))) return rc;
+  if ((rc = dev_alloc(c, &c->attn, (size_t)cap * hd))) return rc;
+  if ((rc = dev_alloc(c, &c->x1, (size_t)cap * g.d_model))) return rc;
+  if ((rc = dev_alloc(c, &c->xg2, (size_t)cap * g.d_model))) return rc;
+  if ((rc = dev_alloc(c, &c->act, (size_t)cap * g.d_ffn))) return rc;
+  if ((rc = dev_alloc(c, &c->ss1, (size_t)cap))) return rc;
+  c->ss2_parts = ((g.d_model + 255) / 256) * 4;  // covers both tile shapes of the projection
+  if ((rc = dev_alloc(c, &c->ss2, (size_t)cap * c->ss2_parts))) return rc;
+  c->cap_rows = cap;
+  return BS_OK;
+}
+
+int ensure_slots(bs_ctx *c, long slots) {
+  if (slots <= c->cap_slots) return BS_OK;
+  const long cap = slots + slots / 4 + 64;
+  const size_t hq = c->cfg.n_q_heads;
+  int rc;
+  c->cap_slots = 0;
+  if ((rc = dev_alloc(c, &c->part_acc, (size_t)cap * hq * c->cfg.head_dim))) return rc;
+  if ((rc = dev_alloc(c, &c->part_m, (size_t)cap * hq))) return rc;
+  if ((rc = dev_alloc(c, &c->part_l, (size_t)cap * hq))) return rc;
+  c->cap_slots = cap;
+  return BS_OK;
+}
+
+int ensure_blob(bs_ctx *c, long ints, int slot) {
+  if (ints > c->cap_blob) {
+    const long cap = ints + ints / 4 + 1024;
+    c->cap_blob = 0;
+    int rc = dev_alloc(c, &c->d_blob, (size_t)cap);
+    if (rc) return rc;
+    c->cap_blob = cap;
+  }
+  if (ints > c->h_cap[slot]) {
+    const long cap = ints + ints / 4 + 1024;
+    if (c->h_blob[slot]) { HIP_TRY(c, hipHostFree(c->h_blob[slot])); c->h_blob[slot] = nullptr; c->h_cap[slot] = 0; }
+    hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&c->h_blob[slot]), (size_t)cap * sizeof(int32_t), hipHostMallocDefault);
+    if (e != hipSuccess) return fail(c, BS_ENOMEM, "hipHostMalloc: %s", hipGetErrorString(e));
+    c->h_cap[slot] = cap;
+  }
+  return BS_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// descriptor validation (host only)
+// ---------------------------------------------------------------------------------
+int validate(bs_ctx *c, const bs_batch *b, int64_t n_pages) {
+  if (!b) return fail(c, BS_EINVAL, "batch is NULL");
+  const int ps = c->cfg.page_size;
+  if (b->n_seq < 0 || b->n_prefill < 0 || b->n_prefill > b->n_seq || b->n_rows < 0)
+    return fail(c, BS_EINVAL, "bad counts: n_seq=%d n_prefill=%d n_rows=%d", b->n_seq, b->n_prefill, b->n_rows);
+  if (n_pages < 0 || n_pages > (int64_t)0x7fffffff) return fail(c, BS_EINVAL, "n_pages=%lld out of range", (long long)n_pages);
+  if (b->n_seq == 0) {
+    if (b->n_rows != 0) return fail(c, BS_EINVAL, "n_rows=%d with no sequences", b->n_rows);
+    return BS_OK;
+  }
+  if (!b->row_start || !b->kv_len || !b->page_start || (!b->page_ids && b->page_start[b->n_seq] > 0))
+    return fail(c, BS_EINVAL, "a required array is NULL");
+  if (b->row_start[0] != 0 || b->page_start[0] != 0) return fail(c, BS_EINVAL, "CSR arrays must start at 0");
+  for (int s = 0; s < b->n_seq; ++s) {
+    const int q = b->row_start[s + 1] - b->row_start[s];
+    if (q < 1) return fail(c, BS_EINVAL, "sequence %d has %d rows", s, q);
+    if (s >= b->n_prefill && q != 1) return fail(c, BS_EINVAL, "decode sequence %d has %d rows (must be 1)", s, q);
+    if (b->kv_len[s] < q) return fail(c, BS_EINVAL, "sequence %d: kv_len %d < its %d rows", s, b->kv_len[s], q);
+    if (b->kv_len[s] > c->cfg.max_positions)
+      return fail(c, BS_EINVAL, "sequence %d: kv_len %d exceeds max_positions %d", s, b->kv_len[s], c->cfg.max_positions);
+    const int np = b->page_start[s + 1] - b->page_start[s];
+    if (np < 0) return fail(c, BS_EINVAL, "page_start not monotone at sequence %d", s);
+    if ((int64_t)np * ps < b->kv_len[s])
+      return fail(c, BS_EINVAL, "sequence %d: kv_len %d exceeds its %d pages", s, b->kv_len[s], np);
+  }
+  if (b->row_start[b->n_seq] != b->n_rows)
+    return fail(c, BS_EINVAL, "row_start ends at %d, n_rows is %d", b->row_start[b->n_seq], b->n_rows);
+  const int n_tab = b->page_start[b->n_seq];
+  c->refcount.assign((size_t)n_pages, 0);
+  for (int i = 0; i < n_tab; ++i) {
+    const int p = b->page_ids[i];
+    if (p < 0 || p >= n_pages) return fail(c, BS_EINVAL, "page_ids[%d]=%d outside the pool of %lld pages", i, p, (long long)n_pages);
+    ++c->refcount[p];
+  }
+  // prefix nodes
+  const int nn = b->n_nodes;
+  if (nn < 0) return fail(c, BS_EINVAL, "n_nodes=%d", nn);
+  c->path_pages.assign((size_t)nn, 0);
+  c->members.assign((size_t)nn, 0);
+  if (nn > 0) {
+    if (!b->node_parent || !b->node_page_start || !b->node_seq_first || !b->node_seq_count || !b->seq_leaf_node)
+      return fail(c, BS_EINVAL, "a node array is NULL");
+    if (b->node_page_start[0] != 0) return fail(c, BS_EINVAL, "node_page_start must start at 0");
+    for (int n = 0; n < nn; ++n) {
+      const int par = b->node_parent[n];
+      if (par < -1 || par >= n) return fail(c, BS_EINVAL, "node %d: parent %d breaks DFS pre-order", n, par);
+      const int np = b->node_page_start[n + 1] - b->node_page_start[n];
+      if (np < 0) return fail(c, BS_EINVAL, "node_page_start not monotone at node %d", n);
+      const int f = b->node_seq_first[n], cnt = b->node_seq_count[n];
+      if (cnt < 0) return fail(c, BS_EINVAL, "node %d: negative member count", n);
+      if (cnt > 0 && (f < b->n_prefill || f + cnt > b->n_seq))
+        return fail(c, BS_EINVAL, "node %d: members [%d,%d) are not decode sequences", n, f, f + cnt);
+      if (par >= 0 && cnt > 0) {
+        const int pf = b->node_seq_first[par], pc = b->node_seq_count[par];
+        if (f < pf || f + cnt > pf + pc) return fail(c, BS_EINVAL, "node %d: members not inside its parent's run", n);
+      }
+      c->path_pages[n] = np + (par >= 0 ? c->path_pages[par] : 0);
+      for (int i = b->node_page_start[n]; i < b->node_page_start[n + 1]; ++i) {
+        const int p = b->node_page_ids[i];
+        if (p < 0 || p >= n_pages) return fail(c, BS_EINVAL, "node_page_ids[%d]=%d outside the pool", i, p);
+        c->refcount[p] += 2;  // node pages are never writable, even with a single member
+      }
+    }
+  }
+  for (int s = 0; s < b->n_seq; ++s) {
+    const int leaf = b->seq_leaf_node ? b->seq_leaf_node[s] : -1;
+    if (leaf < -1 || leaf >= nn) return fail(c, BS_EINVAL, "sequence %d: leaf node %d out of range", s, leaf);
+    const int q = b->row_start[s + 1] - b->row_start[s];
+    if (leaf >= 0) {
+      if (s < b->n_prefill) return fail(c, BS_EINVAL, "prefill segment %d cannot be a node member", s);
+      const int shared = c->path_pages[leaf];
+      if ((int64_t)shared * ps > b->kv_len[s] - q)
+        return fail(c, BS_EINVAL, "sequence %d: %d shared pages leave no private slot for its new token", s, shared);
+      // the path's pages must open the sequence's table, root first
+      int node = leaf, end = shared;
+      while (node >= 0) {
+        const int np = b->node_page_start[node + 1] - b->node_page_start[node];
+        const int f = b->node_seq_first[node], cnt = b->node_seq_count[node];
+        if (s < f || s >= f + cnt) return fail(c, BS_EINVAL, "sequence %d lies outside the member run of node %d", s, node);
+        ++c->members[node];
+        const int32_t *tab = b->page_ids + b->page_start[s] + (end - np);
+        if (np > 0 && std::memcmp(tab, b->node_page_ids + b->node_page_start[node], (size_t)np * sizeof(int32_t)) != 0)
+          return fail(c, BS_EINVAL, "sequence %d: page table does not carry the pages of node %d", s, node);
+        end -= np;
+        node = b->node_parent[node];
+      }
+    }
+    // pages this step writes must be referenced exactly once
+    const int first = (b->kv_len[s] - q) / ps, last = (b->kv_len[s] - 1) / ps;
+    for (int pg = first; pg <= last; ++pg) {
+      const int p = b->page_ids[b->page_start[s] + pg];
+      if (c->refcount[p] != 1)
+        return fail(c, BS_EINVAL, "sequence %d appends into page %d, which is referenced more than once", s, p);
+    }
+  }
+  for (int n = 0; n < nn; ++n)
+    if (c->members[n] != b->node_seq_count[n])
+      return fail(c, BS_EINVAL, "node %d: %d sequences name it, its member run has %d", n, c->members[n], b->node_seq_count[n]);
+  return BS_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// plan: everything the kernels need, packed in one int32 blob
+// ---------------------------------------------------------------------------------
+int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
+  const int ps = c->cfg.page_size;
+  const int grp = c->cfg.n_q_heads / c->cfg.n_kv_heads;
+  const int ch = c->chunk_pages;
+  const int nn = b->n_nodes;
+  p.n_seq = b->n_seq; p.n_prefill = b->n_prefill; p.n_rows = b->n_rows; p.n_decode = b->n_seq - b->n_prefill;
+  p.n_prefill_rows = b->n_seq ? b->row_start[b->n_prefill] : 0;
+  p.total_node_pages = nn > 0 ? b->node_page_start[nn] : 0;
+  const int n_tab = b->n_seq ? b->page_start[b->n_seq] : 0;
+
+  // chunk counts along each node's root path (path_pages was filled by validate)
+  c->path_chunks.assign((size_t)nn, 0);
+  for (int i = 0; i < 3; ++i) c->items[i].clear();
+  const int max_members = std::max(1, 64 / grp);
+  for (int n = 0; n < nn; ++n) {
+    const int par = b->node_parent[n];
+    const int np = b->node_page_start[n + 1] - b->node_page_start[n];
+    const int above = par >= 0 ? c->path_chunks[par] : 0;
+    const int nch = (np + ch - 1) / ch;
+    c->path_chunks[n] = above + nch;
+    const int cnt = b->node_seq_count[n];
+    if (cnt <= 0 || np <= 0) continue;
+    const int n_groups = (cnt + max_members - 1) / max_members;
+    for (int g = 0; g < n_groups; ++g) {
+      const int lo = (int)((long)cnt * g / n_groups), hi = (int)((long)cnt * (g + 1) / n_groups);
+      const int rows = (hi - lo) * grp;
+      const int cls = rows > 32 ? 0 : (rows > 16 ? 1 : 2);
+      for (int k = 0; k < nch; ++k) {
+        DecodeItem it{};
+        it.page_off = b->node_page_start[n] + k * ch;
+        it.n_tokens = std::min(ch, np - k * ch) * ps;
+        it.seq_first = b->node_seq_first[n] + lo;
+        it.n_members = hi - lo;
+        it.slot_off = above + k;
+        c->items[cls].push_back(it);
+      }
+    }
+  }
+  // private tails and partial-state slots
+  std::vector<int32_t> &blob = c->blob;
+  p.off_row_start = 0;
+  p.off_kv_len = p.off_row_start + b->n_seq + 1;
+  p.off_page_start = p.off_kv_len + b->n_seq;
+  p.off_part_start = p.off_page_start + b->n_seq + 1;
+  p.off_row_pos = p.off_part_start + b->n_seq + 1;
+  p.off_row_page = p.off_row_pos + b->n_rows;
+  p.off_row_slot = p.off_row_page + b->n_rows;
+  p.off_pf_work = p.off_row_slot + b->n_rows;
+  blob.assign((size_t)p.off_pf_work, 0);
+  if (b->n_seq) {
+    std::memcpy(&blob[p.off_row_start], b->row_start, sizeof(int32_t) * (b->n_seq + 1));
+    std::memcpy(&blob[p.off_kv_len], b->kv_len, sizeof(int32_t) * b->n_seq);
+    std::memcpy(&blob[p.off_page_start], b->page_start, sizeof(int32_t) * (b->n_seq + 1));
+  }
+  int32_t *part_start = &blob[p.off_part_start];
+  part_start[0] = 0;
+  const int tail_cls = grp > 16 ? 0 : 2;
+  for (int s = 0; s < b->n_seq; ++s) {
+    int slots = 0;
+    if (s >= b->n_prefill) {
+      const int leaf = (nn > 0) ? b->seq_leaf_node[s] : -1;
+      const int shared = leaf >= 0 ? c->path_pages[leaf] : 0;
+      const int above = leaf >= 0 ? c->path_chunks[leaf] : 0;
+      const int tail_tok = b->kv_len[s] - shared * ps;  // >= 1 by validation
+      const int tail_pg = (tail_tok + ps - 1) / ps;
+      const int nch = (tail_pg + ch - 1) / ch;
+      for (int k = 0; k < nch; ++k) {
+        DecodeItem it{};
+        it.page_off = (int32_t)(p.total_node_pages + b->page_start[s] + shared + k * ch);
+        it.n_tokens = std::min(ch * ps, tail_tok - k * ch * ps);
+        it.seq_first = s;
+        it.n_members = 1;
+        it.slot_off = above + k;
+        c->items[tail_cls].push_back(it);
+      }
+      slots = above + nch;
+    }
+    part_start[s + 1] = part_start[s] + slots;
+  }
+  p.n_slots = part_start[b->n_seq];
+  if (with_rows) {
+    for (int s = 0; s < b->n_seq; ++s) {
+      const int r0 = b->row_start[s], q = b->row_start[s + 1] - r0, first = b->kv_len[s] - q;
+      for (int j = 0; j < q; ++j) {
+        const int pos = first + j;
+        blob[p.off_row_pos + r0 + j] = pos;
+        blob[p.off_row_page + r0 + j] = b->page_ids[b->page_start[s] + pos / ps];
+        blob[p.off_row_slot + r0 + j] = pos % ps;
+      }
+    }
+  }
+  // prefill work: (sequence, block of 32 query rows), longest contexts first
+  c->pf_work.clear();
+  std::vector<std::pair<int, std::pair<int, int>>> order;
+  for (int s = 0; s < b->n_prefill; ++s) {
+    const int q = b->row_start[s + 1] - b->row_start[s];
+    for (int k = 0; k * 32 < q; ++k) order.push_back({-(b->kv_len[s] - q + std::min(q, k * 32 + 32)), {s, k}});
+  }
+  std::stable_sort(order.begin(), order.end(), [](const auto &x, const auto &y) { return x.first < y.first; });
+  p.n_pf_work = (int)order.size();
+  p.off_items = p.off_pf_work + 2L * p.n_pf_work;
+  long n_items = 0;
+  for (int i = 0; i < 3; ++i) { p.item_base[i] = (int)n_items; p.item_count[i] = (int)c->items[i].size(); n_items += p.item_count[i]; }
+  p.off_pages = p.off_items + 8 * n_items;
+  p.total_ints = p.off_pages + p.total_node_pages + n_tab;
+  blob.resize((size_t)p.total_ints);
+  for (int i = 0; i < p.n_pf_work; ++i) {
+    blob[p.off_pf_work + 2 * i] = order[i].second.first;
+    blob[p.off_pf_work + 2 * i + 1] = order[i].second.second;
+  }
+  for (int i = 0; i < 3; ++i)
+    if (p.item_count[i])
+      std::memcpy(&blob[p.off_items + 8L * p.item_base[i]], c->items[i].data(), sizeof(DecodeItem) * p.item_count[i]);
+  if (p.total_node_pages) std::memcpy(&blob[p.off_pages], b->node_page_ids, sizeof(int32_t) * p.total_node_pages);
+  if (n_tab) std::memcpy(&blob[p.off_pages + p.total_node_pages], b->page_ids, sizeof(int32_t) * n_tab);
+  return BS_OK;
+}
+
+int upload_plan(bs_ctx *c, const Plan &p, hipStream_t stream) {
+  const int slot = c->ring_pos;
+  c->ring_pos = (c->ring_pos + 1) % RING;
+  if (c->h_ev_live[slot]) HIP_TRY(c, hipEventSynchronize(c->h_ev[slot]));
+  int rc = ensure_blob(c, p.total_ints, slot);
+  if (rc) return rc;
+  if (p.total_ints == 0) return BS_OK;
+  std::memcpy(c->h_blob[slot], c->blob.data(), sizeof(int32_t) * p.total_ints);
+  HIP_TRY(c, hipMemcpyAsync(c->d_blob, c->h_blob[slot], sizeof(int32_t) * p.total_ints, hipMemcpyHostToDevice, stream));
+  HIP_TRY(c, hipEventRecord(c->h_ev[slot], stream));
+  c->h_ev_live[slot] = true;
+  return BS_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// profiling spans
+// ---------------------------------------------------------------------------------
+int span_begin(bs_ctx *c, int which, hipStream_t s, bs_ctx::Span &sp) {
+  if (!c->prof) return BS_OK;
+  for (hipEvent_t *e : {&sp.a, &sp.b}) {
+    if (!c->free_events.empty()) { *e = c->free_events.back(); c->free_events.pop_back(); }
+    else HIP_TRY(c, hipEventCreate(e));
+  }
+  (void)which;
+  HIP_TRY(c, hipEventRecord(sp.a, s));
+  return BS_OK;
+}
+int span_end(bs_ctx *c, int which, hipStream_t s, bs_ctx::Span &sp) {
+  if (!c->prof) return BS_OK;
+  HIP_TRY(c, hipEventRecord(sp.b, s));
+  c->spans[which].push_back(sp);
+  return BS_OK;
+}
+
+#define SPAN(ctx, which, stream, body)                       \
+  do {                                                       \
+    bs_ctx::Span sp_{};                                      \
+    int rc_ = span_begin(ctx, which, stream, sp_);           \
+    if (rc_) return rc_;                                     \
+    body;                                                    \
+    rc_ = span_end(ctx, which, stream, sp_);                 \
+    if (rc_) return rc_;                                     \
+  } while (0)
+
+AttnShape attn_shape(const bs_ctx *c) {
+  AttnShape s;
+  s.n_q_heads = c->cfg.n_q_heads; s.n_kv_heads = c->cfg.n_kv_heads; s.head_dim = c->cfg.head_dim; s.page_size = c->cfg.page_size;
+  s.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)c->cfg.head_dim));
+  return s;
+}
+
+int run_prefill_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, const uint16_t *pool, hipStream_t st) {
+  if (p.n_pf_work == 0) return BS_OK;
+  PrefillArgs a;
+  a.s = attn_shape(c);
+  a.work = c->d_blob + p.off_pf_work; a.n_work = p.n_pf_work;
+  a.row_start = c->d_blob + p.off_row_start; a.kv_len = c->d_blob + p.off_kv_len;
+  a.page_start = c->d_blob + p.off_page_start; a.page_ids = c->d_blob + p.off_pages + p.total_node_pages;
+  a.q = q; a.kv_pool = pool; a.out = out;
+  SPAN(c, BS_K_ATTN_PREFILL, st, HIP_TRY(c, launch_prefill_attn(a, st)));
+  return BS_OK;
+}
+
+int run_decode_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, const uint16_t *pool, hipStream_t st) {
+  if (p.n_decode == 0) return BS_OK;
+  DecodeArgs a;
+  a.s = attn_shape(c);
+  a.items = reinterpret_cast<const DecodeItem *>(c->d_blob + p.off_items);
+  a.item_pages = c->d_blob + p.off_pages;
+  a.row_start = c->d_blob + p.off_row_start; a.part_start = c->d_blob + p.off_part_start;
+  a.q = q; a.kv_pool = pool;
+  a.part_acc = c->part_acc; a.part_m = c->part_m; a.part_l = c->part_l;
+  static const int nqb_of[3] = {4, 2, 1};
+  {
+    bs_ctx::Span sp{};
+    int rc = span_begin(c, BS_K_ATTN_DECODE, st, sp);
+    if (rc) return rc;
+    for (int i = 0; i < 3; ++i)
+      if (p.item_count[i]) HIP_TRY(c, launch_decode_attn(a, p.item_base[i], p.item_count[i], nqb_of[i], st));
+    rc = span_end(c, BS_K_ATTN_DECODE, st, sp);
+    if (rc) return rc;
+  }
+  MergeArgs m;
+  m.s = a.s; m.n_prefill = p.n_prefill; m.n_decode = p.n_decode;
+  m.row_start = a.row_start; m.part_start = a.part_start;
+  m.part_acc = c->part_acc; m.part_m = c->part_m; m.part_l = c->part_l; m.out = out;
+  SPAN(c, BS_K_ATTN_MERGE, st, HIP_TRY(c, launch_decode_merge(m, st)));
+  return BS_OK;
+}
+
+// output projection, FFN and both residuals for rows [r0, r1)
+int run_tail(bs_ctx *c, const bs_weights *w, const uint16_t *x, uint16_t *y, int r0, int r1, hipStream_t st) {
+  const int rows = r1 - r0;
+  if (rows <= 0) return BS_OK;
+  const bs_layer_cfg &g = c->cfg;
+  const int hd = g.n_q_heads * g.head_dim, d = g.d_model, f = g.d_ffn;
+  const int parts = gemm_ss_parts(d, EPI_RESID_NORM, rows, g.head_dim);
+  GemmArgs o{};
+  o.A = c->attn + (size_t)r0 * hd; o.lda = hd; o.B = (const uint16_t *)w->w_o; o.ldb = hd;
+  o.M = rows; o.N = d; o.K = hd;
+  o.C = c->x1 + (size_t)r0 * d; o.ldc = d; o.resid = x + (size_t)r0 * d; o.ldr = d;
+  o.gain = (const uint16_t *)w->g_ffn; o.C_gain = c->xg2 + (size_t)r0 * d;
+  o.ss_out = c->ss2 + r0; o.ss_stride = c->cap_rows;
+  SPAN(c, BS_K_GEMM_O, st, HIP_TRY(c, launch_gemm(o, EPI_RESID_NORM, g.head_dim, st)));
+  GemmArgs u{};
+  u.A = c->xg2 + (size_t)r0 * d; u.lda = d; u.B = (const uint16_t *)w->w_gate_up; u.ldb = d;
+  u.M = rows; u.N = f; u.K = d;
+  u.C = c->act + (size_t)r0 * f; u.ldc = f;
+  u.ss_part = c->ss2 + r0; u.n_ss_part = parts; u.ss_stride = c->cap_rows; u.norm_dim = (float)d; u.eps = g.rms_eps;
+  SPAN(c, BS_K_GEMM_GATE_UP, st, HIP_TRY(c, launch_gemm(u, EPI_SWIGLU, g.head_dim, st)));
+  GemmArgs dn{};
+  dn.A = c->act + (size_t)r0 * f; dn.lda = f; dn.B = (const uint16_t *)w->w_down; dn.ldb = f;
+  dn.M = rows; dn.N = d; dn.K = f;
+  dn.C = y + (size_t)r0 * d; dn.ldc = d; dn.resid = c->x1 + (size_t)r0 * d; dn.ldr = d;
+  SPAN(c, BS_K_GEMM_DOWN, st, HIP_TRY(c, launch_gemm(dn, EPI_RESID, g.head_dim, st)));
+  return BS_OK;
+}
+
+int check_cfg(const bs_layer_cfg *g) {
+  if (!g) return fail(nullptr, BS_EINVAL, "cfg is NULL");
+  if (g->page_size != 16) return fail(nullptr, BS_EUNSUPPORTED, "page_size %d (only 16)", g->page_size);
+  if (g->head_dim != 64 && g->head_dim != 128) return fail(nullptr, BS_EUNSUPPORTED, "head_dim %d (64 or 128)", g->head_dim);
+  if (g->n_kv_heads < 1 || g->n_q_heads < 1 || g->n_q_heads % g->n_kv_heads || g->n_q_heads / g->n_kv_heads > 16)
+    return fail(nullptr, BS_EUNSUPPORTED, "heads %d/%d", g->n_q_heads, g->n_kv_heads);
+  if (g->d_model < 8 || g->d_model % 8 || g->d_ffn < 8 || g->d_ffn % 8)
+    return fail(nullptr, BS_EUNSUPPORTED, "d_model %d and d_ffn %d must be multiples of 8", g->d_model, g->d_ffn);
+  if (!(g->rms_eps >= 0.f) || !(g->rope_theta > 0.f)) return fail(nullptr, BS_EINVAL, "bad rms_eps or rope_theta");
+  return BS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bs_create(const bs_layer_cfg *cfg, int device, bs_ctx **out) {
+  if (!out) return fail(nullptr, BS_EINVAL, "out is NULL");
+  *out = nullptr;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  int n_dev = 0;
+  if (device != BS_DEVICE_NONE && (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev))
+    return fail(nullptr, BS_EHIP, "device %d not available (%d visible)", device, n_dev);
+  bs_ctx *c = new (std::nothrow) bs_ctx();
+  if (!c) return fail(nullptr, BS_ENOMEM, "out of host memory");
+  c->cfg = *cfg;
+  if (c->cfg.max_positions <= 0) c->cfg.max_positions = 16384;
+  c->device = device;
+  if (device == BS_DEVICE_NONE) { *out = c; return BS_OK; }  // host-only: validation and indexing
+  auto bail = [&](int code) { g_create_error = c->err; bs_destroy(c); return code; };
+  if (hipSetDevice(device) != hipSuccess) { c->err = "hipSetDevice failed"; return bail(BS_EHIP); }
+  const int half = c->cfg.head_dim / 2;
+  if ((rc = dev_alloc(c, &c->rope_cos, (size_t)c->cfg.max_positions * half))) return bail(rc);
+  if ((rc = dev_alloc(c, &c->rope_sin, (size_t)c->cfg.max_positions * half))) return bail(rc);
+  hipError_t e = launch_rope_table(c->rope_cos, c->rope_sin, c->cfg.max_positions, half, (double)c->cfg.rope_theta, nullptr);
+  if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+  if (e != hipSuccess) { c->err = std::string("rope table: ") + hipGetErrorString(e); return bail(BS_EHIP); }
+  for (int i = 0; i < RING; ++i)
+    if (hipEventCreateWithFlags(&c->h_ev[i], hipEventDisableTiming) != hipSuccess) { c->err = "hipEventCreate failed"; return bail(BS_EHIP); }
+  if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) { c->err = "side stream setup failed"; return bail(BS_EHIP); }
+  *out = c;
+  return BS_OK;
+}
+
+void bs_destroy(bs_ctx *c) {
+  if (!c) return;
+  if (c->device == BS_DEVICE_NONE) { delete c; return; }
+  (void)hipSetDevice(c->device);
+  (void)hipDeviceSynchronize();
+  for (void *p : {(void *)c->rope_cos, (void *)c->rope_sin, (void *)c->xg, (void *)c->qbuf, (void *)c->attn, (void *)c->x1,
+                  (void *)c->xg2, (void *)c->act, (void *)c->ss1, (void *)c->ss2, (void *)c->part_acc, (void *)c->part_m,
+                  (void *)c->part_l, (void *)c->d_blob})
+    if (p) (void)hipFree(p);
+  for (int i = 0; i < RING; ++i) {
+    if (c->h_blob[i]) (void)hipHostFree(c->h_blob[i]);
+    (void)hipEventDestroy(c->h_ev[i]);
+  }
+  if (c->side) (void)hipStreamDestroy(c->side);
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+  for (auto &v : c->spans) for (auto &s : v) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
+  for (auto e : c->free_events) (void)hipEventDestroy(e);
+  delete c;
+}
+
+const char *bs_last_error(const bs_ctx *c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+int64_t bs_kv_page_bytes(const bs_ctx *c) {
+  return c ? (int64_t)2 * c->cfg.n_kv_heads * c->cfg.page_size * c->cfg.head_dim * 2 : 0;
+}
+
+int bs_kv_pack(bs_ctx *c, const void *k, const void *v, void *pool, int64_t n_pages, void *stream) {
+  if (!c) return BS_EINVAL;
+  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
+  if (!k || !v || !pool || n_pages < 0) return fail(c, BS_EINVAL, "bs_kv_pack: bad argument");
+  HIP_TRY(c, launch_kv_pack((const uint16_t *)k, (const uint16_t *)v, (uint16_t *)pool, n_pages, c->cfg.n_kv_heads, c->cfg.head_dim, (hipStream_t)stream));
+  return BS_OK;
+}
+
+int bs_kv_unpack(bs_ctx *c, const void *pool, void *k, void *v, int64_t n_pages, void *stream) {
+  if (!c) return BS_EINVAL;
+  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
+  if (!k || !v || !pool || n_pages < 0) return fail(c, BS_EINVAL, "bs_kv_unpack: bad argument");
+  HIP_TRY(c, launch_kv_unpack((const uint16_t *)pool, (uint16_t *)k, (uint16_t *)v, n_pages, c->cfg.n_kv_heads, c->cfg.head_dim, (hipStream_t)stream));
+  return BS_OK;
+}
+
+int bs_validate_batch(bs_ctx *c, const bs_batch *b, int64_t n_pages) {
+  if (!c) return BS_EINVAL;
+  return validate(c, b, n_pages);
+}
+
+int bs_resolve_rows(bs_ctx *c, const bs_batch *b, int32_t *page_out, int32_t *slot_out) {
+  if (!c) return BS_EINVAL;
+  if (!b || !page_out || !slot_out) return fail(c, BS_EINVAL, "bs_resolve_rows: NULL argument");
+  int64_t max_page = 0;
+  for (int i = 0; b->n_seq > 0 && i < b->page_start[b->n_seq]; ++i) max_page = std::max<int64_t>(max_page, b->page_ids[i]);
+  for (int i = 0; b->n_nodes > 0 && i < b->node_page_start[b->n_nodes]; ++i) max_page = std::max<int64_t>(max_page, b->node_page_ids[i]);
+  int rc = validate(c, b, max_page + 1);
+  if (rc) return rc;
+  Plan p;
+  if ((rc = build_plan(c, b, p, true))) return rc;
+  for (int r = 0; r < b->n_rows; ++r) {
+    page_out[r] = c->blob[p.off_row_page + r];
+    slot_out[r] = c->blob[p.off_row_slot + r];
+  }
+  return BS_OK;
+}
+
+int bs_blend_step(bs_ctx *c, const bs_weights *w, const bs_batch *b, const void *x_, void *y_, void *pool_,
+                  int64_t n_pages, void *stream_, uint32_t flags) {
+  if (!c) return BS_EINVAL;
+  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
+  if (!w || !w->w_qkv || !w->w_o || !w->w_gate_up || !w->w_down || !w->g_attn || !w->g_ffn)
+    return fail(c, BS_EINVAL, "a weight pointer is NULL");
+  int rc = validate(c, b, n_pages);
+  if (rc) return rc;
+  if (b->n_rows == 0) return BS_OK;
+  if (!x_ || !y_ || !pool_ || x_ == y_) return fail(c, BS_EINVAL, "x, y, kv_pool must be distinct non-NULL device pointers");
+  HIP_TRY(c, hipSetDevice(c->device));
+  hipStream_t st = (hipStream_t)stream_;
+  const uint16_t *x = (const uint16_t *)x_;
+  uint16_t *y = (uint16_t *)y_, *pool = (uint16_t *)pool_;
+  Plan p;
+  if ((rc = build_plan(c, b, p, true))) return rc;
+  if ((rc = ensure_rows(c, p.n_rows))) return rc;
+  if ((rc = ensure_slots(c, p.n_slots))) return rc;
+  if ((rc = upload_plan(c, p, st))) return rc;
+
+  const bs_layer_cfg &g = c->cfg;
+  const int T = p.n_rows, d = g.d_model, hd = g.n_q_heads * g.head_dim;
+  SPAN(c, BS_K_PREP, st, HIP_TRY(c, launch_norm_prep(x, (const uint16_t *)w->g_attn, c->xg, c->ss1, T, d, st)));
+  GemmArgs q{};
+  q.A = c->xg; q.lda = d; q.B = (const uint16_t *)w->w_qkv; q.ldb = d;
+  q.M = T; q.N = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim; q.K = d;
+  q.ss_part = c->ss1; q.n_ss_part = 1; q.ss_stride = c->cap_rows; q.norm_dim = (float)d; q.eps = g.rms_eps;
+  q.n_q_heads = g.n_q_heads; q.n_kv_heads = g.n_kv_heads;
+  q.rope_cos = c->rope_cos; q.rope_sin = c->rope_sin;
+  q.row_pos = c->d_blob + p.off_row_pos; q.row_page = c->d_blob + p.off_row_page; q.row_slot = c->d_blob + p.off_row_slot;
+  q.q_out = c->qbuf; q.kv_pool = pool;
+  SPAN(c, BS_K_GEMM_QKV, st, HIP_TRY(c, launch_gemm(q, EPI_QKV, g.head_dim, st)));
+  (void)hd;
+
+  const bool overlap = (flags & BS_FLAG_OVERLAP) && p.n_decode > 0 && p.n_prefill_rows > 0;
+  if (!overlap) {
+    if ((rc = run_prefill_attn(c, p, c->qbuf, c->attn, pool, st))) return rc;
+    if ((rc = run_decode_attn(c, p, c->qbuf, c->attn, pool, st))) return rc;
+    if ((rc = run_tail(c, w, x, y, 0, T, st))) return rc;
+  } else {
+    // decode attention (HBM-bound) on the side stream while the prefill rows run
+    // their attention, projection and FFN (MFMA-bound) on the caller's stream
+    HIP_TRY(c, hipEventRecord(c->ev_fork, st));
+    HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
+    if ((rc = run_decode_attn(c, p, c->qbuf, c->attn, pool, c->side))) return rc;
+    HIP_TRY(c, hipEventRecord(c->ev_join, c->side));
+    if ((rc = run_prefill_attn(c, p, c->qbuf, c->attn, pool, st))) return rc;
+    if ((rc = run_tail(c, w, x, y, 0, p.n_prefill_rows, st))) return rc;
+    HIP_TRY(c, hipStreamWaitEvent(st, c->ev_join, 0));
+    if ((rc = run_tail(c, w, x, y, p.n_prefill_rows, T, st))) return rc;
+  }
+  return BS_OK;
+}
+
+int bs_attention(bs_ctx *c, const bs_batch *b, const void *q, void *out, const void *pool, int64_t n_pages,
+                 void *stream_, uint32_t flags) {
+  (void)flags;
+  if (!c) return BS_EINVAL;
+  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
+  int rc = validate(c, b, n_pages);
+  if (rc) return rc;
+  if (b->n_rows == 0) return BS_OK;
+  if (!q || !out || !pool) return fail(c, BS_EINVAL, "bs_attention: NULL pointer");
+  HIP_TRY(c, hipSetDevice(c->device));
+  hipStream_t st = (hipStream_t)stream_;
+  Plan p;
+  if ((rc = build_plan(c, b, p, false))) return rc;
+  if ((rc = ensure_slots(c, p.n_slots))) return rc;
+  if ((rc = upload_plan(c, p, st))) return rc;
+  if ((rc = run_prefill_attn(c, p, (const uint16_t *)q, (uint16_t *)out, (const uint16_t *)pool, st))) return rc;
+  if ((rc = run_decode_attn(c, p, (const uint16_t *)q, (uint16_t *)out, (const uint16_t *)pool, st))) return rc;
+  return BS_OK;
+}
+
+int bs_gemm_nt(bs_ctx *c, const void *a, const void *b, void *out, int32_t m, int32_t n, int32_t k, void *stream) {
+  if (!c) return BS_EINVAL;
+  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
+  if (m < 0 || n < 0 || k < 0 || (k % 8) || (n % 8)) return fail(c, BS_EINVAL, "bs_gemm_nt: m=%d n=%d k=%d (n, k multiples of 8)", m, n, k);
+  if (m == 0 || n == 0) return BS_OK;
+  if (!a || !b || !out) return fail(c, BS_EINVAL, "bs_gemm_nt: NULL pointer");
+  HIP_TRY(c, hipSetDevice(c->device));
+  GemmArgs g{};
+  g.A = (const uint16_t *)a; g.lda = k; g.B = (const uint16_t *)b; g.ldb = k;
+  g.M = m; g.N = n; g.K = k; g.C = (uint16_t *)out; g.ldc = n;
+  HIP_TRY(c, launch_gemm(g, EPI_PLAIN, c->cfg.head_dim, (hipStream_t)stream));
+  return BS_OK;
+}
+
+int bs_profile_enable(bs_ctx *c, int on) {
+  if (!c) return BS_EINVAL;
+  c->prof = on != 0;
+  return BS_OK;
+}
+
+int bs_profile_reset(bs_ctx *c) {
+  if (!c) return BS_EINVAL;
+  for (int k = 0; k < BS_K_COUNT; ++k) {
+    for (auto &s : c->spans[k]) {
+      (void)hipEventSynchronize(s.b);
+      c->free_events.push_back(s.a);
+      c->free_events.push_back(s.b);
+    }
+    c->spans[k].clear();
+    c->prof_ms[k] = 0;
+    c->prof_n[k] = 0;
+  }
+  return BS_OK;
+}
+
+int bs_profile_read(bs_ctx *c, int which, double *total_ms, int64_t *launches) {
+  if (!c) return BS_EINVAL;
+  if (which < 0 || which >= BS_K_COUNT) return fail(c, BS_EINVAL, "bs_profile_read: class %d", which);
+  for (auto &s : c->spans[which]) {
+    HIP_TRY(c, hipEventSynchronize(s.b));
+    float ms = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&ms, s.a, s.b));
+    c->prof_ms[which] += ms;
+    c->prof_n[which] += 1;
+    c->free_events.push_back(s.a);
+    c->free_events.push_back(s.b);
+  }
+  c->spans[which].clear();
+  if (total_ms) *total_ms = c->prof_ms[which];
+  if (launches) *launches = c->prof_n[which];
+  return BS_OK;
+}
+
+/* Tuning knob used by the benchmark sweeps: pages per decode-attention chunk. */
+int bs_set_chunk_pages(bs_ctx *c, int32_t pages) {
+  if (!c) return BS_EINVAL;
+  if (pages < 2 || pages > 4096 || (pages & 1)) return fail(c, BS_EINVAL, "chunk_pages %d (even, 2..4096)", pages);
+  c->chunk_pages = pages;
+  return BS_OK;
+}
+
+}  // extern "C"

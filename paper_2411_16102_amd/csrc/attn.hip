@@ -1,0 +1,428 @@
+// Paged attention kernels for gfx950.
+//
+// KV page layout (per page, per KV head): a K tile [16 slots][dh] and a
+// TRANSPOSED V tile [dh][16 slots].  Both contractions then read their MFMA
+// operands straight from global memory with the contracted index contiguous:
+// scores contract over dh (K rows), outputs contract over tokens (V^T rows).
+//
+// Both kernels compute transposed products, S^T = K Q^T and O^T = V^T P^T, so that
+// a lane owns ONE query row (its accumulator column): the running maximum, the
+// running sum and the rescale factor of the online softmax are per-lane scalars,
+// and the probabilities leave the score accumulators already in the register
+// layout the second MFMA wants for its P^T operand (the token order inside a
+// k-group is permuted the same way on the V^T side, which a contraction allows).
+//
+// Decode attention is prefix-aware (BlendServe Appendix A.2, intra-batch prefix
+// sharing; Section 4.1, decode attention is the memory-bound operator whose time
+// is the bytes of KV it loads): the pages of a prefix node are read once for all
+// member sequences of the node, whose query rows are stacked along the MFMA N
+// dimension; every (node chunk | private tail chunk) leaves a partial softmax
+// state (m, l, acc) per query row and head, and a second kernel merges a
+// sequence's states along its root-to-leaf path.
+#include "attn.hpp"
+#include "common.hpp"
+
+namespace bs {
+namespace {
+
+constexpr float NEG_BIG = -1.0e30f;
+constexpr int XCDS = 8;
+
+// contiguous ranges of workgroups per XCD (ids are dealt round-robin to the XCDs),
+// so that neighbouring work, which reads the same pages, meets in one L2
+__device__ __forceinline__ int xcd_contiguous(int pid, int n) {
+  const int per = n / XCDS, rem = n % XCDS;
+  const int xcd = pid % XCDS, idx = pid / XCDS;
+  return xcd * per + (xcd < rem ? xcd : rem) + idx;
+}
+
+__device__ __forceinline__ u32x4_t ld16(const uint16_t *p) { return *reinterpret_cast<const u32x4_t *>(p); }
+__device__ __forceinline__ u32x2_t ld8(const uint16_t *p) { return *reinterpret_cast<const u32x2_t *>(p); }
+
+// zero the bf16 halves of `v` (tokens t0 .. t0+3) that lie at or beyond `limit`
+__device__ __forceinline__ u32x2_t mask_tokens(u32x2_t v, int t0, int limit) {
+  if (t0 + 0 >= limit) v.x &= 0xFFFF0000u;
+  if (t0 + 1 >= limit) v.x &= 0x0000FFFFu;
+  if (t0 + 2 >= limit) v.y &= 0xFFFF0000u;
+  if (t0 + 3 >= limit) v.y &= 0x0000FFFFu;
+  return v;
+}
+
+// ------------------------------------------------------------------------------
+// decode attention: one wavefront per (item, KV head)
+// ------------------------------------------------------------------------------
+template <int DH, int NQB>
+__global__ __launch_bounds__(256) void decode_attn_kernel(const DecodeArgs a, int item_base, int n_units) {
+  constexpr int KC = DH / 32;  // 32-wide chunks of the head dimension (QK^T contraction)
+  constexpr int DB = DH / 16;  // 16-row blocks of the head dimension (PV output rows)
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int unit = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + wave;
+  if (unit >= n_units) return;
+  const int hkv = a.s.n_kv_heads, hq = a.s.n_q_heads, grp = hq / hkv;
+  const int item = item_base + unit / hkv;
+  const int kvh = unit % hkv;
+  const DecodeItem it = a.items[item];
+  const int n_rows = it.n_members * grp;
+  const int n_tok = it.n_tokens;
+  const int n_pg = (n_tok + 15) >> 4;
+  const int jq = lane & 15, g4 = lane >> 4;
+  const size_t tile = (size_t)16 * DH;
+
+  // query fragments: B operand of S^T = K Q^T; lane (jq, g4) holds Q[row jq][32c + 8 g4 ..+7]
+  bf16x8_t qf[NQB][KC];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int r = qb * 16 + jq;
+    const bool ok = r < n_rows;
+    const int seq = it.seq_first + (ok ? r / grp : 0);
+    const int head = kvh * grp + (ok ? r % grp : 0);
+    const uint16_t *p = a.q + (size_t)a.row_start[seq] * (hq * DH) + head * DH + 8 * g4;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      u32x4_t v = {0u, 0u, 0u, 0u};
+      if (ok) v = ld16(p + 32 * c);
+      qf[qb][c] = as_bf16x8(v);
+    }
+  }
+
+  f32x4_t o[NQB][DB];
+  float m[NQB], l[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    m[qb] = NEG_BIG;
+    l[qb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) o[qb][db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const int32_t *pages = a.item_pages + it.page_off;
+  const int n_pairs = (n_pg + 1) >> 1;
+
+  struct Frags {
+    u32x4_t k[2][KC];
+    u32x2_t v0[DB], v1[DB];
+  };
+  auto load = [&](int pr, Frags &f) {
+    const int i0 = 2 * pr;
+    const size_t p0 = pages[i0];
+    const size_t p1 = (i0 + 1 < n_pg) ? pages[i0 + 1] : p0;
+    const uint16_t *k0 = a.kv_pool + ((p0 * 2 + 0) * hkv + kvh) * tile + jq * DH + 8 * g4;
+    const uint16_t *k1 = a.kv_pool + ((p1 * 2 + 0) * hkv + kvh) * tile + jq * DH + 8 * g4;
+    const uint16_t *v0 = a.kv_pool + ((p0 * 2 + 1) * hkv + kvh) * tile + jq * 16 + 4 * g4;
+    const uint16_t *v1 = a.kv_pool + ((p1 * 2 + 1) * hkv + kvh) * tile + jq * 16 + 4 * g4;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      f.k[0][c] = ld16(k0 + 32 * c);
+      f.k[1][c] = ld16(k1 + 32 * c);
+    }
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      f.v0[db] = ld8(v0 + db * 256);
+      f.v1[db] = ld8(v1 + db * 256);
+    }
+  };
+  auto compute = [&](int pr, Frags &f) {
+    const int tb = pr * 32;
+    const bool ragged = tb + 32 > n_tok;
+    if (ragged) {  // never let stale slots (possibly NaN bit patterns) meet a zero probability
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        f.v0[db] = mask_tokens(f.v0[db], tb + 4 * g4, n_tok);
+        f.v1[db] = mask_tokens(f.v1[db], tb + 16 + 4 * g4, n_tok);
+      }
+    }
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < KC; ++c) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[0][c]), qf[qb][c], s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[1][c]), qf[qb][c], s1, 0, 0, 0);
+      }
+      float sv[8];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        sv[r] = (tb + 4 * g4 + r < n_tok) ? s0[r] * a.s.scale_log2e : NEG_BIG;
+        sv[4 + r] = (tb + 16 + 4 * g4 + r < n_tok) ? s1[r] * a.s.scale_log2e : NEG_BIG;
+      }
+      float mx = sv[0];
+#pragma unroll
+      for (int r = 1; r < 8; ++r) mx = fmaxf(mx, sv[r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m[qb], mx);
+      const float alpha = exp2f(m[qb] - m_new);
+      m[qb] = m_new;
+      float ps = 0.f;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        sv[r] = exp2f(sv[r] - m_new);
+        ps += sv[r];
+      }
+      l[qb] = l[qb] * alpha + ps;
+      u32x4_t pw;
+      pw.x = pack_bf16x2(sv[0], sv[1]);
+      pw.y = pack_bf16x2(sv[2], sv[3]);
+      pw.z = pack_bf16x2(sv[4], sv[5]);
+      pw.w = pack_bf16x2(sv[6], sv[7]);
+      const bf16x8_t pf = as_bf16x8(pw);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        u32x4_t vw;
+        vw.x = f.v0[db].x;
+        vw.y = f.v0[db].y;
+        vw.z = f.v1[db].x;
+        vw.w = f.v1[db].y;
+        o[qb][db] *= alpha;
+        o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vw), pf, o[qb][db], 0, 0, 0);
+      }
+    }
+  };
+
+  Frags fa, fb;
+  load(0, fa);
+  for (int pr = 0; pr < n_pairs; pr += 2) {
+    if (pr + 1 < n_pairs) load(pr + 1, fb);
+    compute(pr, fa);
+    if (pr + 1 < n_pairs) {
+      if (pr + 2 < n_pairs) load(pr + 2, fa);
+      compute(pr + 1, fb);
+    }
+  }
+
+  // partial state out: lane (jq, g4) holds, of query row jq, dh = 16 db + 4 g4 .. +3
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    float ls = l[qb];
+    ls += __shfl_xor(ls, 16, 64);
+    ls += __shfl_xor(ls, 32, 64);
+    const int r = qb * 16 + jq;
+    if (r < n_rows) {
+      const int seq = it.seq_first + r / grp;
+      const int head = kvh * grp + r % grp;
+      const size_t base = (size_t)(a.part_start[seq] + it.slot_off) * hq + head;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        *reinterpret_cast<f32x4_t *>(a.part_acc + base * DH + 16 * db + 4 * g4) = o[qb][db];
+      if (g4 == 0) {
+        a.part_m[base] = m[qb];
+        a.part_l[base] = ls;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------
+// merge: one wavefront per (decode sequence, query head)
+//   M = max_p m_p;  w_p = 2^(m_p - M);  out = sum_p w_p acc_p / sum_p w_p l_p
+// ------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void decode_merge_kernel(const MergeArgs a) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int hq = a.s.n_q_heads;
+  const int unit = blockIdx.x * 4 + wave;
+  if (unit >= a.n_decode * hq) return;
+  const int seq = a.n_prefill + unit / hq;
+  const int head = unit % hq;
+  const int s0 = a.part_start[seq], n = a.part_start[seq + 1] - s0;
+  float mx = NEG_BIG;
+  for (int p = lane; p < n; p += 64) mx = fmaxf(mx, a.part_m[(size_t)(s0 + p) * hq + head]);
+  mx = wave_max(mx);
+  float ls = 0.f;
+  for (int p = lane; p < n; p += 64) {
+    const size_t b = (size_t)(s0 + p) * hq + head;
+    ls += exp2f(a.part_m[b] - mx) * a.part_l[b];
+  }
+  ls = wave_sum(ls);
+  constexpr int E = DH / 64;  // elements per lane
+  float acc[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) acc[e] = 0.f;
+  for (int p = 0; p < n; ++p) {
+    const size_t b = (size_t)(s0 + p) * hq + head;
+    const float w = exp2f(a.part_m[b] - mx);
+    const float *src = a.part_acc + b * DH + lane * E;
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[e] += w * src[e];
+  }
+  const float inv = 1.f / ls;
+  uint16_t *dst = a.out + (size_t)a.row_start[seq] * (hq * DH) + head * DH + lane * E;
+#pragma unroll
+  for (int e = 0; e < E; ++e) dst[e] = f32_to_bf16(acc[e] * inv);
+}
+
+// ------------------------------------------------------------------------------
+// prefill attention: one wavefront per (32 query rows, query head); the
+// wavefronts of a workgroup are the heads of one KV group and walk the same pages
+// ------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, int heads_per_wg) {
+  constexpr int KC = DH / 16;  // k-steps of the 32x32x16 score MFMA
+  constexpr int DB = DH / 32;  // 32-row blocks of the output
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int hkv = a.s.n_kv_heads, hq = a.s.n_q_heads, grp = hq / hkv;
+  const int wg_per_work = hq / heads_per_wg;
+  const int w = blockIdx.x / wg_per_work;
+  const int seq = a.work[2 * w], qblk = a.work[2 * w + 1];
+  const int head = (blockIdx.x % wg_per_work) * heads_per_wg + wave;
+  const int kvh = head / grp;
+  const int r0 = a.row_start[seq], q_len = a.row_start[seq + 1] - r0;
+  const int kv_len = a.kv_len[seq];
+  const int n_q = min(32, q_len - qblk * 32);
+  const int first_pos = kv_len - q_len + qblk * 32;
+  const int lr = lane & 31, g2 = lane >> 5;
+  const int my_pos = min(first_pos + lr, kv_len - 1);
+  const size_t tile = (size_t)16 * DH;
+  const int32_t *pages = a.page_ids + a.page_start[seq];
+  const int n_pg = (kv_len + 15) >> 4;
+
+  bf16x8_t qf[KC];
+  {
+    const bool ok = lr < n_q;
+    const uint16_t *p = a.q + (size_t)(r0 + qblk * 32 + (ok ? lr : 0)) * (hq * DH) + head * DH + 8 * g2;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      u32x4_t v = {0u, 0u, 0u, 0u};
+      if (ok) v = ld16(p + 16 * c);
+      qf[c] = as_bf16x8(v);
+    }
+  }
+  f32x16_t o[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m = NEG_BIG, l = 0.f;
+
+  const int last_tok = first_pos + n_q - 1;
+  const int n_tb = last_tok / 32 + 1;
+  for (int tb = 0; tb < n_tb; ++tb) {
+    const size_t p0 = pages[2 * tb];
+    const size_t p1 = (2 * tb + 1 < n_pg) ? pages[2 * tb + 1] : p0;
+    const size_t pk = (lr < 16) ? p0 : p1;
+    const uint16_t *kp = a.kv_pool + ((pk * 2 + 0) * hkv + kvh) * tile + (lr & 15) * DH + 8 * g2;
+    f32x16_t s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int c = 0; c < KC; ++c)
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ld16(kp + 16 * c)), qf[c], s, 0, 0, 0);
+    // element r: token tb*32 + 8*(r/4) + 4*g2 + r%4 against the query at my_pos
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int t = tb * 32 + 8 * (r >> 2) + 4 * g2 + (r & 3);
+      s[r] = (t <= my_pos) ? s[r] * a.s.scale_log2e : NEG_BIG;
+      mx = fmaxf(mx, s[r]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);
+    const float alpha = exp2f(m - m_new);
+    m = m_new;
+    float ps = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      s[r] = exp2f(s[r] - m_new);
+      ps += s[r];
+    }
+    l = l * alpha + ps;
+    u32x4_t pw0, pw1;
+    pw0.x = pack_bf16x2(s[0], s[1]);
+    pw0.y = pack_bf16x2(s[2], s[3]);
+    pw0.z = pack_bf16x2(s[4], s[5]);
+    pw0.w = pack_bf16x2(s[6], s[7]);
+    pw1.x = pack_bf16x2(s[8], s[9]);
+    pw1.y = pack_bf16x2(s[10], s[11]);
+    pw1.z = pack_bf16x2(s[12], s[13]);
+    pw1.w = pack_bf16x2(s[14], s[15]);
+    const bool ragged = tb * 32 + 32 > kv_len;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const uint16_t *v0 = a.kv_pool + ((p0 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
+      const uint16_t *v1 = a.kv_pool + ((p1 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
+      u32x2_t a0 = ld8(v0), a1 = ld8(v0 + 8), b0 = ld8(v1), b1 = ld8(v1 + 8);
+      if (ragged) {
+        a0 = mask_tokens(a0, tb * 32 + 4 * g2, kv_len);
+        a1 = mask_tokens(a1, tb * 32 + 8 + 4 * g2, kv_len);
+        b0 = mask_tokens(b0, tb * 32 + 16 + 4 * g2, kv_len);
+        b1 = mask_tokens(b1, tb * 32 + 24 + 4 * g2, kv_len);
+      }
+      u32x4_t va, vb;
+      va.x = a0.x; va.y = a0.y; va.z = a1.x; va.w = a1.y;
+      vb.x = b0.x; vb.y = b0.y; vb.z = b1.x; vb.w = b1.y;
+      o[db] *= alpha;
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va), as_bf16x8(pw0), o[db], 0, 0, 0);
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vb), as_bf16x8(pw1), o[db], 0, 0, 0);
+    }
+  }
+  l += __shfl_xor(l, 32, 64);
+  if (lr < n_q) {
+    const float inv = 1.f / l;
+    uint16_t *dst = a.out + (size_t)(r0 + qblk * 32 + lr) * (hq * DH) + head * DH;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        u32x2_t v;
+        v.x = pack_bf16x2(o[db][4 * q + 0] * inv, o[db][4 * q + 1] * inv);
+        v.y = pack_bf16x2(o[db][4 * q + 2] * inv, o[db][4 * q + 3] * inv);
+        *reinterpret_cast<u32x2_t *>(dst + 32 * db + 8 * q + 4 * g2) = v;
+      }
+  }
+}
+
+template <int DH, int NQB>
+hipError_t launch_decode_t(const DecodeArgs &a, int item_base, int n_items, hipStream_t stream) {
+  const int n_units = n_items * a.s.n_kv_heads;
+  if (n_units <= 0) return hipSuccess;
+  hipLaunchKernelGGL((decode_attn_kernel<DH, NQB>), dim3((n_units + 3) / 4), dim3(256), 0, stream, a, item_base,
+                     n_units);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_decode_attn(const DecodeArgs &a, int item_base, int n_items, int nqb, hipStream_t stream) {
+  const int dh = a.s.head_dim;
+  if (dh == 128) {
+    if (nqb == 1) return launch_decode_t<128, 1>(a, item_base, n_items, stream);
+    if (nqb == 2) return launch_decode_t<128, 2>(a, item_base, n_items, stream);
+    if (nqb == 4) return launch_decode_t<128, 4>(a, item_base, n_items, stream);
+  } else if (dh == 64) {
+    if (nqb == 1) return launch_decode_t<64, 1>(a, item_base, n_items, stream);
+    if (nqb == 2) return launch_decode_t<64, 2>(a, item_base, n_items, stream);
+    if (nqb == 4) return launch_decode_t<64, 4>(a, item_base, n_items, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_decode_merge(const MergeArgs &a, hipStream_t stream) {
+  const int units = a.n_decode * a.s.n_q_heads;
+  if (units <= 0) return hipSuccess;
+  if (a.s.head_dim == 128)
+    hipLaunchKernelGGL((decode_merge_kernel<128>), dim3((units + 3) / 4), dim3(256), 0, stream, a);
+  else if (a.s.head_dim == 64)
+    hipLaunchKernelGGL((decode_merge_kernel<64>), dim3((units + 3) / 4), dim3(256), 0, stream, a);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_prefill_attn(const PrefillArgs &a, hipStream_t stream) {
+  if (a.n_work <= 0) return hipSuccess;
+  const int grp = a.s.n_q_heads / a.s.n_kv_heads;
+  const int hpw = (grp % 4 == 0) ? 4 : ((grp % 2 == 0) ? 2 : 1);  // heads of one KV group share a workgroup
+  const dim3 grid(a.n_work * (a.s.n_q_heads / hpw)), block(64 * hpw);
+  if (a.s.head_dim == 128)
+    hipLaunchKernelGGL((prefill_attn_kernel<128>), grid, block, 0, stream, a, hpw);
+  else if (a.s.head_dim == 64)
+    hipLaunchKernelGGL((prefill_attn_kernel<64>), grid, block, 0, stream, a, hpw);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace bs

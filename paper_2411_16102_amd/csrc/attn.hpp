@@ -1,0 +1,62 @@
+// Paged attention for the blended step: prefix-aware decode attention (partial
+// softmax states per prefix node / private tail, then a merge) and causal
+// prefill attention, both on the gfx950 matrix cores.
+#pragma once
+#include <stdint.h>
+#include <hip/hip_runtime.h>
+
+namespace bs {
+
+// One unit of decode-attention work: a run of pages (a chunk of a prefix node,
+// or of one sequence's private tail) attended to by the query rows of a
+// contiguous run of member sequences.
+struct DecodeItem {
+  int32_t page_off;   // first page of the chunk in item_pages
+  int32_t n_tokens;   // tokens in the chunk (the last page may be partial)
+  int32_t seq_first;  // first member sequence
+  int32_t n_members;  // member sequences (n_members * group <= 16 * NQB of the launch)
+  int32_t slot_off;   // partial-state slot of this chunk inside every member's slot range
+  int32_t pad[3];
+};
+
+struct AttnShape {
+  int n_q_heads, n_kv_heads, head_dim, page_size;
+  float scale_log2e;  // log2(e) / sqrt(dh)
+};
+
+struct DecodeArgs {
+  AttnShape s;
+  const DecodeItem *items;
+  const int32_t *item_pages;
+  const int32_t *row_start;   // [n_seq + 1]
+  const int32_t *part_start;  // [n_seq + 1] partial-state slots of each sequence
+  const uint16_t *q;          // [T, Hq*dh]
+  const uint16_t *kv_pool;
+  float *part_acc;            // [slots][Hq][dh]
+  float *part_m, *part_l;     // [slots][Hq]
+};
+
+// items [item_base, item_base + n_items) all fit `nqb` blocks of 16 query rows
+hipError_t launch_decode_attn(const DecodeArgs &a, int item_base, int n_items, int nqb, hipStream_t stream);
+
+struct MergeArgs {
+  AttnShape s;
+  int n_prefill, n_decode;
+  const int32_t *row_start, *part_start;
+  const float *part_acc, *part_m, *part_l;
+  uint16_t *out;  // [T, Hq*dh]
+};
+hipError_t launch_decode_merge(const MergeArgs &a, hipStream_t stream);
+
+struct PrefillArgs {
+  AttnShape s;
+  const int32_t *work;  // [n_work][2] = (sequence, block of 32 query rows)
+  int n_work;
+  const int32_t *row_start, *kv_len, *page_start, *page_ids;
+  const uint16_t *q;
+  const uint16_t *kv_pool;
+  uint16_t *out;
+};
+hipError_t launch_prefill_attn(const PrefillArgs &a, hipStream_t stream);
+
+}  // namespace bs

@@ -1,0 +1,401 @@
+// bf16 "NT" GEMM  C[M,N] = A[M,K] * B[N,K]^T  for gfx950, fp32 accumulation on
+// v_mfma_f32_32x32x16_bf16, tiles staged through LDS, fused epilogues.
+//
+// Operand roles are swapped with respect to the usual picture: the weight rows
+// feed the MFMA "A" operand and the activation rows the "B" operand, so an
+// accumulator block holds C^T: a lane owns ONE activation row (m = lane % 32) and
+// runs of four consecutive output features (n).  Every fused epilogue is then
+// lane-local: the RMSNorm factor of a row is one scalar per lane, a RoPE pair
+// (i, i + dh/2) and a SwiGLU (gate, up) pair sit in two accumulator blocks of the
+// same lane, and results leave as 8-byte bf16x4 stores.
+//
+// LDS tile layout: rows of BK = 64 bf16 (128 B) whose eight 16-byte chunks are
+// XOR-swizzled with (row & 7), so the ds_read_b128 of a fragment (32 rows, one
+// chunk column) spreads over all banks.
+#include "gemm.hpp"
+#include "common.hpp"
+
+namespace bs {
+
+namespace {
+
+constexpr int BK = 64;
+constexpr int XCDS = 8;
+
+struct TileCoord { int tm, tn; };
+
+// Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous
+// range of tiles and walk that range in groups of GM tile rows, so the tiles in
+// flight on one XCD share activation and weight panels in that XCD's L2.
+__device__ __forceinline__ TileCoord map_tile(int pid, int n_tiles, int tiles_m, int tiles_n) {
+  const int per = n_tiles / XCDS, rem = n_tiles % XCDS;
+  const int xcd = pid % XCDS, idx = pid / XCDS;
+  const int lin = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  constexpr int GM = 4;
+  const int group = GM * tiles_n;
+  const int g = lin / group;
+  const int first_m = g * GM;
+  const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+  const int in = lin - g * group;
+  TileCoord t;
+  t.tm = first_m + in % gm;
+  t.tn = in / gm;
+  return t;
+}
+
+__device__ __forceinline__ void store_bf16x4(uint16_t *p, float a, float b, float c, float d) {
+  u32x2_t v;
+  v.x = pack_bf16x2(a, b);
+  v.y = pack_bf16x2(c, d);
+  *reinterpret_cast<u32x2_t *>(p) = v;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
+  constexpr int NT = WAVES_M * WAVES_N * 64;
+  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  constexpr int MI = WTM / 32, NI = WTN / 32;
+  constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  constexpr int X_BYTES = BM * BK * 2, W_BYTES = BN * BK * 2, STAGE = X_BYTES + W_BYTES;
+  constexpr int XCH = BM * 8 / NT, WCH = BN * 8 / NT;  // 16-byte chunks per thread per tile
+  static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile rows must divide over the threads");
+  static_assert(EPI != EPI_SWIGLU || NI % 2 == 0, "gate and up blocks pair up inside a wave");
+  static_assert(EPI != EPI_QKV || (WTN % DH == 0 && DH % 64 == 0), "a wave covers whole heads");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + OUT_BN - 1) / OUT_BN;
+  const TileCoord tc = map_tile(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n);
+  const int m0 = tc.tm * BM, n0 = tc.tn * OUT_BN;
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm0 = (wave / WAVES_N) * WTM, wn0 = (wave % WAVES_N) * WTN;
+  const int lr = lane & 31, lg = lane >> 5;
+
+  // ---- global -> register staging --------------------------------------------
+  const int kc = t & 7;          // 16-byte chunk column of this thread
+  const int r0 = t >> 3;         // first tile row of this thread; next rows are NT/8 apart
+  const uint16_t *xptr[XCH];
+  bool xok[XCH];
+  int xoff[XCH];
+#pragma unroll
+  for (int i = 0; i < XCH; ++i) {
+    const int row = r0 + i * (NT / 8);
+    const int gm = m0 + row;
+    xok[i] = gm < a.M;
+    xptr[i] = a.A + (size_t)(xok[i] ? gm : 0) * a.lda + kc * 8;
+    xoff[i] = row * 128 + ((kc ^ (row & 7)) << 4);
+  }
+  const uint16_t *wptr[WCH];
+  bool wok[WCH];
+  int woff[WCH];
+#pragma unroll
+  for (int i = 0; i < WCH; ++i) {
+    const int row = r0 + i * (NT / 8);
+    int gn;
+    bool ok;
+    if (EPI == EPI_SWIGLU) {
+      const int blk = row >> 5;
+      const int col = n0 + (blk >> 1) * 32 + (row & 31);
+      ok = col < a.N;
+      gn = col + ((blk & 1) ? a.N : 0);
+    } else {
+      gn = n0 + row;
+      ok = gn < a.N;
+    }
+    wok[i] = ok;
+    wptr[i] = a.B + (size_t)(ok ? gn : 0) * a.ldb + kc * 8;
+    woff[i] = X_BYTES + row * 128 + ((kc ^ (row & 7)) << 4);
+  }
+
+  u32x4_t xs[XCH], ws[WCH];
+  auto load_global = [&](int k0) {
+    const bool kok = (k0 + kc * 8) < a.K;
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) {
+      u32x4_t v = {0u, 0u, 0u, 0u};
+      if (xok[i] && kok) v = *reinterpret_cast<const u32x4_t *>(xptr[i] + k0);
+      xs[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < WCH; ++i) {
+      u32x4_t v = {0u, 0u, 0u, 0u};
+      if (wok[i] && kok) v = *reinterpret_cast<const u32x4_t *>(wptr[i] + k0);
+      ws[i] = v;
+    }
+  };
+  auto store_lds = [&](int buf) {
+    unsigned char *base = smem + buf * STAGE;
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) *reinterpret_cast<u32x4_t *>(base + xoff[i]) = xs[i];
+#pragma unroll
+    for (int i = 0; i < WCH; ++i) *reinterpret_cast<u32x4_t *>(base + woff[i]) = ws[i];
+  };
+
+  f32x16_t acc[NI][MI];
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[ni][mi][r] = 0.f;
+
+  // fragment addresses: row = tile row of the lane, chunk = 2*ks + lg, swizzled by (row & 7) = (lr & 7)
+  const int xfrag = (wm0 + lr) * 128;
+  const int wfrag = X_BYTES + (wn0 + lr) * 128;
+  const int sw = lr & 7;
+
+  const int nk = (a.K + BK - 1) / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    if (kt + 1 < nk) load_global((kt + 1) * BK);
+    const unsigned char *base = smem + (kt & 1) * STAGE;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const int ch = ((ks * 2 + lg) ^ sw) << 4;
+      bf16x8_t xf[MI], wf[NI];
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+        xf[mi] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + xfrag + mi * 32 * 128 + ch));
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        wf[ni] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + wfrag + ni * 32 * 128 + ch));
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+          acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_lds((kt + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- epilogues ---------------------------------------------------------------
+  // accumulator element r of block (ni, mi): m = m0 + wm0 + mi*32 + lr,
+  // n = n_tile + wn0 + ni*32 + 8*(r/4) + 4*lg + r%4
+  float rstd[MI];
+  if (EPI == EPI_QKV || EPI == EPI_SWIGLU) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int m = m0 + wm0 + mi * 32 + lr;
+      float s = 0.f;
+      if (m < a.M)
+        for (int p = 0; p < a.n_ss_part; ++p) s += a.ss_part[(size_t)p * a.ss_stride + m];
+      rstd[mi] = rsqrtf(s / a.norm_dim + a.eps);
+    }
+  }
+
+  if (EPI == EPI_PLAIN || EPI == EPI_RESID) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int m = m0 + wm0 + mi * 32 + lr;
+      if (m >= a.M) continue;
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int n = n0 + wn0 + ni * 32 + 8 * q + 4 * lg;
+          if (n >= a.N) continue;
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = acc[ni][mi][4 * q + e];
+          if (EPI == EPI_RESID) {
+            const u32x2_t rr = *reinterpret_cast<const u32x2_t *>(a.resid + (size_t)m * a.ldr + n);
+            v[0] += __uint_as_float(rr.x << 16);
+            v[1] += __uint_as_float(rr.x & 0xFFFF0000u);
+            v[2] += __uint_as_float(rr.y << 16);
+            v[3] += __uint_as_float(rr.y & 0xFFFF0000u);
+          }
+          store_bf16x4(a.C + (size_t)m * a.ldc + n, v[0], v[1], v[2], v[3]);
+        }
+    }
+  }
+
+  if (EPI == EPI_RESID_NORM) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int m = m0 + wm0 + mi * 32 + lr;
+      float ss = 0.f;
+      if (m < a.M) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int n = n0 + wn0 + ni * 32 + 8 * q + 4 * lg;
+            if (n >= a.N) continue;
+            const u32x2_t rr = *reinterpret_cast<const u32x2_t *>(a.resid + (size_t)m * a.ldr + n);
+            const u32x2_t gg = *reinterpret_cast<const u32x2_t *>(a.gain + n);
+            float v[4], g[4];
+            v[0] = acc[ni][mi][4 * q + 0] + __uint_as_float(rr.x << 16);
+            v[1] = acc[ni][mi][4 * q + 1] + __uint_as_float(rr.x & 0xFFFF0000u);
+            v[2] = acc[ni][mi][4 * q + 2] + __uint_as_float(rr.y << 16);
+            v[3] = acc[ni][mi][4 * q + 3] + __uint_as_float(rr.y & 0xFFFF0000u);
+            g[0] = __uint_as_float(gg.x << 16);
+            g[1] = __uint_as_float(gg.x & 0xFFFF0000u);
+            g[2] = __uint_as_float(gg.y << 16);
+            g[3] = __uint_as_float(gg.y & 0xFFFF0000u);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              v[e] = round_bf16(v[e]);  // x1 as it is stored; the norm sees the stored value
+              ss += v[e] * v[e];
+            }
+            store_bf16x4(a.C + (size_t)m * a.ldc + n, v[0], v[1], v[2], v[3]);
+            store_bf16x4(a.C_gain + (size_t)m * a.ldc + n, v[0] * g[0], v[1] * g[1], v[2] * g[2], v[3] * g[3]);
+          }
+      }
+      ss += __shfl_xor(ss, 32, 64);
+      if (lg == 0 && m < a.M)
+        a.ss_out[(size_t)(tc.tn * WAVES_N + (wave % WAVES_N)) * a.ss_stride + m] = ss;
+    }
+  }
+
+  if (EPI == EPI_SWIGLU) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int m = m0 + wm0 + mi * 32 + lr;
+      if (m >= a.M) continue;
+      const float s = rstd[mi];
+#pragma unroll
+      for (int p = 0; p < NI / 2; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int n = n0 + (wn0 >> 1) + p * 32 + 8 * q + 4 * lg;
+          if (n >= a.N) continue;
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float g = acc[2 * p][mi][4 * q + e] * s;
+            const float u = acc[2 * p + 1][mi][4 * q + e] * s;
+            v[e] = g / (1.f + __expf(-g)) * u;
+          }
+          store_bf16x4(a.C + (size_t)m * a.ldc + n, v[0], v[1], v[2], v[3]);
+        }
+    }
+  }
+
+  if (EPI == EPI_QKV) {
+    constexpr int HB = DH / 32, PB = HB / 2, HALF = DH / 2;
+    const size_t tile_elems = (size_t)16 * DH;  // one K or V tile of a (page, head)
+#pragma unroll
+    for (int hh = 0; hh < WTN / DH; ++hh) {
+      const int nh = n0 + wn0 + hh * DH;
+      if (nh >= a.N) continue;
+      const int head = nh / DH;
+      const bool is_q = head < a.n_q_heads;
+      const bool is_k = !is_q && head < a.n_q_heads + a.n_kv_heads;
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        const int m = m0 + wm0 + mi * 32 + lr;
+        if (m >= a.M) continue;
+        const float s = rstd[mi];
+        if (is_q || is_k) {
+          const int pos = a.row_pos[m];
+          uint16_t *dst;
+          if (is_q) {
+            dst = a.q_out + (size_t)m * (a.n_q_heads * DH) + head * DH;
+          } else {
+            const size_t page = a.row_page[m];
+            dst = a.kv_pool + ((page * 2 + 0) * a.n_kv_heads + (head - a.n_q_heads)) * tile_elems +
+                  (size_t)a.row_slot[m] * DH;
+          }
+#pragma unroll
+          for (int j = 0; j < PB; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int i = j * 32 + 8 * q + 4 * lg;
+              const f32x4_t c4 = *reinterpret_cast<const f32x4_t *>(a.rope_cos + (size_t)pos * HALF + i);
+              const f32x4_t s4 = *reinterpret_cast<const f32x4_t *>(a.rope_sin + (size_t)pos * HALF + i);
+              float lo[4], hi[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const float l = acc[hh * HB + j][mi][4 * q + e] * s;
+                const float h = acc[hh * HB + PB + j][mi][4 * q + e] * s;
+                lo[e] = l * c4[e] - h * s4[e];
+                hi[e] = h * c4[e] + l * s4[e];
+              }
+              store_bf16x4(dst + i, lo[0], lo[1], lo[2], lo[3]);
+              store_bf16x4(dst + HALF + i, hi[0], hi[1], hi[2], hi[3]);
+            }
+        } else {
+          const size_t page = a.row_page[m];
+          const int slot = a.row_slot[m];
+          uint16_t *dst = a.kv_pool +
+                          ((page * 2 + 1) * a.n_kv_heads + (head - a.n_q_heads - a.n_kv_heads)) * tile_elems + slot;
+#pragma unroll
+          for (int b = 0; b < HB; ++b)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const int ei = b * 32 + 8 * q + 4 * lg + e;
+                dst[ei * 16] = f32_to_bf16(acc[hh * HB + b][mi][4 * q + e] * s);
+              }
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH>
+hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
+  constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  constexpr int LDS = 2 * (BM + BN) * BK * 2;
+  auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI, DH>;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + OUT_BN - 1) / OUT_BN);
+  if (tiles <= 0) return hipSuccess;
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(WAVES_M * WAVES_N * 64), LDS, stream, a);
+  return hipGetLastError();
+}
+
+// Large tiles once they can fill the chip; otherwise 128 x 128 tiles.
+bool use_big_tiles(int m, int n_tiles_cols_256) {
+  const long tiles = (long)((m + 255) / 256) * n_tiles_cols_256;
+  return m >= 1024 && tiles >= 128;
+}
+
+}  // namespace
+
+int gemm_ss_parts(int n, int epilogue, int m, int dh) {
+  (void)epilogue; (void)dh;
+  const bool big = use_big_tiles(m, (n + 255) / 256);
+  // RESID_NORM instances: 256x256 tiles with 4 waves along N, or 128x128 with 2
+  return big ? ((n + 255) / 256) * 4 : ((n + 127) / 128) * 2;
+}
+
+hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream) {
+  switch (epilogue) {
+    case EPI_PLAIN:
+      return use_big_tiles(a.M, (a.N + 255) / 256) ? launch_one<256, 256, 2, 4, EPI_PLAIN, 64>(a, stream)
+                                                  : launch_one<128, 128, 2, 2, EPI_PLAIN, 64>(a, stream);
+    case EPI_RESID:
+      return use_big_tiles(a.M, (a.N + 255) / 256) ? launch_one<256, 256, 2, 4, EPI_RESID, 64>(a, stream)
+                                                  : launch_one<128, 128, 2, 2, EPI_RESID, 64>(a, stream);
+    case EPI_RESID_NORM:
+      return use_big_tiles(a.M, (a.N + 255) / 256) ? launch_one<256, 256, 2, 4, EPI_RESID_NORM, 64>(a, stream)
+                                                  : launch_one<128, 128, 2, 2, EPI_RESID_NORM, 64>(a, stream);
+    case EPI_SWIGLU:
+      return use_big_tiles(a.M, (a.N + 127) / 128) ? launch_one<256, 256, 2, 4, EPI_SWIGLU, 64>(a, stream)
+                                                  : launch_one<128, 128, 2, 2, EPI_SWIGLU, 64>(a, stream);
+    case EPI_QKV:
+      if (dh == 128)
+        return use_big_tiles(a.M, (a.N + 255) / 256) ? launch_one<256, 256, 4, 2, EPI_QKV, 128>(a, stream)
+                                                    : launch_one<128, 128, 4, 1, EPI_QKV, 128>(a, stream);
+      if (dh == 64)
+        return use_big_tiles(a.M, (a.N + 255) / 256) ? launch_one<256, 256, 2, 4, EPI_QKV, 64>(a, stream)
+                                                    : launch_one<128, 128, 2, 2, EPI_QKV, 64>(a, stream);
+      return hipErrorInvalidValue;
+    default:
+      return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace bs

@@ -1,0 +1,50 @@
+// bf16 GEMM on the gfx950 matrix cores with the layer's small operators fused
+// into the epilogues (BlendServe Section 4.1: the GEMMs - QKV generation, output
+// projection, FFN - are the compute-bound operators; Section 4.2: normalisation,
+// activation and position embedding are small next to them, so they ride along).
+#pragma once
+#include <stdint.h>
+#include <hip/hip_runtime.h>
+
+namespace bs {
+
+enum GemmEpilogue {
+  EPI_PLAIN = 0,      // C = A B^T
+  EPI_QKV = 1,        // row scale (RMSNorm), RoPE on q and k heads, q to its buffer, k and v into KV pages
+  EPI_RESID_NORM = 2, // x1 = resid + A B^T; also x1 * gain and partial row sums of x1^2 for the next norm
+  EPI_SWIGLU = 3,     // out = silu(s * gate) * (s * up), s = per-row RMSNorm scale
+  EPI_RESID = 4       // y = resid + A B^T
+};
+
+struct GemmArgs {
+  const uint16_t *A;  // [M, K] bf16 activations, row stride lda
+  const uint16_t *B;  // [N, K] bf16 weights (out-features major), row stride ldb
+  int M, N, K, lda, ldb;
+  uint16_t *C;        // output [M, ldc] bf16 (PLAIN, RESID*, SWIGLU)
+  int ldc;
+  const uint16_t *resid;  // [M, ldr] bf16
+  int ldr;
+  // RMSNorm of the A rows, applied as a per-row factor after the contraction:
+  // rstd = rsqrt(sum_p ss_part[p][m] / norm_dim + eps)
+  const float *ss_part;
+  int n_ss_part, ss_stride;
+  float norm_dim, eps;
+  // RESID_NORM extras
+  const uint16_t *gain;  // [N] bf16 gain of the next norm
+  uint16_t *C_gain;      // [M, ldc] x1 * gain
+  float *ss_out;         // [tiles_n * waves_n][ss_stride] partial row sums of x1^2
+  // SWIGLU: B holds F gate rows then F up rows; N = F
+  // QKV extras
+  int n_q_heads, n_kv_heads;
+  const float *rope_cos, *rope_sin;  // [max_pos][dh/2]
+  const int32_t *row_pos, *row_page, *row_slot;  // [M]
+  uint16_t *q_out;    // [M, Hq*dh]
+  uint16_t *kv_pool;  // pages: [2][Hkv][...]
+};
+
+// Picks a tile shape for the problem and launches on `stream`.  dh is the head
+// dimension (used by EPI_QKV only).  Returns hipSuccess or the launch error.
+hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream);
+int gemm_ss_parts(int n, int epilogue, int m, int dh);  // partial-sum slots a RESID_NORM launch over N columns writes
+
+}  // namespace bs

@@ -136,6 +136,9 @@ def assemble_batch(page_size: int,
 
     seqs:  (q_len, kv_len, leaf_node) per sequence, prefill segments first;
            members of a node must be contiguous and children follow parents.
+           A prefill segment that names a node only borrows the pages of that
+           node's root path as its cached prefix: it is not a member of the node
+           (node members are decode sequences) and its seq_leaf_node is -1.
     nodes: (parent, n_pages) in DFS pre-order.
     Logical pages are numbered node pages first, then private pages, and mapped
     to physical ids by a random permutation of the pool (identity if rng is
@@ -157,7 +160,7 @@ def assemble_batch(page_size: int,
     first = [n_seq] * n_nodes
     last = [-1] * n_nodes
     for s, (_, _, leaf) in enumerate(seqs):
-        nd = leaf
+        nd = leaf if s >= n_prefill else -1
         while nd >= 0:
             first[nd] = min(first[nd], s)
             last[nd] = max(last[nd], s)
@@ -200,7 +203,8 @@ def assemble_batch(page_size: int,
         node_page_start=_i32(node_page_start),
         node_page_ids=_i32(perm[np.arange(int(node_page_start[-1]))] if n_nodes else []),
         node_seq_first=_i32(first), node_seq_count=_i32(count),
-        seq_leaf_node=_i32([l for _, _, l in seqs]), n_pages=int(n_pages))
+        seq_leaf_node=_i32([(l if s >= n_prefill else -1) for s, (_, _, l) in enumerate(seqs)]),
+        n_pages=int(n_pages))
 
 
 def expand_batch(b: Batch) -> Tuple[Batch, np.ndarray]:
@@ -353,16 +357,9 @@ def batch_random(seed: int, n_prefill: int = 3, n_decode: int = 9, max_q: int = 
         # sequences that stop at an inner node go before those of its children
         return sorted(items, key=lambda s: (0,) + dfs_key(s[2]) if s[2] >= 0 else (1,))
 
-    pre = order([draw("p") for _ in range(n_prefill)])
+    pre = [draw("p") for _ in range(n_prefill)]   # prefill chunks borrow prefix pages, in any order
     dec = order([draw("d") for _ in range(n_decode)])
-    # a node's run must be contiguous over the whole sequence list: give prefill and
-    # decode sequences disjoint node sets by cloning the forest for the prefill side
-    off = len(nodes)
-    nodes2 = nodes + [((p + off) if p >= 0 else -1, n) for p, n in nodes]
-    pre = [(q, k, (l + off) if l >= 0 else -1) for q, k, l in pre]
-    # DFS pre-order requires each node list to be ordered; both halves already are
-    b = assemble_batch(page_size, pre + dec, n_prefill, nodes2, rng)
-    return b
+    return assemble_batch(page_size, pre + dec, n_prefill, nodes, rng)
 
 
 # ----------------------------------------------------------------------------

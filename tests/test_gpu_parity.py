@@ -1,0 +1,229 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, at sizes the
+oracle finishes in seconds (several tiles and ragged tails included).
+
+Tolerances (north star of the build): max relative error 2e-2, taken as
+max|gpu - ref| / max|ref| over a tensor, and mean absolute error 1e-3 with the
+reference rounded to bfloat16 (the output's storage type).  Integer work (page
+and slot of every appended row, which pool elements change) is compared exactly.
+"""
+import numpy as np
+import pytest
+
+from oracle import layer as O
+from paper_2411_16102_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+MAXREL = 2e-2
+MAE = 1e-3
+
+
+def errs(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    maxrel = float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30))
+    ref_b = W.round_to_bf16(ref.astype(np.float32)).astype(np.float64)
+    mae = float(np.mean(np.abs(got - ref_b)))
+    return maxrel, mae
+
+
+def to_np(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def run_step(lib, shape, batch, tens, flags=0):
+    import torch
+    layer = lib.Layer(shape, device=0)
+    dev = layer.upload(tens, batch)
+    y = layer.blend_step(dev, batch, flags=flags)
+    torch.cuda.synchronize()
+    k, v = layer.unpack_pool(dev.kv_pool, dev.n_pages)
+    return to_np(y), to_np(k), to_np(v), layer
+
+
+def check_step(lib, shape, batch, tens, flags=0, mae_tol=MAE):
+    ref = O.layer_step(shape, tens, batch)
+    y, k, v, layer = run_step(lib, shape, batch, tens, flags)
+    maxrel, mae = errs(y, ref["y"])
+    print("rows=%d maxrel=%.3e mae=%.3e" % (batch.n_rows, maxrel, mae))
+    assert np.isfinite(y).all()
+    assert maxrel <= MAXREL and mae <= mae_tol, (maxrel, mae)
+    # KV append: exactly the destination slots change, and they hold k, v of the rows
+    k0 = W.bf16_bits_to_f32(tens.k_pool).astype(np.float64)
+    v0 = W.bf16_bits_to_f32(tens.v_pool).astype(np.float64)
+    written = np.zeros(k0.shape[:2], dtype=bool)
+    written[ref["dest"][:, 0], ref["dest"][:, 1]] = True
+    assert np.array_equal(k[~written], k0[~written]), "a slot outside the append destinations changed (K)"
+    assert np.array_equal(v[~written], v0[~written]), "a slot outside the append destinations changed (V)"
+    kn = k[ref["dest"][:, 0], ref["dest"][:, 1]]
+    vn = v[ref["dest"][:, 0], ref["dest"][:, 1]]
+    mr_k, mae_k = errs(kn, ref["k_new"])
+    mr_v, mae_v = errs(vn, ref["v_new"])
+    assert mr_k <= MAXREL and mr_v <= MAXREL and mae_k <= 2 * MAE and mae_v <= 2 * MAE, (mr_k, mae_k, mr_v, mae_v)
+    pg, sl = layer.resolve_rows(batch)
+    assert np.array_equal(pg, ref["dest"][:, 0]) and np.array_equal(sl, ref["dest"][:, 1])
+    return y, ref
+
+
+# ---------------------------------------------------------------------------
+# stand-alone operators
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("m,n,k", [(136, 512, 256), (300, 264, 688), (1, 8, 8), (1030, 1544, 520), (2048, 1024, 512)])
+def test_gemm_nt(lib, m, n, k):
+    import torch
+    rng = np.random.default_rng(m + n + k)
+    a = W.round_to_bf16(rng.standard_normal((m, k), dtype=np.float32))
+    b = W.round_to_bf16(rng.standard_normal((n, k), dtype=np.float32) * 0.05)
+    layer = lib.Layer(W.TINY, device=0)
+    ta = torch.from_numpy(a).cuda().to(torch.bfloat16)
+    tb = torch.from_numpy(b).cuda().to(torch.bfloat16)
+    c = to_np(layer.gemm_nt(ta, tb))
+    ref = a.astype(np.float64) @ b.astype(np.float64).T
+    maxrel, mae = errs(c, ref)
+    # a bf16 result is within half an ulp (2^-9 relative) of the exact value plus fp32 accumulation error
+    assert np.max(np.abs(c - ref) / (np.abs(ref) + 1e-3 * np.max(np.abs(ref)))) < 6e-3
+    assert maxrel < 4e-3
+
+
+def attention_reference(shape, batch, q, k_pool, v_pool):
+    out = np.zeros((batch.n_rows, shape.n_q_heads * shape.head_dim))
+    for s in range(batch.n_seq):
+        r0, r1 = int(batch.row_start[s]), int(batch.row_start[s + 1])
+        L = int(batch.kv_len[s])
+        K, V = O.gather_kv(batch, s, L, k_pool, v_pool)
+        o = O.attention(q[r0:r1].reshape(r1 - r0, shape.n_q_heads, shape.head_dim), K, V, L - (r1 - r0))
+        out[r0:r1] = o.reshape(r1 - r0, -1)
+    return out
+
+
+@pytest.mark.parametrize("shape", [W.LayerShape(256, 4, 2, 64, 688), W.LayerShape(512, 8, 2, 128, 256),
+                                   W.LayerShape(512, 8, 1, 128, 256), W.LayerShape(256, 4, 4, 64, 256)])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_attention_alone(lib, shape, seed):
+    import torch
+    batch = W.batch_random(seed, n_prefill=4, n_decode=40, max_q=100, max_ctx=700, n_roots=3)
+    tens = W.make_tensors(shape, batch, seed)
+    rng = np.random.default_rng(seed)
+    q = W.round_to_bf16(rng.standard_normal((batch.n_rows, shape.n_q_heads * shape.head_dim), dtype=np.float32))
+    layer = lib.Layer(shape, device=0)
+    layer.set_chunk_pages(4)  # several chunks per node and per tail
+    pool = layer.pack_pool(tens.k_pool, tens.v_pool)
+    tq = torch.from_numpy(q).cuda().to(torch.bfloat16)
+    out = to_np(layer.attention(batch, tq, pool, batch.n_pages))
+    ref = attention_reference(shape, batch, q.astype(np.float64), tens.k_pool, tens.v_pool)
+    maxrel, mae = errs(out, ref)
+    print("attention maxrel=%.3e mae=%.3e" % (maxrel, mae))
+    assert maxrel <= MAXREL and mae <= 2 * MAE
+
+
+def test_attention_ignores_stale_slots(lib):
+    # slots past kv_len in the last page hold NaN bit patterns: they must never reach the output
+    import torch
+    shape = W.LayerShape(256, 4, 2, 64, 688)
+    batch = W.assemble_batch(16, [(5, 21, -1), (1, 35, -1), (1, 17, -1)], 1, [], None)
+    tens = W.make_tensors(shape, batch, 3)
+    kp, vp = tens.k_pool.copy(), tens.v_pool.copy()
+    for s in range(batch.n_seq):
+        L = int(batch.kv_len[s])
+        pg = int(batch.page_ids[int(batch.page_start[s]) + (L - 1) // 16])
+        kp[pg, L % 16:] = 0x7FC0 if L % 16 else kp[pg, L % 16:]
+        vp[pg, L % 16:] = 0x7FC0 if L % 16 else vp[pg, L % 16:]
+    rng = np.random.default_rng(0)
+    q = W.round_to_bf16(rng.standard_normal((batch.n_rows, 256), dtype=np.float32))
+    layer = lib.Layer(shape, device=0)
+    pool = layer.pack_pool(kp, vp)
+    out = to_np(layer.attention(batch, torch.from_numpy(q).cuda().to(torch.bfloat16), pool, batch.n_pages))
+    assert np.isfinite(out).all()
+    ref = attention_reference(shape, batch, q.astype(np.float64), tens.k_pool, tens.v_pool)
+    assert errs(out, ref)[0] <= MAXREL
+
+
+# ---------------------------------------------------------------------------
+# the whole step
+# ---------------------------------------------------------------------------
+def test_tiny_config(lib):
+    batch = W.batch_tiny(0)
+    tens = W.make_tensors(W.TINY, batch, 0)
+    check_step(lib, W.TINY, batch, tens)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+@pytest.mark.parametrize("flags", [0, 1])
+def test_random_batches_tiny_shape(lib, seed, flags):
+    batch = W.batch_random(seed, n_prefill=3, n_decode=20, max_q=90, max_ctx=400, n_roots=2)
+    tens = W.make_tensors(W.TINY, batch, seed, gains="random")
+    check_step(lib, W.TINY, batch, tens, flags)
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_random_batches_head_dim_128(lib, seed):
+    shape = W.LayerShape(512, 8, 2, 128, 1288)
+    batch = W.batch_random(10 + seed, n_prefill=4, n_decode=30, max_q=150, max_ctx=600, n_roots=3)
+    tens = W.make_tensors(shape, batch, seed, gains="random")
+    check_step(lib, shape, batch, tens, mae_tol=2 * MAE)
+
+
+def test_many_rows_use_large_tiles(lib):
+    # enough rows for the 256x256-tile instances, ragged in every dimension
+    shape = W.LayerShape(1024, 8, 2, 128, 2056)
+    batch = W.assemble_batch(16, [(700, 700, -1), (391, 500, -1)] + [(1, 200 + 7 * i, -1) for i in range(50)], 2,
+                             [], np.random.default_rng(5))
+    tens = W.make_tensors(shape, batch, 5)
+    check_step(lib, shape, batch, tens, mae_tol=3 * MAE)
+
+
+def test_decode_only_and_prefill_only(lib):
+    for batch in (W.batch_decode_only(33, 130, seed=2), W.batch_prefill_only(3, 75, seed=2)):
+        tens = W.make_tensors(W.TINY, batch, 2)
+        check_step(lib, W.TINY, batch, tens)
+
+
+def test_shared_and_expanded_kv_agree(lib):
+    batch = W.batch_random(21, n_prefill=2, n_decode=24, max_ctx=300, n_roots=3)
+    tens = W.make_tensors(W.TINY, batch, 21)
+    y, _ = check_step(lib, W.TINY, batch, tens)
+    e, src = W.expand_batch(batch)
+    te = W.make_tensors(W.TINY, batch, 21)
+    te.k_pool = tens.k_pool[np.maximum(src, 0)]
+    te.v_pool = tens.v_pool[np.maximum(src, 0)]
+    y2, _, _, _ = run_step(lib, W.TINY, e, te)
+    # same math, different grouping of the softmax partials: equal up to bf16 rounding of the output
+    assert np.max(np.abs(y - y2)) / np.max(np.abs(y)) < 1e-2
+    assert np.mean(np.abs(y - y2)) < MAE
+
+
+def test_overlap_mode_matches_serial(lib):
+    batch = W.batch_random(4, n_prefill=4, n_decode=30, max_q=120, max_ctx=500)
+    tens = W.make_tensors(W.TINY, batch, 4)
+    y0, _, _, _ = run_step(lib, W.TINY, batch, tens, 0)
+    y1, _, _, _ = run_step(lib, W.TINY, batch, tens, 1)
+    assert np.array_equal(y0, y1)
+
+
+def test_repeated_calls_and_growing_workspace(lib):
+    import torch
+    layer = lib.Layer(W.TINY, device=0)
+    for seed, (npf, ndec) in enumerate([(1, 4), (3, 40), (2, 9)]):
+        batch = W.batch_random(30 + seed, n_prefill=npf, n_decode=ndec, max_q=200, max_ctx=300)
+        tens = W.make_tensors(W.TINY, batch, seed)
+        dev = layer.upload(tens, batch)
+        y = layer.blend_step(dev, batch)
+        torch.cuda.synchronize()
+        ref = O.layer_step(W.TINY, tens, batch)["y"]
+        maxrel, mae = errs(to_np(y), ref)
+        assert maxrel <= MAXREL and mae <= MAE
+
+
+def test_malformed_batch_is_an_error_code_on_the_gpu_path(lib):
+    batch = W.batch_tiny(0)
+    tens = W.make_tensors(W.TINY, batch, 0)
+    layer = lib.Layer(W.TINY, device=0)
+    dev = layer.upload(tens, batch)
+    bad = batch.copy()
+    bad.page_ids[0] = batch.n_pages + 5
+    with pytest.raises(lib.BlendStepError) as ei:
+        layer.blend_step(dev, bad)
+    assert ei.value.code == -1
+    # the context still works afterwards
+    y = layer.blend_step(dev, batch)
+    assert np.isfinite(to_np(y)).all()
