@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Throughput of one blended decoder-layer step on one MI355X.
+
+A "step" is one call of bs_blend_step: descriptor validation and upload, RMSNorm,
+QKV GEMM with RoPE and KV append, prefill and prefix-aware decode attention,
+output projection, SwiGLU FFN and both residuals, over one seeded synthetic batch
+already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--flags 0|1]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16 = 2.5e15  # dense bf16 MFMA, FLOP/s (MI355X datasheet)
+PEAK_HBM = 8.0e12        # HBM3E, B/s
+
+
+def cpu_baseline(shape, batch, tens, target_flops=1.2e12):
+    """The oracle, as it stands, on a bounded sample of the same batch: whole
+    prefill segments and evenly spaced decode sequences in the batch's own
+    prefill:decode proportion."""
+    import numpy as np
+    from oracle import layer as oracle_layer
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    q_len = batch.q_len()
+    n_pre_rows = int(batch.row_start[batch.n_prefill])
+    target_rows = target_flops / (2.0 * shape.matrix_params)   # about 10-20 s of float64 BLAS on 16 cores
+    frac = min(1.0, target_rows / max(1, batch.n_rows))
+    rows = []
+    pre_target = frac * n_pre_rows
+    took = 0
+    for s in range(batch.n_prefill):
+        if took >= pre_target:
+            break
+        rows.extend(range(int(batch.row_start[s]), int(batch.row_start[s + 1])))
+        took += int(q_len[s])
+    n_dec = batch.n_seq - batch.n_prefill
+    dec_take = int(round(frac * n_dec)) if n_dec else 0
+    if n_dec and dec_take == 0:
+        dec_take = 1
+    if dec_take:
+        pick = np.unique(np.linspace(0, n_dec - 1, dec_take).astype(int))
+        rows.extend(int(batch.row_start[batch.n_prefill + i]) for i in pick)
+    t0 = time.perf_counter()
+    oracle_layer.layer_step(shape, tens, batch, rows=rows)
+    dt = time.perf_counter() - t0
+    return {"value": len(rows) / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d of %d rows (%d prefill rows in whole segments + %d decode sequences), %.1f s, float64 numpy"
+                      % (len(rows), batch.n_rows, took, len(rows) - took, dt)}, rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="blended_8b")
+    ap.add_argument("--flags", type=int, default=-1, help="0 serial, 1 overlap, -1 pick the faster in warm-up")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk-pages", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by independent replicas, "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2411_16102_amd as pkg
+    from paper_2411_16102_amd import workloads as W
+
+    def note(msg):
+        print("[bench] " + msg, file=sys.stderr, flush=True)
+
+    lib = pkg.load()
+    note("generating inputs for " + args.workload)
+    shape, make_batch = W.CONFIGS[args.workload]
+    batch = make_batch(seed=args.seed)
+    work = W.work_of(shape, batch)
+    tens = W.make_tensors(shape, batch, args.seed)
+    layer = lib.Layer(shape, device=0)
+    if args.chunk_pages:
+        layer.set_chunk_pages(args.chunk_pages)
+    note("uploading")
+    dev = layer.upload(tens, batch)
+    desc = lib.marshal_batch(batch)
+    note("timing")
+    y = torch.empty_like(dev.x)
+
+    def run(n, flags):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            layer.blend_step(dev, batch, flags=flags, y=y, desc=desc)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / max(1, n)
+
+    flags = args.flags
+    if flags < 0:
+        run(max(2, args.warmup // 2), 0)
+        t_serial = run(max(3, args.warmup // 2), 0)
+        run(max(2, args.warmup // 2), 1)
+        t_overlap = run(max(3, args.warmup // 2), 1)
+        flags = 1 if t_overlap < t_serial else 0
+    run(args.warmup, flags)
+    sec = run(args.steps, flags)
+
+    # per-kernel durations: the same loop again with HIP events around every kernel class
+    layer.profile(True)
+    run(args.steps, flags)
+    prof = layer.profile_read()
+    layer.profile(False)
+    kernels = {k: {"ms": (ms / n if n else 0.0), "launches_per_step": n / args.steps} for k, (ms, n) in prof.items()}
+
+    T, d, f = batch.n_rows, shape.d_model, shape.d_ffn
+    gu_flops = 2.0 * T * d * 2 * f
+    gu_launches = max(1, prof["gemm_gate_up"][1])
+    gu_ms = prof["gemm_gate_up"][0] / gu_launches            # average launch duration
+    gu_flops_per_launch = gu_flops * args.steps / gu_launches
+    t_flop = work["flops"] / PEAK_MFMA_BF16
+    t_byte = work["bytes_once"] / PEAK_HBM
+    bound = "mfma" if t_flop >= t_byte else "hbm"
+    if bound == "mfma":
+        roofline = {"bound": "mfma", "kernel": "gemm_gate_up (SwiGLU epilogue)",
+                    "achieved": gu_flops_per_launch / (gu_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_BF16 / 1e12,
+                    "unit": "TFLOP/s", "traffic": None}
+    else:
+        dec_ms = prof["attn_decode"][0] / max(1, prof["attn_decode"][1])
+        kv_bytes = work["kv_tokens_once"] * shape.kv_bytes_per_token
+        roofline = {"bound": "hbm", "kernel": "decode_attn (paged, prefix-aware)",
+                    "achieved": kv_bytes / (dec_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                    "traffic": None}
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+
+    out = {
+        "metric": "blended-step tokens/s per layer", "value": T / sec, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "rows": T, "prefill_rows": int(batch.row_start[batch.n_prefill]),
+                   "decode_seqs": batch.n_seq - batch.n_prefill, "prefix_nodes": batch.n_nodes,
+                   "d_model": d, "n_q_heads": shape.n_q_heads, "n_kv_heads": shape.n_kv_heads,
+                   "head_dim": shape.head_dim, "d_ffn": f, "seed": args.seed,
+                   "schedule": "overlap" if flags else "serial"},
+        "step_roofline": {"flops": work["flops"], "bytes": work["bytes_once"], "bytes_if_expanded": work["bytes_expanded"],
+                          "t_flop_us": t_flop * 1e6, "t_byte_us": t_byte * 1e6, "bound": bound,
+                          "frac": max(t_flop, t_byte) / sec},
+        "roofline": roofline,
+        "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
+    }
+    if not args.no_cpu_baseline:
+        note("timing the CPU oracle on a sample")
+        out["cpu_baseline"], _ = cpu_baseline(shape, batch, tens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

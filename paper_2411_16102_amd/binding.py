@@ -68,6 +68,9 @@ def raw():
     if _lib is None:
         if not os.path.exists(_SO):
             raise ImportError("%s is not built: run `python __graft_entry__.py` (hipcc, gfx950) first" % _SO)
+        # PyTorch ships its own HIP runtime; load it first so that this library binds
+        # to the same runtime instance (two runtimes in one process do not share a GPU)
+        import torch  # noqa: F401
         lib = C.CDLL(_SO)
         lib.bs_create.argtypes = [C.POINTER(LayerCfg), C.c_int, C.POINTER(C.c_void_p)]
         lib.bs_destroy.argtypes = [C.c_void_p]

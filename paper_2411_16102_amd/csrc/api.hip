@@ -42,8 +42,8 @@ struct bs_ctx {
   float *rope_cos = nullptr, *rope_sin = nullptr;
   // activations workspace
   int cap_rows = 0, ss2_parts = 0;
-  uint16_t *xg = nullptr, *qbuf = nullptr, *attn = nullptr, *x1 = nullptr, *xg2 = nullptr, *act = nullptr;
-  float *ss1 = nullptr, *ss2 = nullptr;
+  uint16_t *xg = nullptr, *qbuf = nullptr, *attn = nullptr, *xg2 = nullptr, *act = nullptr;
+  float *x1 = nullptr, *ss1 = nullptr, *ss2 = nullptr;
   long cap_slots = 0;
   float *part_acc = nullptr, *part_m = nullptr, *part_l = nullptr;
   // descriptor blob: pinned host ring and one device copy
@@ -475,7 +475,7 @@ int run_tail(bs_ctx *c, const bs_weights *w, const uint16_t *x, uint16_t *y, int
   GemmArgs o{};
   o.A = c->attn + (size_t)r0 * hd; o.lda = hd; o.B = (const uint16_t *)w->w_o; o.ldb = hd;
   o.M = rows; o.N = d; o.K = hd;
-  o.C = c->x1 + (size_t)r0 * d; o.ldc = d; o.resid = x + (size_t)r0 * d; o.ldr = d;
+  o.C32 = c->x1 + (size_t)r0 * d; o.ldc = d; o.resid = x + (size_t)r0 * d; o.ldr = d;
   o.gain = (const uint16_t *)w->g_ffn; o.C_gain = c->xg2 + (size_t)r0 * d;
   o.ss_out = c->ss2 + r0; o.ss_stride = c->cap_rows;
   SPAN(c, BS_K_GEMM_O, st, HIP_TRY(c, launch_gemm(o, EPI_RESID_NORM, g.head_dim, st)));
@@ -488,7 +488,7 @@ int run_tail(bs_ctx *c, const bs_weights *w, const uint16_t *x, uint16_t *y, int
   GemmArgs dn{};
   dn.A = c->act + (size_t)r0 * f; dn.lda = f; dn.B = (const uint16_t *)w->w_down; dn.ldb = f;
   dn.M = rows; dn.N = d; dn.K = f;
-  dn.C = y + (size_t)r0 * d; dn.ldc = d; dn.resid = c->x1 + (size_t)r0 * d; dn.ldr = d;
+  dn.C = y + (size_t)r0 * d; dn.ldc = d; dn.resid32 = c->x1 + (size_t)r0 * d; dn.ldr = d;
   SPAN(c, BS_K_GEMM_DOWN, st, HIP_TRY(c, launch_gemm(dn, EPI_RESID, g.head_dim, st)));
   return BS_OK;
 }

@@ -202,11 +202,17 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = acc[ni][mi][4 * q + e];
           if (EPI == EPI_RESID) {
-            const u32x2_t rr = *reinterpret_cast<const u32x2_t *>(a.resid + (size_t)m * a.ldr + n);
-            v[0] += __uint_as_float(rr.x << 16);
-            v[1] += __uint_as_float(rr.x & 0xFFFF0000u);
-            v[2] += __uint_as_float(rr.y << 16);
-            v[3] += __uint_as_float(rr.y & 0xFFFF0000u);
+            if (a.resid32) {
+              const f32x4_t rr = *reinterpret_cast<const f32x4_t *>(a.resid32 + (size_t)m * a.ldr + n);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] += rr[e];
+            } else {
+              const u32x2_t rr = *reinterpret_cast<const u32x2_t *>(a.resid + (size_t)m * a.ldr + n);
+              v[0] += __uint_as_float(rr.x << 16);
+              v[1] += __uint_as_float(rr.x & 0xFFFF0000u);
+              v[2] += __uint_as_float(rr.y << 16);
+              v[3] += __uint_as_float(rr.y & 0xFFFF0000u);
+            }
           }
           store_bf16x4(a.C + (size_t)m * a.ldc + n, v[0], v[1], v[2], v[3]);
         }
@@ -237,11 +243,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
             g[2] = __uint_as_float(gg.y << 16);
             g[3] = __uint_as_float(gg.y & 0xFFFF0000u);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              v[e] = round_bf16(v[e]);  // x1 as it is stored; the norm sees the stored value
-              ss += v[e] * v[e];
-            }
-            store_bf16x4(a.C + (size_t)m * a.ldc + n, v[0], v[1], v[2], v[3]);
+            for (int e = 0; e < 4; ++e) ss += v[e] * v[e];
+            // x1 stays in fp32 for the second residual add; the next GEMM reads bf16(x1 * gain)
+            *reinterpret_cast<f32x4_t *>(a.C32 + (size_t)m * a.ldc + n) = f32x4_t{v[0], v[1], v[2], v[3]};
             store_bf16x4(a.C_gain + (size_t)m * a.ldc + n, v[0] * g[0], v[1] * g[1], v[2] * g[2], v[3] * g[3]);
           }
       }

@@ -11,9 +11,9 @@ namespace bs {
 enum GemmEpilogue {
   EPI_PLAIN = 0,      // C = A B^T
   EPI_QKV = 1,        // row scale (RMSNorm), RoPE on q and k heads, q to its buffer, k and v into KV pages
-  EPI_RESID_NORM = 2, // x1 = resid + A B^T; also x1 * gain and partial row sums of x1^2 for the next norm
+  EPI_RESID_NORM = 2, // x1 = resid + A B^T in fp32; also bf16(x1 * gain) and partial row sums of x1^2 for the next norm
   EPI_SWIGLU = 3,     // out = silu(s * gate) * (s * up), s = per-row RMSNorm scale
-  EPI_RESID = 4       // y = resid + A B^T
+  EPI_RESID = 4       // y = resid + A B^T (resid in bf16, or in fp32 when resid32 is set)
 };
 
 struct GemmArgs {
@@ -23,6 +23,7 @@ struct GemmArgs {
   uint16_t *C;        // output [M, ldc] bf16 (PLAIN, RESID*, SWIGLU)
   int ldc;
   const uint16_t *resid;  // [M, ldr] bf16
+  const float *resid32;   // [M, ldr] fp32 (EPI_RESID only; takes precedence)
   int ldr;
   // RMSNorm of the A rows, applied as a per-row factor after the contraction:
   // rstd = rsqrt(sum_p ss_part[p][m] / norm_dim + eps)
@@ -31,7 +32,8 @@ struct GemmArgs {
   float norm_dim, eps;
   // RESID_NORM extras
   const uint16_t *gain;  // [N] bf16 gain of the next norm
-  uint16_t *C_gain;      // [M, ldc] x1 * gain
+  float *C32;            // [M, ldc] x1 in fp32
+  uint16_t *C_gain;      // [M, ldc] bf16(x1 * gain)
   float *ss_out;         // [tiles_n * waves_n][ss_stride] partial row sums of x1^2
   // SWIGLU: B holds F gate rows then F up rows; N = F
   // QKV extras
