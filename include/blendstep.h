@@ -159,7 +159,7 @@ int bs_profile_enable(bs_ctx *ctx, int on);
 int bs_profile_read(bs_ctx *ctx, int which, double *total_ms, int64_t *launches);
 int bs_profile_reset(bs_ctx *ctx);
 
-/* Tuning knob: pages per chunk of decode-attention work (even, 2..4096; default 32).
+/* Tuning knob: pages per chunk of decode-attention work (even, 2..64; default 32).
  * Smaller chunks give more parallelism and more partial states to merge. */
 int bs_set_chunk_pages(bs_ctx *ctx, int32_t pages);
 

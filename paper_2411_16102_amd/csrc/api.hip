@@ -30,7 +30,7 @@ struct Plan {
        off_part_start = 0, off_pf_work = 0, off_items = 0, off_pages = 0, total_ints = 0;
   long total_node_pages = 0, n_slots = 0;
   int n_pf_work = 0;
-  int item_base[3] = {0, 0, 0}, item_count[3] = {0, 0, 0};  // classes of 4, 2, 1 blocks of 16 query rows
+  int n_items = 0;
 };
 
 }  // namespace
@@ -43,7 +43,7 @@ struct bs_ctx {
   // activations workspace
   int cap_rows = 0, ss2_parts = 0;
   uint16_t *xg = nullptr, *qbuf = nullptr, *attn = nullptr, *xg2 = nullptr, *act = nullptr;
-  float *x1 = nullptr, *ss1 = nullptr, *ss2 = nullptr;
+  float *x1 = nullptr, *rstd1 = nullptr, *rstd2 = nullptr, *ss2 = nullptr;
   long cap_slots = 0;
   float *part_acc = nullptr, *part_m = nullptr, *part_l = nullptr;
   // descriptor blob: pinned host ring and one device copy
@@ -56,7 +56,7 @@ struct bs_ctx {
   int ring_pos = 0;
   // host scratch reused across calls
   std::vector<int32_t> refcount, path_pages, path_chunks, members, blob;
-  std::vector<DecodeItem> items[3];
+  std::vector<DecodeItem> items;
   std::vector<int32_t> pf_work;
   // overlap
   hipStream_t side = nullptr;
@@ -112,7 +112,8 @@ int ensure_rows(bs_ctx *c, int rows) {
   if ((rc = dev_alloc(c, &c->x1, (size_t)cap * g.d_model))) return rc;
   if ((rc = dev_alloc(c, &c->xg2, (size_t)cap * g.d_model))) return rc;
   if ((rc = dev_alloc(c, &c->act, (size_t)cap * g.d_ffn))) return rc;
-  if ((rc = dev_alloc(c, &c->ss1, (size_t)cap))) return rc;
+  if ((rc = dev_alloc(c, &c->rstd1, (size_t)cap))) return rc;
+  if ((rc = dev_alloc(c, &c->rstd2, (size_t)cap))) return rc;
   c->ss2_parts = ((g.d_model + 255) / 256) * 4;  // covers both tile shapes of the projection
   if ((rc = dev_alloc(c, &c->ss2, (size_t)cap * c->ss2_parts))) return rc;
   c->cap_rows = cap;
@@ -269,8 +270,8 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
 
   // chunk counts along each node's root path (path_pages was filled by validate)
   c->path_chunks.assign((size_t)nn, 0);
-  for (int i = 0; i < 3; ++i) c->items[i].clear();
-  const int max_members = std::max(1, 64 / grp);
+  c->items.clear();
+  const int max_members = std::max(1, 16 / grp);  // 16 query rows per work item
   for (int n = 0; n < nn; ++n) {
     const int par = b->node_parent[n];
     const int np = b->node_page_start[n + 1] - b->node_page_start[n];
@@ -282,8 +283,6 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
     const int n_groups = (cnt + max_members - 1) / max_members;
     for (int g = 0; g < n_groups; ++g) {
       const int lo = (int)((long)cnt * g / n_groups), hi = (int)((long)cnt * (g + 1) / n_groups);
-      const int rows = (hi - lo) * grp;
-      const int cls = rows > 32 ? 0 : (rows > 16 ? 1 : 2);
       for (int k = 0; k < nch; ++k) {
         DecodeItem it{};
         it.page_off = b->node_page_start[n] + k * ch;
@@ -291,7 +290,7 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
         it.seq_first = b->node_seq_first[n] + lo;
         it.n_members = hi - lo;
         it.slot_off = above + k;
-        c->items[cls].push_back(it);
+        c->items.push_back(it);
       }
     }
   }
@@ -313,7 +312,6 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
   }
   int32_t *part_start = &blob[p.off_part_start];
   part_start[0] = 0;
-  const int tail_cls = grp > 16 ? 0 : 2;
   for (int s = 0; s < b->n_seq; ++s) {
     int slots = 0;
     if (s >= b->n_prefill) {
@@ -330,7 +328,7 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
         it.seq_first = s;
         it.n_members = 1;
         it.slot_off = above + k;
-        c->items[tail_cls].push_back(it);
+        c->items.push_back(it);
       }
       slots = above + nch;
     }
@@ -358,8 +356,11 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
   std::stable_sort(order.begin(), order.end(), [](const auto &x, const auto &y) { return x.first < y.first; });
   p.n_pf_work = (int)order.size();
   p.off_items = p.off_pf_work + 2L * p.n_pf_work;
-  long n_items = 0;
-  for (int i = 0; i < 3; ++i) { p.item_base[i] = (int)n_items; p.item_count[i] = (int)c->items[i].size(); n_items += p.item_count[i]; }
+  // longest chunks first: the many short tail chunks then fill the gaps at the end of the launch
+  std::stable_sort(c->items.begin(), c->items.end(),
+                   [](const DecodeItem &x, const DecodeItem &y) { return x.n_tokens > y.n_tokens; });
+  const long n_items = (long)c->items.size();
+  p.n_items = (int)n_items;
   p.off_pages = p.off_items + 8 * n_items;
   p.total_ints = p.off_pages + p.total_node_pages + n_tab;
   blob.resize((size_t)p.total_ints);
@@ -367,9 +368,7 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
     blob[p.off_pf_work + 2 * i] = order[i].second.first;
     blob[p.off_pf_work + 2 * i + 1] = order[i].second.second;
   }
-  for (int i = 0; i < 3; ++i)
-    if (p.item_count[i])
-      std::memcpy(&blob[p.off_items + 8L * p.item_base[i]], c->items[i].data(), sizeof(DecodeItem) * p.item_count[i]);
+  if (n_items) std::memcpy(&blob[p.off_items], c->items.data(), sizeof(DecodeItem) * n_items);
   if (p.total_node_pages) std::memcpy(&blob[p.off_pages], b->node_page_ids, sizeof(int32_t) * p.total_node_pages);
   if (n_tab) std::memcpy(&blob[p.off_pages + p.total_node_pages], b->page_ids, sizeof(int32_t) * n_tab);
   return BS_OK;
@@ -447,16 +446,7 @@ int run_decode_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, 
   a.row_start = c->d_blob + p.off_row_start; a.part_start = c->d_blob + p.off_part_start;
   a.q = q; a.kv_pool = pool;
   a.part_acc = c->part_acc; a.part_m = c->part_m; a.part_l = c->part_l;
-  static const int nqb_of[3] = {4, 2, 1};
-  {
-    bs_ctx::Span sp{};
-    int rc = span_begin(c, BS_K_ATTN_DECODE, st, sp);
-    if (rc) return rc;
-    for (int i = 0; i < 3; ++i)
-      if (p.item_count[i]) HIP_TRY(c, launch_decode_attn(a, p.item_base[i], p.item_count[i], nqb_of[i], st));
-    rc = span_end(c, BS_K_ATTN_DECODE, st, sp);
-    if (rc) return rc;
-  }
+  SPAN(c, BS_K_ATTN_DECODE, st, HIP_TRY(c, launch_decode_attn(a, p.n_items, st)));
   MergeArgs m;
   m.s = a.s; m.n_prefill = p.n_prefill; m.n_decode = p.n_decode;
   m.row_start = a.row_start; m.part_start = a.part_start;
@@ -478,12 +468,15 @@ int run_tail(bs_ctx *c, const bs_weights *w, const uint16_t *x, uint16_t *y, int
   o.C32 = c->x1 + (size_t)r0 * d; o.ldc = d; o.resid = x + (size_t)r0 * d; o.ldr = d;
   o.gain = (const uint16_t *)w->g_ffn; o.C_gain = c->xg2 + (size_t)r0 * d;
   o.ss_out = c->ss2 + r0; o.ss_stride = c->cap_rows;
-  SPAN(c, BS_K_GEMM_O, st, HIP_TRY(c, launch_gemm(o, EPI_RESID_NORM, g.head_dim, st)));
+  SPAN(c, BS_K_GEMM_O, st, {
+    HIP_TRY(c, launch_gemm(o, EPI_RESID_NORM, g.head_dim, st));
+    HIP_TRY(c, launch_rstd_finalize(c->ss2 + r0, parts, c->cap_rows, c->rstd2 + r0, rows, d, g.rms_eps, st));
+  });
   GemmArgs u{};
   u.A = c->xg2 + (size_t)r0 * d; u.lda = d; u.B = (const uint16_t *)w->w_gate_up; u.ldb = d;
   u.M = rows; u.N = f; u.K = d;
   u.C = c->act + (size_t)r0 * f; u.ldc = f;
-  u.ss_part = c->ss2 + r0; u.n_ss_part = parts; u.ss_stride = c->cap_rows; u.norm_dim = (float)d; u.eps = g.rms_eps;
+  u.rstd = c->rstd2 + r0;
   SPAN(c, BS_K_GEMM_GATE_UP, st, HIP_TRY(c, launch_gemm(u, EPI_SWIGLU, g.head_dim, st)));
   GemmArgs dn{};
   dn.A = c->act + (size_t)r0 * f; dn.lda = f; dn.B = (const uint16_t *)w->w_down; dn.ldb = f;
@@ -546,7 +539,7 @@ void bs_destroy(bs_ctx *c) {
   (void)hipSetDevice(c->device);
   (void)hipDeviceSynchronize();
   for (void *p : {(void *)c->rope_cos, (void *)c->rope_sin, (void *)c->xg, (void *)c->qbuf, (void *)c->attn, (void *)c->x1,
-                  (void *)c->xg2, (void *)c->act, (void *)c->ss1, (void *)c->ss2, (void *)c->part_acc, (void *)c->part_m,
+                  (void *)c->xg2, (void *)c->act, (void *)c->rstd1, (void *)c->rstd2, (void *)c->ss2, (void *)c->part_acc, (void *)c->part_m,
                   (void *)c->part_l, (void *)c->d_blob})
     if (p) (void)hipFree(p);
   for (int i = 0; i < RING; ++i) {
@@ -627,11 +620,11 @@ int bs_blend_step(bs_ctx *c, const bs_weights *w, const bs_batch *b, const void 
 
   const bs_layer_cfg &g = c->cfg;
   const int T = p.n_rows, d = g.d_model, hd = g.n_q_heads * g.head_dim;
-  SPAN(c, BS_K_PREP, st, HIP_TRY(c, launch_norm_prep(x, (const uint16_t *)w->g_attn, c->xg, c->ss1, T, d, st)));
+  SPAN(c, BS_K_PREP, st, HIP_TRY(c, launch_norm_prep(x, (const uint16_t *)w->g_attn, c->xg, c->rstd1, T, d, g.rms_eps, st)));
   GemmArgs q{};
   q.A = c->xg; q.lda = d; q.B = (const uint16_t *)w->w_qkv; q.ldb = d;
   q.M = T; q.N = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim; q.K = d;
-  q.ss_part = c->ss1; q.n_ss_part = 1; q.ss_stride = c->cap_rows; q.norm_dim = (float)d; q.eps = g.rms_eps;
+  q.rstd = c->rstd1;
   q.n_q_heads = g.n_q_heads; q.n_kv_heads = g.n_kv_heads;
   q.rope_cos = c->rope_cos; q.rope_sin = c->rope_sin;
   q.row_pos = c->d_blob + p.off_row_pos; q.row_page = c->d_blob + p.off_row_page; q.row_slot = c->d_blob + p.off_row_slot;
@@ -735,7 +728,7 @@ int bs_profile_read(bs_ctx *c, int which, double *total_ms, int64_t *launches) {
 /* Tuning knob used by the benchmark sweeps: pages per decode-attention chunk. */
 int bs_set_chunk_pages(bs_ctx *c, int32_t pages) {
   if (!c) return BS_EINVAL;
-  if (pages < 2 || pages > 4096 || (pages & 1)) return fail(c, BS_EINVAL, "chunk_pages %d (even, 2..4096)", pages);
+  if (pages < 2 || pages > 64 || (pages & 1)) return fail(c, BS_EINVAL, "chunk_pages %d (even, 2..64)", pages);
   c->chunk_pages = pages;
   return BS_OK;
 }

@@ -49,18 +49,25 @@ __device__ __forceinline__ u32x2_t mask_tokens(u32x2_t v, int t0, int limit) {
 }
 
 // ------------------------------------------------------------------------------
-// decode attention: one wavefront per (item, KV head)
+// decode attention: one wavefront per (item, KV head), up to 16 query rows
 // ------------------------------------------------------------------------------
-template <int DH, int NQB>
-__global__ __launch_bounds__(256) void decode_attn_kernel(const DecodeArgs a, int item_base, int n_units) {
+// The online softmax keeps a per-row reference exponent m that only moves when a
+// new score exceeds it by more than TAU (in log2 units): probabilities are then
+// bounded by 2^TAU, which bf16 and the fp32 accumulators hold without loss, and
+// the accumulators are rescaled a few times per chunk instead of once per page.
+constexpr float TAU = 8.0f;
+
+template <int DH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_attn_kernel(const DecodeArgs a,
+                                                                                                     int n_units) {
   constexpr int KC = DH / 32;  // 32-wide chunks of the head dimension (QK^T contraction)
   constexpr int DB = DH / 16;  // 16-row blocks of the head dimension (PV output rows)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const int unit = xcd_contiguous(blockIdx.x, gridDim.x) * 4 + wave;
+  const int unit = blockIdx.x * 4 + wave;
   if (unit >= n_units) return;
   const int hkv = a.s.n_kv_heads, hq = a.s.n_q_heads, grp = hq / hkv;
-  const int item = item_base + unit / hkv;
+  const int item = unit / hkv;
   const int kvh = unit % hkv;
   const DecodeItem it = a.items[item];
   const int n_rows = it.n_members * grp;
@@ -68,45 +75,48 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const DecodeArgs a, in
   const int n_pg = (n_tok + 15) >> 4;
   const int jq = lane & 15, g4 = lane >> 4;
   const size_t tile = (size_t)16 * DH;
+  const float sc = a.s.scale_log2e;
 
   // query fragments: B operand of S^T = K Q^T; lane (jq, g4) holds Q[row jq][32c + 8 g4 ..+7]
-  bf16x8_t qf[NQB][KC];
-#pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    const int r = qb * 16 + jq;
-    const bool ok = r < n_rows;
-    const int seq = it.seq_first + (ok ? r / grp : 0);
-    const int head = kvh * grp + (ok ? r % grp : 0);
-    const uint16_t *p = a.q + (size_t)a.row_start[seq] * (hq * DH) + head * DH + 8 * g4;
+  bf16x8_t qf[KC];
+  const bool row_ok = jq < n_rows;
+  const int my_seq = it.seq_first + (row_ok ? jq / grp : 0);
+  const int my_head = kvh * grp + (row_ok ? jq % grp : 0);
+  {
+    const uint16_t *p = a.q + (size_t)a.row_start[my_seq] * (hq * DH) + my_head * DH + 8 * g4;
 #pragma unroll
     for (int c = 0; c < KC; ++c) {
       u32x4_t v = {0u, 0u, 0u, 0u};
-      if (ok) v = ld16(p + 32 * c);
-      qf[qb][c] = as_bf16x8(v);
+      if (row_ok) v = ld16(p + 32 * c);
+      qf[c] = as_bf16x8(v);
     }
   }
 
-  f32x4_t o[NQB][DB];
-  float m[NQB], l[NQB];
+  f32x4_t o[DB];
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    m[qb] = NEG_BIG;
-    l[qb] = 0.f;
-#pragma unroll
-    for (int db = 0; db < DB; ++db) o[qb][db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  }
+  for (int db = 0; db < DB; ++db) o[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m = NEG_BIG, l = 0.f;
 
-  const int32_t *pages = a.item_pages + it.page_off;
+  // The chunk's page ids sit in one register (lane i holds page i; chunks have at most
+  // 64 pages), so the loop never waits on a scalar memory load to form an address.
   const int n_pairs = (n_pg + 1) >> 1;
+  const int my_page = a.item_pages[it.page_off + (lane < n_pg ? lane : n_pg - 1)];
 
+  // One pair of pages (32 tokens) per step, two register sets in ping-pong: while one
+  // pair is being computed the other pair (16 KB per wavefront) is in flight, and the
+  // set just consumed is refilled at once.  Loads are unconditional (past the end they
+  // re-read the last pair, whose tokens are then all masked), which keeps the loop
+  // straight-line so that every wait covers exactly the loads it needs.
   struct Frags {
     u32x4_t k[2][KC];
     u32x2_t v0[DB], v1[DB];
   };
+  auto page_of = [&](int i) -> size_t {
+    return (size_t)__builtin_amdgcn_readlane(my_page, i < n_pg ? i : n_pg - 1);
+  };
   auto load = [&](int pr, Frags &f) {
-    const int i0 = 2 * pr;
-    const size_t p0 = pages[i0];
-    const size_t p1 = (i0 + 1 < n_pg) ? pages[i0 + 1] : p0;
+    const int i0 = 2 * (pr < n_pairs ? pr : n_pairs - 1);
+    const size_t p0 = page_of(i0), p1 = page_of(i0 + 1);
     const uint16_t *k0 = a.kv_pool + ((p0 * 2 + 0) * hkv + kvh) * tile + jq * DH + 8 * g4;
     const uint16_t *k1 = a.kv_pool + ((p1 * 2 + 0) * hkv + kvh) * tile + jq * DH + 8 * g4;
     const uint16_t *v0 = a.kv_pool + ((p0 * 2 + 1) * hkv + kvh) * tile + jq * 16 + 4 * g4;
@@ -124,91 +134,86 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(const DecodeArgs a, in
   };
   auto compute = [&](int pr, Frags &f) {
     const int tb = pr * 32;
-    const bool ragged = tb + 32 > n_tok;
-    if (ragged) {  // never let stale slots (possibly NaN bit patterns) meet a zero probability
+    const bool ragged = tb + 32 > n_tok;  // the last pair of a chunk, or a step past the end
+    f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[0][c]), qf[c], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[1][c]), qf[c], s1, 0, 0, 0);
+    }
+    float sv[8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      sv[r] = s0[r] * sc;
+      sv[4 + r] = s1[r] * sc;
+    }
+    if (ragged) {  // mask scores, and never let stale slots (possibly NaN bits) meet a zero probability
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (tb + 4 * g4 + r >= n_tok) sv[r] = NEG_BIG;
+        if (tb + 16 + 4 * g4 + r >= n_tok) sv[4 + r] = NEG_BIG;
+      }
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         f.v0[db] = mask_tokens(f.v0[db], tb + 4 * g4, n_tok);
         f.v1[db] = mask_tokens(f.v1[db], tb + 16 + 4 * g4, n_tok);
       }
     }
+    float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    if (__builtin_amdgcn_ballot_w64(mx > m + TAU) != 0) {  // wave-uniform: somebody's reference must move
+      const float m_new = fmaxf(m, mx);
+      const float alpha = fast_exp2(m - m_new);
+      m = m_new;
+      l *= alpha;
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+      for (int db = 0; db < DB; ++db) o[db] *= alpha;
+    }
+    float ps = 0.f;
 #pragma unroll
-      for (int c = 0; c < KC; ++c) {
-        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[0][c]), qf[qb][c], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[1][c]), qf[qb][c], s1, 0, 0, 0);
-      }
-      float sv[8];
+    for (int r = 0; r < 8; ++r) {
+      sv[r] = fast_exp2(sv[r] - m);
+      ps += sv[r];
+    }
+    l += ps;
+    u32x4_t pw;
+    pw.x = pack_bf16x2(sv[0], sv[1]);
+    pw.y = pack_bf16x2(sv[2], sv[3]);
+    pw.z = pack_bf16x2(sv[4], sv[5]);
+    pw.w = pack_bf16x2(sv[6], sv[7]);
+    const bf16x8_t pf = as_bf16x8(pw);
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        sv[r] = (tb + 4 * g4 + r < n_tok) ? s0[r] * a.s.scale_log2e : NEG_BIG;
-        sv[4 + r] = (tb + 16 + 4 * g4 + r < n_tok) ? s1[r] * a.s.scale_log2e : NEG_BIG;
-      }
-      float mx = sv[0];
-#pragma unroll
-      for (int r = 1; r < 8; ++r) mx = fmaxf(mx, sv[r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m[qb], mx);
-      const float alpha = exp2f(m[qb] - m_new);
-      m[qb] = m_new;
-      float ps = 0.f;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        sv[r] = exp2f(sv[r] - m_new);
-        ps += sv[r];
-      }
-      l[qb] = l[qb] * alpha + ps;
-      u32x4_t pw;
-      pw.x = pack_bf16x2(sv[0], sv[1]);
-      pw.y = pack_bf16x2(sv[2], sv[3]);
-      pw.z = pack_bf16x2(sv[4], sv[5]);
-      pw.w = pack_bf16x2(sv[6], sv[7]);
-      const bf16x8_t pf = as_bf16x8(pw);
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        u32x4_t vw;
-        vw.x = f.v0[db].x;
-        vw.y = f.v0[db].y;
-        vw.z = f.v1[db].x;
-        vw.w = f.v1[db].y;
-        o[qb][db] *= alpha;
-        o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vw), pf, o[qb][db], 0, 0, 0);
-      }
+    for (int db = 0; db < DB; ++db) {
+      u32x4_t vw;
+      vw.x = f.v0[db].x;
+      vw.y = f.v0[db].y;
+      vw.z = f.v1[db].x;
+      vw.w = f.v1[db].y;
+      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vw), pf, o[db], 0, 0, 0);
     }
   };
 
   Frags fa, fb;
   load(0, fa);
+  load(1, fb);
   for (int pr = 0; pr < n_pairs; pr += 2) {
-    if (pr + 1 < n_pairs) load(pr + 1, fb);
     compute(pr, fa);
-    if (pr + 1 < n_pairs) {
-      if (pr + 2 < n_pairs) load(pr + 2, fa);
-      compute(pr + 1, fb);
-    }
+    load(pr + 2, fa);
+    compute(pr + 1, fb);
+    load(pr + 3, fb);
   }
 
   // partial state out: lane (jq, g4) holds, of query row jq, dh = 16 db + 4 g4 .. +3
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  if (row_ok) {
+    const size_t base = (size_t)(a.part_start[my_seq] + it.slot_off) * hq + my_head;
 #pragma unroll
-  for (int qb = 0; qb < NQB; ++qb) {
-    float ls = l[qb];
-    ls += __shfl_xor(ls, 16, 64);
-    ls += __shfl_xor(ls, 32, 64);
-    const int r = qb * 16 + jq;
-    if (r < n_rows) {
-      const int seq = it.seq_first + r / grp;
-      const int head = kvh * grp + r % grp;
-      const size_t base = (size_t)(a.part_start[seq] + it.slot_off) * hq + head;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-        *reinterpret_cast<f32x4_t *>(a.part_acc + base * DH + 16 * db + 4 * g4) = o[qb][db];
-      if (g4 == 0) {
-        a.part_m[base] = m[qb];
-        a.part_l[base] = ls;
-      }
+    for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4_t *>(a.part_acc + base * DH + 16 * db + 4 * g4) = o[db];
+    if (g4 == 0) {
+      a.part_m[base] = m;
+      a.part_l[base] = l;
     }
   }
 }
@@ -233,7 +238,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const MergeArgs a) {
   float ls = 0.f;
   for (int p = lane; p < n; p += 64) {
     const size_t b = (size_t)(s0 + p) * hq + head;
-    ls += exp2f(a.part_m[b] - mx) * a.part_l[b];
+    ls += fast_exp2(a.part_m[b] - mx) * a.part_l[b];
   }
   ls = wave_sum(ls);
   constexpr int E = DH / 64;  // elements per lane
@@ -242,7 +247,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const MergeArgs a) {
   for (int e = 0; e < E; ++e) acc[e] = 0.f;
   for (int p = 0; p < n; ++p) {
     const size_t b = (size_t)(s0 + p) * hq + head;
-    const float w = exp2f(a.part_m[b] - mx);
+    const float w = fast_exp2(a.part_m[b] - mx);
     const float *src = a.part_acc + b * DH + lane * E;
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[e] += w * src[e];
@@ -320,12 +325,12 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m, mx);
-    const float alpha = exp2f(m - m_new);
+    const float alpha = fast_exp2(m - m_new);
     m = m_new;
     float ps = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      s[r] = exp2f(s[r] - m_new);
+      s[r] = fast_exp2(s[r] - m_new);
       ps += s[r];
     }
     l = l * alpha + ps;
@@ -374,29 +379,19 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
   }
 }
 
-template <int DH, int NQB>
-hipError_t launch_decode_t(const DecodeArgs &a, int item_base, int n_items, hipStream_t stream) {
-  const int n_units = n_items * a.s.n_kv_heads;
-  if (n_units <= 0) return hipSuccess;
-  hipLaunchKernelGGL((decode_attn_kernel<DH, NQB>), dim3((n_units + 3) / 4), dim3(256), 0, stream, a, item_base,
-                     n_units);
-  return hipGetLastError();
-}
-
 }  // namespace
 
-hipError_t launch_decode_attn(const DecodeArgs &a, int item_base, int n_items, int nqb, hipStream_t stream) {
-  const int dh = a.s.head_dim;
-  if (dh == 128) {
-    if (nqb == 1) return launch_decode_t<128, 1>(a, item_base, n_items, stream);
-    if (nqb == 2) return launch_decode_t<128, 2>(a, item_base, n_items, stream);
-    if (nqb == 4) return launch_decode_t<128, 4>(a, item_base, n_items, stream);
-  } else if (dh == 64) {
-    if (nqb == 1) return launch_decode_t<64, 1>(a, item_base, n_items, stream);
-    if (nqb == 2) return launch_decode_t<64, 2>(a, item_base, n_items, stream);
-    if (nqb == 4) return launch_decode_t<64, 4>(a, item_base, n_items, stream);
-  }
-  return hipErrorInvalidValue;
+hipError_t launch_decode_attn(const DecodeArgs &a, int n_items, hipStream_t stream) {
+  const int n_units = n_items * a.s.n_kv_heads;
+  if (n_units <= 0) return hipSuccess;
+  const dim3 grid((n_units + 3) / 4), block(256);
+  if (a.s.head_dim == 128)
+    hipLaunchKernelGGL((decode_attn_kernel<128>), grid, block, 0, stream, a, n_units);
+  else if (a.s.head_dim == 64)
+    hipLaunchKernelGGL((decode_attn_kernel<64>), grid, block, 0, stream, a, n_units);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
 }
 
 hipError_t launch_decode_merge(const MergeArgs &a, hipStream_t stream) {

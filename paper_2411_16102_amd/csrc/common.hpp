@@ -25,9 +25,18 @@ __device__ __forceinline__ bf16_raw f32_to_bf16(float f) {
   return static_cast<bf16_raw>(u >> 16);
 }
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// two floats to packed bf16 (lo in bits 15:0), round to nearest even: one v_cvt_pk_bf16_f32
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+  union { bf16x2_t b; uint32_t u; } c;
+  c.b = __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t);
+  return c.u;
 }
+
+// 2^x on the transcendental unit (v_exp_f32)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ float round_bf16(float f) { return bf16_to_f32(f32_to_bf16(f)); }
 

@@ -9,17 +9,24 @@
 // (i, i + dh/2) and a SwiGLU (gate, up) pair sit in two accumulator blocks of the
 // same lane, and results leave as 8-byte bf16x4 stores.
 //
-// LDS tile layout: rows of BK = 64 bf16 (128 B) whose eight 16-byte chunks are
-// XOR-swizzled with (row & 7), so the ds_read_b128 of a fragment (32 rows, one
-// chunk column) spreads over all banks.
+// Tiles travel global -> LDS directly (global_load_lds_dwordx4), four stages deep,
+// so three k-tiles are always in flight and no VGPRs are spent on staging.  LDS
+// tile layout: rows of BK = 32 bf16 (64 B) whose four 16-byte chunks are
+// XOR-swizzled with ((row >> 1) & 3), so the ds_read_b128 of a fragment (32 rows,
+// one chunk column) spreads over all banks.  Waits on the LDS-DMA loads are placed
+// by hand (s_waitcnt vmcnt + s_barrier); the compiler does not track them.
 #include "gemm.hpp"
 #include "common.hpp"
 
 namespace bs {
 
+// sixteen bytes of zeros: the source of tile chunks that lie beyond K
+__device__ __align__(16) uint16_t g_gemm_zero_chunk[8];
+
 namespace {
 
-constexpr int BK = 64;
+constexpr int BK = 32;      // k-extent of one LDS stage
+constexpr int STAGES = 4;   // LDS ring: one stage being read, three in flight
 constexpr int XCDS = 8;
 
 struct TileCoord { int tm, tn; };
@@ -50,15 +57,24 @@ __device__ __forceinline__ void store_bf16x4(uint16_t *p, float a, float b, floa
   *reinterpret_cast<u32x2_t *>(p) = v;
 }
 
+// s_waitcnt immediate (gfx9 encoding): wait until at most `vm` vector-memory
+// operations are outstanding and, if lgkm0, until all LDS reads have returned
+constexpr int waitcnt_imm(int vm, bool lgkm0) {
+  return (vm & 0xF) | ((vm >> 4) << 14) | 0x70 | (lgkm0 ? 0 : 0xF00);
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
-  constexpr int NT = WAVES_M * WAVES_N * 64;
+  constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  constexpr int X_BYTES = BM * BK * 2, W_BYTES = BN * BK * 2, STAGE = X_BYTES + W_BYTES;
-  constexpr int XCH = BM * 8 / NT, WCH = BN * 8 / NT;  // 16-byte chunks per thread per tile
-  static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile rows must divide over the threads");
+  constexpr int ROWB = BK * 2;                       // bytes of one tile row
+  constexpr int X_BYTES = BM * ROWB, W_BYTES = BN * ROWB, STAGE = X_BYTES + W_BYTES;
+  constexpr int GROUPS = (BM + BN) / 16;             // 16-row groups = one 1 KB wavefront load each
+  constexpr int LPT = GROUPS / NW;                   // loads per thread per k-tile
+  static_assert(BK == 32, "swizzle and fragment addressing assume 64-byte tile rows");
+  static_assert(GROUPS % NW == 0 && BM % 16 == 0, "row groups must divide over the wavefronts");
   static_assert(EPI != EPI_SWIGLU || NI % 2 == 0, "gate and up blocks pair up inside a wave");
   static_assert(EPI != EPI_QKV || (WTN % DH == 0 && DH % 64 == 0), "a wave covers whole heads");
 
@@ -68,68 +84,54 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   const TileCoord tc = map_tile(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n);
   const int m0 = tc.tm * BM, n0 = tc.tn * OUT_BN;
 
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm0 = (wave / WAVES_N) * WTM, wn0 = (wave % WAVES_N) * WTN;
   const int lr = lane & 31, lg = lane >> 5;
 
-  // ---- global -> register staging --------------------------------------------
-  const int kc = t & 7;          // 16-byte chunk column of this thread
-  const int r0 = t >> 3;         // first tile row of this thread; next rows are NT/8 apart
-  const uint16_t *xptr[XCH];
-  bool xok[XCH];
-  int xoff[XCH];
+  // ---- global -> LDS, without passing through registers ---------------------------
+  // One wavefront load moves 16 tile rows (1 KB): lane i lands at LDS byte 16 i of the
+  // group, i.e. row i/4, 16-byte slot i%4, and fetches the chunk that the XOR swizzle
+  // assigns to that slot.  Rows past the matrix edge are clamped to the last row (their
+  // accumulators are never stored); chunks past K read a block of zeros instead.
+  const int g_row = lane >> 2, g_slot = lane & 3;
+  const uint16_t *src[LPT];
+  int src_k[LPT];      // element offset of this lane's chunk inside a k-tile
+  int dst[LPT];        // LDS byte offset of the group inside a stage
 #pragma unroll
-  for (int i = 0; i < XCH; ++i) {
-    const int row = r0 + i * (NT / 8);
-    const int gm = m0 + row;
-    xok[i] = gm < a.M;
-    xptr[i] = a.A + (size_t)(xok[i] ? gm : 0) * a.lda + kc * 8;
-    xoff[i] = row * 128 + ((kc ^ (row & 7)) << 4);
-  }
-  const uint16_t *wptr[WCH];
-  bool wok[WCH];
-  int woff[WCH];
-#pragma unroll
-  for (int i = 0; i < WCH; ++i) {
-    const int row = r0 + i * (NT / 8);
-    int gn;
-    bool ok;
-    if (EPI == EPI_SWIGLU) {
-      const int blk = row >> 5;
-      const int col = n0 + (blk >> 1) * 32 + (row & 31);
-      ok = col < a.N;
-      gn = col + ((blk & 1) ? a.N : 0);
+  for (int i = 0; i < LPT; ++i) {
+    const int grp = wave + i * NW;
+    const int row = grp * 16 + g_row;        // row in the stacked [X tile ; W tile]
+    const int chunk = g_slot ^ ((row >> 1) & 3);
+    src_k[i] = chunk * 8;
+    dst[i] = grp * 1024;
+    if (row < BM) {
+      int gm = m0 + row;
+      gm = gm < a.M ? gm : a.M - 1;
+      src[i] = a.A + (size_t)gm * a.lda + chunk * 8;
     } else {
-      gn = n0 + row;
-      ok = gn < a.N;
+      const int wr = row - BM;
+      int gn;
+      if (EPI == EPI_SWIGLU) {
+        const int blk = wr >> 5;
+        int col = n0 + (blk >> 1) * 32 + (wr & 31);
+        col = col < a.N ? col : a.N - 1;
+        gn = col + ((blk & 1) ? a.N : 0);
+      } else {
+        gn = n0 + wr;
+        gn = gn < a.N ? gn : a.N - 1;
+      }
+      src[i] = a.B + (size_t)gn * a.ldb + chunk * 8;
     }
-    wok[i] = ok;
-    wptr[i] = a.B + (size_t)(ok ? gn : 0) * a.ldb + kc * 8;
-    woff[i] = X_BYTES + row * 128 + ((kc ^ (row & 7)) << 4);
   }
-
-  u32x4_t xs[XCH], ws[WCH];
-  auto load_global = [&](int k0) {
-    const bool kok = (k0 + kc * 8) < a.K;
+  auto issue = [&](int kt) {
+    unsigned char *stage = smem + (kt & (STAGES - 1)) * STAGE;
+    const int k0 = kt * BK;
 #pragma unroll
-    for (int i = 0; i < XCH; ++i) {
-      u32x4_t v = {0u, 0u, 0u, 0u};
-      if (xok[i] && kok) v = *reinterpret_cast<const u32x4_t *>(xptr[i] + k0);
-      xs[i] = v;
+    for (int i = 0; i < LPT; ++i) {
+      const uint16_t *p = (k0 + src_k[i] < a.K) ? src[i] + k0 : g_gemm_zero_chunk;
+      __builtin_amdgcn_global_load_lds(reinterpret_cast<const void *>(p), (__attribute__((address_space(3))) void *)(stage + dst[i]), 16, 0, 0);
     }
-#pragma unroll
-    for (int i = 0; i < WCH; ++i) {
-      u32x4_t v = {0u, 0u, 0u, 0u};
-      if (wok[i] && kok) v = *reinterpret_cast<const u32x4_t *>(wptr[i] + k0);
-      ws[i] = v;
-    }
-  };
-  auto store_lds = [&](int buf) {
-    unsigned char *base = smem + buf * STAGE;
-#pragma unroll
-    for (int i = 0; i < XCH; ++i) *reinterpret_cast<u32x4_t *>(base + xoff[i]) = xs[i];
-#pragma unroll
-    for (int i = 0; i < WCH; ++i) *reinterpret_cast<u32x4_t *>(base + woff[i]) = ws[i];
   };
 
   f32x16_t acc[NI][MI];
@@ -140,37 +142,43 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[ni][mi][r] = 0.f;
 
-  // fragment addresses: row = tile row of the lane, chunk = 2*ks + lg, swizzled by (row & 7) = (lr & 7)
-  const int xfrag = (wm0 + lr) * 128;
-  const int wfrag = X_BYTES + (wn0 + lr) * 128;
-  const int sw = lr & 7;
+  // fragment addresses: tile row of the lane, chunk 2*ks + lg swizzled by ((row >> 1) & 3)
+  const int sw = (lr >> 1) & 3;
+  const int xfrag = (wm0 + lr) * ROWB;
+  const int wfrag = X_BYTES + (wn0 + lr) * ROWB;
 
   const int nk = (a.K + BK - 1) / BK;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
+  // prologue: STAGES-1 tiles in flight (a tile beyond K is all zeros, harmless)
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s) issue(s);
   for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) load_global((kt + 1) * BK);
-    const unsigned char *base = smem + (kt & 1) * STAGE;
+    // tile kt has landed once this wavefront's older loads are done and every wavefront
+    // has reached the barrier; the barrier also frees the stage read in iteration kt-1
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm((STAGES - 2) * LPT, true));
+    __builtin_amdgcn_s_barrier();
+    issue(kt + STAGES - 1);
+    const unsigned char *base = smem + (kt & (STAGES - 1)) * STAGE;
+    bf16x8_t xf[BK / 16][MI], wf[BK / 16][NI];
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       const int ch = ((ks * 2 + lg) ^ sw) << 4;
-      bf16x8_t xf[MI], wf[NI];
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
-        xf[mi] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + xfrag + mi * 32 * 128 + ch));
+        xf[ks][mi] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + xfrag + mi * 32 * ROWB + ch));
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
-        wf[ni] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + wfrag + ni * 32 * 128 + ch));
+        wf[ks][ni] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + wfrag + ni * 32 * ROWB + ch));
+    }
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks)
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
-          acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
-    }
-    if (kt + 1 < nk) store_lds((kt + 1) & 1);
-    __syncthreads();
+          acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks][ni], xf[ks][mi], acc[ni][mi], 0, 0, 0);
   }
+  // drain the look-ahead loads (zeros or clamped rows) before the stage memory is released
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
 
   // ---- epilogues ---------------------------------------------------------------
   // accumulator element r of block (ni, mi): m = m0 + wm0 + mi*32 + lr,
@@ -180,10 +188,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
       const int m = m0 + wm0 + mi * 32 + lr;
-      float s = 0.f;
-      if (m < a.M)
-        for (int p = 0; p < a.n_ss_part; ++p) s += a.ss_part[(size_t)p * a.ss_stride + m];
-      rstd[mi] = rsqrtf(s / a.norm_dim + a.eps);
+      rstd[mi] = (m < a.M) ? a.rstd[m] : 0.f;
     }
   }
 
@@ -345,7 +350,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH>
 hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
   constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  constexpr int LDS = 2 * (BM + BN) * BK * 2;
+  constexpr int LDS = STAGES * (BM + BN) * BK * 2;
   auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI, DH>;
   static bool configured = false;
   if (!configured) {

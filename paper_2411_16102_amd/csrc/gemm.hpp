@@ -25,11 +25,9 @@ struct GemmArgs {
   const uint16_t *resid;  // [M, ldr] bf16
   const float *resid32;   // [M, ldr] fp32 (EPI_RESID only; takes precedence)
   int ldr;
-  // RMSNorm of the A rows, applied as a per-row factor after the contraction:
-  // rstd = rsqrt(sum_p ss_part[p][m] / norm_dim + eps)
-  const float *ss_part;
-  int n_ss_part, ss_stride;
-  float norm_dim, eps;
+  // RMSNorm of the A rows, applied as a per-row factor after the contraction
+  const float *rstd;     // [M] 1 / sqrt(mean(x^2) + eps) of each row (QKV, SWIGLU)
+  int ss_stride;         // row stride of ss_out
   // RESID_NORM extras
   const uint16_t *gain;  // [N] bf16 gain of the next norm
   float *C32;            // [M, ldc] x1 in fp32

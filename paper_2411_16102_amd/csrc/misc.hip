@@ -9,9 +9,9 @@ namespace {
 
 // One wavefront per row: xg = bf16(x * g) (the GEMM operand of the normalised
 // row; the 1/rms factor commutes with the contraction and is applied in the GEMM
-// epilogue) and ss = sum x^2.
+// epilogue) and rstd = 1 / sqrt(mean(x^2) + eps).
 __global__ __launch_bounds__(256) void norm_prep_kernel(const uint16_t *x, const uint16_t *g, uint16_t *xg,
-                                                       float *ss, int rows, int d) {
+                                                       float *rstd, int rows, int d, float eps) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + wave;
   if (row >= rows) return;
@@ -32,7 +32,18 @@ __global__ __launch_bounds__(256) void norm_prep_kernel(const uint16_t *x, const
     *reinterpret_cast<u32x4_t *>(outr + c) = ov;
   }
   s = wave_sum(s);
-  if (lane == 0) ss[row] = s;
+  if (lane == 0) rstd[row] = rsqrtf(s / (float)d + eps);
+}
+
+// rstd[m] = 1 / sqrt(sum_p part[p][m] / d + eps): closes the row sums of squares that
+// the output projection's epilogue leaves per column tile
+__global__ void rstd_finalize_kernel(const float *part, int n_part, int stride, float *rstd, int rows, float d,
+                                     float eps) {
+  const int m = blockIdx.x * blockDim.x + threadIdx.x;
+  if (m >= rows) return;
+  float s = 0.f;
+  for (int p = 0; p < n_part; ++p) s += part[(size_t)p * stride + m];
+  rstd[m] = rsqrtf(s / d + eps);
 }
 
 // cos/sin of pos * theta^(-2i/dh), evaluated in double and stored as float
@@ -72,10 +83,18 @@ __global__ void kv_pack_kernel(const uint16_t *k, const uint16_t *v, uint16_t *p
 
 }  // namespace
 
-hipError_t launch_norm_prep(const uint16_t *x, const uint16_t *g, uint16_t *xg, float *ss, int rows, int d,
-                            hipStream_t stream) {
+hipError_t launch_norm_prep(const uint16_t *x, const uint16_t *g, uint16_t *xg, float *rstd, int rows, int d,
+                            float eps, hipStream_t stream) {
   if (rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(norm_prep_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, x, g, xg, ss, rows, d);
+  hipLaunchKernelGGL(norm_prep_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, x, g, xg, rstd, rows, d, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_rstd_finalize(const float *part, int n_part, int stride, float *rstd, int rows, int d, float eps,
+                                hipStream_t stream) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(rstd_finalize_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, part, n_part, stride, rstd,
+                     rows, (float)d, eps);
   return hipGetLastError();
 }
 
