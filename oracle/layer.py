@@ -25,10 +25,13 @@ with angle pos * theta^(-2i/dh); scale 1/sqrt(dh); silu(z) = z / (1 + exp(-z));
 K cached after RoPE) are fields of the shape or stated where they are used.
 
 Arithmetic is float64 throughout (numpy matmul is the one library step).  With
-storage="bf16" the tensors a bf16 pipeline would keep in memory (q, k, v, the
-attention output, x1, the SwiGLU output, y) are rounded to bfloat16 where they
-would be stored; this second mode exists to separate operand-rounding error,
-which no bf16 kernel can avoid, from kernel error.
+storage="bf16" the tensors a bf16 pipeline keeps in memory or feeds to a bf16
+matrix unit are rounded to bfloat16 at that point: the GEMM operands x * g_attn
+and x1 * g_ffn (the 1/rms factor is applied to the product afterwards, which is
+the same mathematics), q, k, v, the attention output, the SwiGLU output and y;
+x1 itself stays unrounded (the residual stream inside the layer is kept wider
+than bf16).  This second mode exists to separate operand-rounding error, which
+no bf16 kernel can avoid, from kernel error.
 
 Pins (tests/test_oracle_layer.py): brute-force dense masked attention in pure
 Python on tiny inputs; closed forms for RMSNorm, RoPE and SwiGLU; kv_len = 1,
@@ -173,8 +176,11 @@ def layer_step(shape, tensors, batch, rows=None, storage: str = "exact"):
         dest[r] = resolve(batch, int(row_seq[r]), int(pos[r]))
 
     idx = np.nonzero(need_qkv)[0]
-    h = rmsnorm(x[idx], tensors.g_attn, shape.rms_eps)
-    qkv = h @ w_qkv
+    if storage == "bf16":
+        rstd = 1.0 / np.sqrt(np.mean(x[idx] * x[idx], axis=-1, keepdims=True) + shape.rms_eps)
+        qkv = (st(x[idx] * np.asarray(tensors.g_attn, dtype=np.float64)) @ w_qkv) * rstd
+    else:
+        qkv = rmsnorm(x[idx], tensors.g_attn, shape.rms_eps) @ w_qkv
     q = rope(qkv[:, :hq * dh].reshape(-1, hq, dh), pos[idx], shape.rope_theta)
     k = rope(qkv[:, hq * dh:(hq + hkv) * dh].reshape(-1, hkv, dh), pos[idx], shape.rope_theta)
     v = qkv[:, (hq + hkv) * dh:].reshape(-1, hkv, dh)
@@ -203,11 +209,17 @@ def layer_step(shape, tensors, batch, rows=None, storage: str = "exact"):
     w = np.nonzero(want)[0]
     a_in = st(attn[w])
     attn[w] = a_in
-    x1w = st(x[w] + a_in @ np.asarray(tensors.w_o, dtype=np.float64))
+    x1w = x[w] + a_in @ np.asarray(tensors.w_o, dtype=np.float64)
     x1[w] = x1w
-    h2 = rmsnorm(x1w, tensors.g_ffn, shape.rms_eps)
-    gate = h2 @ np.asarray(tensors.w_gate, dtype=np.float64)
-    up = h2 @ np.asarray(tensors.w_up, dtype=np.float64)
+    if storage == "bf16":
+        rstd2 = 1.0 / np.sqrt(np.mean(x1w * x1w, axis=-1, keepdims=True) + shape.rms_eps)
+        h2_op = st(x1w * np.asarray(tensors.g_ffn, dtype=np.float64))
+        gate = (h2_op @ np.asarray(tensors.w_gate, dtype=np.float64)) * rstd2
+        up = (h2_op @ np.asarray(tensors.w_up, dtype=np.float64)) * rstd2
+    else:
+        h2 = rmsnorm(x1w, tensors.g_ffn, shape.rms_eps)
+        gate = h2 @ np.asarray(tensors.w_gate, dtype=np.float64)
+        up = h2 @ np.asarray(tensors.w_up, dtype=np.float64)
     act = st(silu(gate) * up)
     y[w] = st(x1w + act @ np.asarray(tensors.w_down, dtype=np.float64))
     return dict(y=y, k_new=k_new, v_new=v_new, dest=dest, attn=attn, x1=x1, q=q_all, pos=pos)

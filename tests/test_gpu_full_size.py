@@ -1,0 +1,89 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch
+configuration bench.py times: the GPU runs the whole step, the oracle computes a
+sample of output rows one by one (prefill rows at several depths of several
+segments, decode rows from several prefix groups), plus properties that hold at
+any size (finite output, only the append destinations of the KV pool change).
+
+Tolerances.  Max relative error 2e-2 against the float64 oracle, as stated for
+the build.  The stated mean absolute error of 1e-3 is an absolute figure for
+unit-scale outputs and is enforced on the tiny configuration (test_gpu_parity).
+Here the outputs have mean magnitude 2 to 6, where the final rounding of y to
+bf16 alone has a mean error of 2^-9 / 1.44 = 1.4e-3 of the magnitude and each
+bf16 GEMM operand (attention output, normalised FFN input, SwiGLU output,
+K = 4096 .. 28672 terms) adds about 1e-3 of it, errors no bf16 kernel can avoid.
+So the mean absolute error is bounded relative to the output scale:
+  MAE(gpu, exact oracle)        <= 8e-3 * mean|y|
+  MAE(gpu, bf16-storage oracle) <= 4e-3 * mean|y|   (same operand roundings; what
+      remains is output elements that round to the neighbouring bf16 value)
+and every figure is printed.
+"""
+import numpy as np
+import pytest
+
+from oracle import layer as O
+from paper_2411_16102_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(batch, rng, n_prefill_rows=10, n_decode_rows=14):
+    rows = []
+    if batch.n_prefill:
+        segs = rng.choice(batch.n_prefill, size=min(2, batch.n_prefill), replace=False)
+        for s in segs:
+            r0, r1 = int(batch.row_start[s]), int(batch.row_start[s + 1])
+            picks = {r0, r1 - 1, r0 + (r1 - r0) // 2} | set(int(x) for x in rng.integers(r0, r1, n_prefill_rows // 2))
+            rows.extend(sorted(picks))
+    n_dec = batch.n_seq - batch.n_prefill
+    if n_dec:
+        # always include the shortest and the longest context
+        kv = batch.kv_len[batch.n_prefill:]
+        picks = {int(np.argmin(kv)), int(np.argmax(kv))} | set(int(x) for x in rng.integers(0, n_dec, n_decode_rows))
+        rows.extend(int(batch.row_start[batch.n_prefill + i]) for i in sorted(picks))
+    return rows
+
+
+@pytest.mark.parametrize("name", ["decode_8b", "prefill_8b", "blended_8b", "blended_70b"])
+def test_full_size_config(lib, name):
+    import torch
+    shape, make = W.CONFIGS[name]
+    batch = make(seed=0)
+    tens = W.make_tensors(shape, batch, 0)
+    layer = lib.Layer(shape, device=0)
+    dev = layer.upload(tens, batch)
+    # the schedule bench.py ends up timing (serial unless overlap wins its warm-up comparison)
+    y = layer.blend_step(dev, batch, flags=0)
+    torch.cuda.synchronize()
+    y = y.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(y).all()
+
+    rng = np.random.default_rng(123)
+    rows = sample_rows(batch, rng)
+    ref = O.layer_step(shape, tens, batch, rows=rows)
+    ref_b = O.layer_step(shape, tens, batch, rows=rows, storage="bf16")
+    got = y[rows]
+    scale = float(np.max(np.abs(ref["y"][rows])))
+    maxrel = float(np.max(np.abs(got - ref["y"][rows])) / scale)
+    mae_exact = float(np.mean(np.abs(got - ref["y"][rows])))
+    mae_b = float(np.mean(np.abs(got - ref_b["y"][rows])))
+    mean_abs = float(np.mean(np.abs(ref["y"][rows])))
+    print("%s: %d sampled rows  maxrel=%.3e  mae(exact)=%.3e  mae(bf16-storage oracle)=%.3e  mean|y|=%.3f"
+          % (name, len(rows), maxrel, mae_exact, mae_b, mean_abs))
+    assert maxrel <= 2e-2
+    assert mae_exact <= 8e-3 * mean_abs
+    assert mae_b <= 4e-3 * mean_abs
+
+    # KV append: destination slots of the sampled rows hold k, v; all other slots are untouched
+    k, v = layer.unpack_pool(dev.kv_pool, dev.n_pages)
+    k = k.view(torch.int16).cpu().numpy().view(np.uint16)
+    v = v.view(torch.int16).cpu().numpy().view(np.uint16)
+    pg, sl = layer.resolve_rows(batch)
+    written = np.zeros(k.shape[:2], dtype=bool)
+    written[pg, sl] = True
+    assert np.array_equal(k[~written], tens.k_pool[~written])
+    assert np.array_equal(v[~written], tens.v_pool[~written])
+    assert np.array_equal(pg[rows], ref["dest"][rows, 0]) and np.array_equal(sl[rows], ref["dest"][rows, 1])
+    kn = W.bf16_bits_to_f32(k[pg[rows], sl[rows]]).astype(np.float64)
+    vn = W.bf16_bits_to_f32(v[pg[rows], sl[rows]]).astype(np.float64)
+    assert np.max(np.abs(kn - ref["k_new"][rows])) / np.max(np.abs(ref["k_new"][rows])) <= 2e-2
+    assert np.max(np.abs(vn - ref["v_new"][rows])) / np.max(np.abs(ref["v_new"][rows])) <= 2e-2
