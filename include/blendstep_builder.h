@@ -1,0 +1,92 @@
+/*
+ * blendstep_builder.h - host-side batch builder: BlendServe's resource-aware
+ * prefix tree (Section 5.1), layer-wise sort (Section 5.2, Algorithm 1) and dual
+ * scan with memory partition (Section 5.3, Algorithm 3), in the single-step form
+ * that feeds bs_blend_step.  Pure CPU code: no HIP call is made.
+ *
+ * All pointers are HOST memory.  Functions return 0 or a negative bs_status
+ * (blendstep.h); bs_builder_last_error gives the message.
+ */
+#ifndef BLENDSTEP_BUILDER_H
+#define BLENDSTEP_BUILDER_H
+
+#include "blendstep.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Constants of the performance model of Section 4.1: rho = Comp / Mem with
+ * Comp = 2 (tokens) P_model / compute and Mem = (loaded tokens) kv_bytes / bandwidth. */
+typedef struct bs_cost_model {
+  int64_t p_model;    /* model parameters */
+  int64_t kv_bytes;   /* bytes of K and V per token over all layers ("H_kv * L * 4") */
+  double compute;     /* FLOP/s */
+  double bandwidth;   /* bytes/s */
+  int64_t mem_bytes;  /* M: KV-cache capacity the dual scanner partitions */
+  int32_t page_size;  /* tokens per KV page */
+} bs_cost_model;
+
+typedef struct bs_builder bs_builder;
+
+int bs_builder_create(const bs_cost_model *cm, bs_builder **out);
+void bs_builder_destroy(bs_builder *b);
+const char *bs_builder_last_error(const bs_builder *b);
+
+/* Add a request: its prompt token ids (copied), estimated output length d_est >= 0
+ * (Section 5.1, output length sampling, is outside this library: the estimate is an
+ * input) and n_cached, the number of its tokens whose KV is already cached;
+ * n_cached >= n_tokens means the request is decoding with context n_cached.
+ * Returns the request's index (>= 0) or a negative bs_status. */
+int bs_builder_add(bs_builder *b, const int32_t *tokens, int32_t n_tokens, int32_t d_est, int32_t n_cached);
+
+/* Build the compressed trie over all prompts (every request a leaf, every internal
+ * node a maximal shared segment), annotate every node with
+ *   A = distinct prompt tokens of its subtree with the root path counted once + sum d_i
+ *   B = sum (2 p_i d_i + d_i^2)            (rho is proportional to A / B)
+ * sort every node's children by rho, compute-intensive first (exact comparison of
+ * A1 B2 against A2 B1 in 128-bit integers; B = 0 is +infinity; ties to the subtree
+ * with the smaller request index), and number the nodes in DFS pre-order. */
+int bs_builder_finalize(bs_builder *b);
+
+/* The sorted tree in DFS pre-order.  bs_builder_tree_size gives the array lengths;
+ * bs_builder_tree fills caller-provided arrays: per node its parent (-1 for the
+ * root), token range [start, end) of its segment, request index (-1 for internal
+ * nodes), the position of its first leaf in the leaf order, its number of leaves,
+ * A and B; and leaf_order[n_requests], the request indices from left to right. */
+int bs_builder_tree_size(const bs_builder *b, int32_t *n_nodes, int32_t *n_requests);
+int bs_builder_tree(const bs_builder *b, int32_t *parent, int32_t *start, int32_t *end, int32_t *req,
+                    int32_t *first_leaf, int32_t *leaf_count, int64_t *A, int64_t *B, int32_t *leaf_order);
+
+/* What Algorithm 3 computed for the step. */
+typedef struct bs_scan_info {
+  double rho_rt, rho_l, rho_r; /* densities of the (first branching) root and of its leftmost / rightmost subtree */
+  double m_l, m_r;             /* memory partition, M_L + M_R = M and M_L rho_L + M_R rho_R = M rho_rt (clamped to [0, M]) */
+  int64_t n_l, n_r;            /* decode requests per side, floor(M_X / ((p_X + d_X/2) kv_bytes)), at least 1 */
+  int64_t c_l, c_r;            /* prefill token budgets per side, floor(N_X p_X / d_X); -1 = unlimited (d_X = 0) */
+  int32_t n_prefill, n_decode; /* sequences admitted to the batch */
+} bs_scan_info;
+
+/* A batch owned by the library: `batch` points into memory freed by bs_batch_free. */
+typedef struct bs_batch_owned {
+  bs_batch batch;
+  const int32_t *seq_request; /* [n_seq] request index of each sequence */
+  int64_t n_pages;            /* physical pages the page tables refer to: ids 0 .. n_pages-1 */
+  bs_scan_info info;
+} bs_batch_owned;
+
+/* One step: partition M between the two ends of the leaf order, then scan the leaves
+ * inwards from both ends, admitting up to N_X decoding requests and up to C_X prefill
+ * tokens per side (the last prompt may be cut: chunked prefill).  prefill_budget and
+ * decode_budget (<= 0: none) cap C_L + C_R and N_L + N_R, split in proportion.  The
+ * descriptor lists prefill segments first (in admission order), then decode
+ * sequences in leaf order; prefix nodes are the trie nodes with at least two admitted
+ * decode members and at least one whole page, physical pages are numbered node pages
+ * first (DFS order), then each sequence's private pages in sequence order. */
+int bs_builder_next_batch(bs_builder *b, int64_t prefill_budget, int64_t decode_budget, bs_batch_owned **out);
+void bs_batch_free(bs_batch_owned *batch);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLENDSTEP_BUILDER_H */

@@ -43,6 +43,21 @@ class BatchDesc(C.Structure):
                 ("seq_leaf_node", _i32p)]
 
 
+class CostModel(C.Structure):
+    _fields_ = [("p_model", C.c_int64), ("kv_bytes", C.c_int64), ("compute", C.c_double), ("bandwidth", C.c_double),
+                ("mem_bytes", C.c_int64), ("page_size", C.c_int32)]
+
+
+class ScanInfo(C.Structure):
+    _fields_ = [("rho_rt", C.c_double), ("rho_l", C.c_double), ("rho_r", C.c_double), ("m_l", C.c_double),
+                ("m_r", C.c_double), ("n_l", C.c_int64), ("n_r", C.c_int64), ("c_l", C.c_int64), ("c_r", C.c_int64),
+                ("n_prefill", C.c_int32), ("n_decode", C.c_int32)]
+
+
+class BatchOwned(C.Structure):
+    _fields_ = [("batch", BatchDesc), ("seq_request", _i32p), ("n_pages", C.c_int64), ("info", ScanInfo)]
+
+
 class BlendStepError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__("blendstep error %d: %s" % (code, msg))
@@ -93,6 +108,19 @@ def raw():
                                    C.c_void_p]
         lib.bs_attention.argtypes = [C.c_void_p, C.POINTER(BatchDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                      C.c_void_p, C.c_uint32]
+        _i64p = C.POINTER(C.c_int64)
+        lib.bs_builder_create.argtypes = [C.POINTER(CostModel), C.POINTER(C.c_void_p)]
+        lib.bs_builder_destroy.argtypes = [C.c_void_p]
+        lib.bs_builder_destroy.restype = None
+        lib.bs_builder_last_error.argtypes = [C.c_void_p]
+        lib.bs_builder_last_error.restype = C.c_char_p
+        lib.bs_builder_add.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_int32, C.c_int32]
+        lib.bs_builder_finalize.argtypes = [C.c_void_p]
+        lib.bs_builder_tree_size.argtypes = [C.c_void_p, _i32p, _i32p]
+        lib.bs_builder_tree.argtypes = [C.c_void_p] + [_i32p] * 6 + [_i64p, _i64p, _i32p]
+        lib.bs_builder_next_batch.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.POINTER(C.POINTER(BatchOwned))]
+        lib.bs_batch_free.argtypes = [C.POINTER(BatchOwned)]
+        lib.bs_batch_free.restype = None
         _lib = lib
     return _lib
 
@@ -274,8 +302,81 @@ class Layer:
         return out
 
 
+class Builder:
+    """Host-side batch builder (prefix tree, layer-wise sort, dual scan)."""
+
+    def __init__(self, p_model, kv_bytes, compute, bandwidth, mem_bytes, page_size=16):
+        self.lib = raw()
+        cm = CostModel(p_model, kv_bytes, compute, bandwidth, mem_bytes, page_size)
+        h = C.c_void_p()
+        rc = self.lib.bs_builder_create(C.byref(cm), C.byref(h))
+        if rc != 0:
+            raise BlendStepError(rc, "bs_builder_create failed")
+        self.h = h
+        self.page_size = page_size
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.bs_builder_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc):
+        if rc < 0:
+            raise BlendStepError(rc, (self.lib.bs_builder_last_error(self.h) or b"").decode())
+        return rc
+
+    def add(self, tokens, d_est, n_cached=0):
+        a = np.ascontiguousarray(tokens, dtype=np.int32)
+        return self._check(self.lib.bs_builder_add(self.h, _ptr(a), len(a), int(d_est), int(n_cached)))
+
+    def finalize(self):
+        self._check(self.lib.bs_builder_finalize(self.h))
+
+    def tree(self):
+        nn, nr = C.c_int32(), C.c_int32()
+        self._check(self.lib.bs_builder_tree_size(self.h, C.byref(nn), C.byref(nr)))
+        i32 = lambda n: np.zeros(max(1, n), dtype=np.int32)
+        i64 = lambda n: np.zeros(max(1, n), dtype=np.int64)
+        parent, start, end, req, first, count = (i32(nn.value) for _ in range(6))
+        A, B, order = i64(nn.value), i64(nn.value), i32(nr.value)
+        p64 = lambda a: a.ctypes.data_as(C.POINTER(C.c_int64))
+        self._check(self.lib.bs_builder_tree(self.h, _ptr(parent), _ptr(start), _ptr(end), _ptr(req), _ptr(first),
+                                             _ptr(count), p64(A), p64(B), _ptr(order)))
+        n = nn.value
+        return dict(parent=parent[:n], start=start[:n], end=end[:n], req=req[:n], first_leaf=first[:n],
+                    leaf_count=count[:n], A=A[:n], B=B[:n], leaf_order=order[:nr.value])
+
+    def next_batch(self, prefill_budget=0, decode_budget=0):
+        """Returns (info dict, descriptor dict of numpy arrays); the library's copy is freed."""
+        out = C.POINTER(BatchOwned)()
+        self._check(self.lib.bs_builder_next_batch(self.h, int(prefill_budget), int(decode_budget), C.byref(out)))
+        o = out.contents
+        b = o.batch
+        arr = lambda p, n: np.ctypeslib.as_array(p, shape=(max(1, n),))[:n].copy()
+        n_tab = int(b.page_start[b.n_seq]) if b.n_seq else 0
+        n_np = int(b.node_page_start[b.n_nodes]) if b.n_nodes else 0
+        d = dict(n_seq=b.n_seq, n_prefill=b.n_prefill, n_rows=b.n_rows,
+                 row_start=arr(b.row_start, b.n_seq + 1), kv_len=arr(b.kv_len, b.n_seq),
+                 page_start=arr(b.page_start, b.n_seq + 1), page_ids=arr(b.page_ids, n_tab),
+                 n_nodes=b.n_nodes, node_parent=arr(b.node_parent, b.n_nodes),
+                 node_page_start=arr(b.node_page_start, b.n_nodes + 1), node_page_ids=arr(b.node_page_ids, n_np),
+                 node_seq_first=arr(b.node_seq_first, b.n_nodes), node_seq_count=arr(b.node_seq_count, b.n_nodes),
+                 seq_leaf_node=arr(b.seq_leaf_node, b.n_seq), seq_request=arr(o.seq_request, b.n_seq),
+                 n_pages=int(o.n_pages))
+        info = {k: getattr(o.info, k) for k, _ in ScanInfo._fields_}
+        self.lib.bs_batch_free(out)
+        return info, d
+
+
 class _Api:
     Layer = Layer
+    Builder = Builder
     BlendStepError = BlendStepError
     FLAG_SERIAL = FLAG_SERIAL
     FLAG_OVERLAP = FLAG_OVERLAP

@@ -1,0 +1,468 @@
+// Host-side batch builder: resource-aware prefix tree, layer-wise sort and dual
+// scan of BlendServe (Sections 5.1-5.3, Algorithms 1 and 3), single-step form.
+// Plain C++, no GPU calls.  Built with floating-point contraction off: the few
+// double-precision expressions are evaluated exactly as written.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <map>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/blendstep_builder.h"
+
+namespace {
+
+struct Req {
+  std::vector<int32_t> tok;
+  int32_t d_est, n_cached;
+};
+
+// A trie node while the tree is being grown by insertion.
+struct Grow {
+  int32_t start = 0, end = 0;        // token depths of the segment
+  int32_t owner = -1;                // a request whose prompt spells the segment
+  int32_t parent = -1;
+  int32_t req = -1;                  // >= 0: a leaf
+  std::map<int32_t, int32_t> kids;   // first token of the child's segment -> node
+  std::vector<int32_t> ends_here;    // requests whose prompt ends exactly at `end`
+};
+
+// The finished tree in DFS pre-order.
+struct Node {
+  int32_t parent, start, end, req, first_leaf, leaf_count;
+  int64_t A, B, n_req, sum_p, sum_d;
+  int32_t min_req;
+  std::vector<int32_t> kids;
+};
+
+}  // namespace
+
+struct bs_builder {
+  bs_cost_model cm;
+  std::string err;
+  std::vector<Req> reqs;
+  std::vector<Node> nodes;          // valid after finalize
+  std::vector<int32_t> leaf_order;
+  std::vector<int32_t> leaf_node;   // request -> node
+  bool finalized = false;
+};
+
+namespace {
+
+int fail(bs_builder *b, int code, const char *fmt, ...) {
+  char buf[400];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (b) b->err = buf;
+  return code;
+}
+
+// is (A1, B1) strictly more compute-intensive than (A2, B2)?  A/B compared exactly.
+int cmp_density(int64_t A1, int64_t B1, int64_t A2, int64_t B2) {
+  if (B1 == 0 && B2 == 0) return 0;
+  if (B1 == 0) return 1;
+  if (B2 == 0) return -1;
+  const __int128 l = (__int128)A1 * B2, r = (__int128)A2 * B1;
+  return (l > r) - (l < r);
+}
+
+double rho_of(const bs_cost_model &cm, int64_t A, int64_t B) {
+  if (B == 0) return std::numeric_limits<double>::infinity();
+  const double t_comp = (2.0 * (double)cm.p_model) * (double)A / cm.compute;
+  const double t_mem = ((double)cm.kv_bytes * (double)B) / (2.0 * cm.bandwidth);
+  return t_comp / t_mem;
+}
+
+void partition(double rho_rt, double rho_l, double rho_r, double M, double *m_l, double *m_r) {
+  const double inf = std::numeric_limits<double>::infinity();
+  double ml;
+  if (rho_l == rho_r) ml = M;
+  else if (rho_l == inf) ml = (rho_rt != inf) ? 0.0 : M;
+  else ml = M * ((rho_rt - rho_r) / (rho_l - rho_r));
+  ml = std::min(std::max(ml, 0.0), M);
+  *m_l = ml;
+  *m_r = M - ml;
+}
+
+// ---- trie growth: radix insertion ------------------------------------------------------
+struct Grower {
+  const std::vector<Req> &reqs;
+  std::vector<Grow> g;
+  explicit Grower(const std::vector<Req> &r) : reqs(r) { g.emplace_back(); }
+
+  int32_t tok_at(const Grow &n, int32_t depth) const { return reqs[n.owner].tok[depth]; }
+
+  void insert(int32_t r) {
+    const std::vector<int32_t> &t = reqs[r].tok;
+    const int32_t p = (int32_t)t.size();
+    int32_t node = 0, depth = 0;
+    for (;;) {
+      if (g[node].req >= 0) {  // reached a leaf: it becomes an internal node that its request ends at
+        g[node].ends_here.push_back(g[node].req);
+        g[node].req = -1;
+      }
+      if (depth == p) { g[node].ends_here.push_back(r); return; }
+      auto it = g[node].kids.find(t[depth]);
+      if (it == g[node].kids.end()) {
+        Grow leaf;
+        leaf.start = depth; leaf.end = p; leaf.owner = r; leaf.parent = node; leaf.req = r;
+        g.push_back(leaf);
+        g[node].kids[t[depth]] = (int32_t)g.size() - 1;
+        return;
+      }
+      const int32_t c = it->second;
+      const int32_t len = g[c].end - g[c].start;
+      int32_t m = 0;
+      while (m < len && depth + m < p && tok_at(g[c], g[c].start + m) == t[depth + m]) ++m;
+      if (m == len) { node = c; depth += m; continue; }
+      // split c at m: a new internal node takes the matched part
+      Grow mid;
+      mid.start = g[c].start; mid.end = g[c].start + m; mid.owner = g[c].owner; mid.parent = node;
+      g.push_back(mid);
+      const int32_t mi = (int32_t)g.size() - 1;
+      g[node].kids[t[depth]] = mi;
+      g[c].start += m;
+      g[c].parent = mi;
+      g[mi].kids[tok_at(g[c], g[c].start)] = c;
+      node = mi;
+      depth += m;
+    }
+  }
+};
+
+struct Tmp {  // unsorted finished tree
+  int32_t parent, start, end, req;
+  int64_t A = 0, B = 0, n_req = 0, sum_p = 0, sum_d = 0;
+  int32_t min_req = 0;
+  std::vector<int32_t> kids;
+};
+
+}  // namespace
+
+extern "C" {
+
+int bs_builder_create(const bs_cost_model *cm, bs_builder **out) {
+  if (!out) return BS_EINVAL;
+  *out = nullptr;
+  if (!cm || cm->p_model <= 0 || cm->kv_bytes <= 0 || !(cm->compute > 0) || !(cm->bandwidth > 0) || cm->mem_bytes < 0 ||
+      cm->page_size <= 0)
+    return BS_EINVAL;
+  bs_builder *b = new (std::nothrow) bs_builder();
+  if (!b) return BS_ENOMEM;
+  b->cm = *cm;
+  *out = b;
+  return BS_OK;
+}
+
+void bs_builder_destroy(bs_builder *b) { delete b; }
+
+const char *bs_builder_last_error(const bs_builder *b) { return b ? b->err.c_str() : "builder is NULL"; }
+
+int bs_builder_add(bs_builder *b, const int32_t *tokens, int32_t n_tokens, int32_t d_est, int32_t n_cached) {
+  if (!b) return BS_EINVAL;
+  if (b->finalized) return fail(b, BS_EINVAL, "requests cannot be added after finalize");
+  if (n_tokens < 1 || !tokens) return fail(b, BS_EINVAL, "a request needs at least one prompt token");
+  if (d_est < 0 || n_cached < 0) return fail(b, BS_EINVAL, "d_est and n_cached must be >= 0");
+  Req r;
+  r.tok.assign(tokens, tokens + n_tokens);
+  r.d_est = d_est;
+  r.n_cached = n_cached;
+  b->reqs.push_back(std::move(r));
+  return (int)b->reqs.size() - 1;
+}
+
+int bs_builder_finalize(bs_builder *b) {
+  if (!b) return BS_EINVAL;
+  if (b->finalized) return BS_OK;
+  const int32_t nr = (int32_t)b->reqs.size();
+  Grower gr(b->reqs);
+  for (int32_t r = 0; r < nr; ++r) gr.insert(r);
+  // flatten: requests that end at an internal node become leaves with an empty segment
+  std::vector<Tmp> t(gr.g.size());
+  for (size_t i = 0; i < gr.g.size(); ++i) {
+    t[i].parent = gr.g[i].parent; t[i].start = gr.g[i].start; t[i].end = gr.g[i].end; t[i].req = gr.g[i].req;
+    for (auto &kv : gr.g[i].kids) t[i].kids.push_back(kv.second);
+  }
+  for (size_t i = 0; i < gr.g.size(); ++i)
+    for (int32_t r : gr.g[i].ends_here) {
+      Tmp leaf;
+      leaf.parent = (int32_t)i; leaf.start = leaf.end = gr.g[i].end; leaf.req = r;
+      t.push_back(leaf);
+      t[i].kids.push_back((int32_t)t.size() - 1);
+    }
+  // bottom-up annotation in reverse creation order is not enough (splits re-parent), so walk explicitly
+  std::vector<int32_t> order;  // pre-order
+  order.reserve(t.size());
+  {
+    std::vector<int32_t> st{0};
+    while (!st.empty()) {
+      const int32_t n = st.back(); st.pop_back();
+      order.push_back(n);
+      for (int32_t c : t[n].kids) st.push_back(c);
+    }
+  }
+  for (size_t k = order.size(); k-- > 0;) {
+    Tmp &n = t[order[k]];
+    int64_t below;
+    if (n.req >= 0) {
+      const Req &r = b->reqs[n.req];
+      const int64_t p = (int64_t)r.tok.size(), d = r.d_est;
+      n.n_req = 1; n.sum_p = p; n.sum_d = d; n.min_req = n.req;
+      n.B = 2 * p * d + d * d;
+      below = (n.end - n.start) + d;
+    } else {
+      below = n.end - n.start;
+      n.min_req = std::numeric_limits<int32_t>::max();
+      for (int32_t c : n.kids) {
+        const Tmp &ch = t[c];
+        n.n_req += ch.n_req; n.sum_p += ch.sum_p; n.sum_d += ch.sum_d; n.B += ch.B;
+        n.min_req = std::min(n.min_req, ch.min_req);
+        below += ch.A - ch.start;
+      }
+    }
+    n.A = n.start + below;
+  }
+  // Algorithm 1: order every node's children by density, compute-intensive first
+  for (Tmp &n : t)
+    std::sort(n.kids.begin(), n.kids.end(), [&](int32_t x, int32_t y) {
+      const int c = cmp_density(t[x].A, t[x].B, t[y].A, t[y].B);
+      if (c) return c > 0;
+      return t[x].min_req < t[y].min_req;
+    });
+  // DFS pre-order numbering of the sorted tree
+  b->nodes.clear();
+  b->leaf_order.clear();
+  b->leaf_node.assign(nr, -1);
+  std::vector<int32_t> new_id(t.size(), -1);
+  struct Frame { int32_t n; size_t next; };
+  std::vector<Frame> st;
+  auto open = [&](int32_t n, int32_t parent_new) {
+    Node out;
+    out.parent = parent_new; out.start = t[n].start; out.end = t[n].end; out.req = t[n].req;
+    out.first_leaf = (int32_t)b->leaf_order.size(); out.leaf_count = 0;
+    out.A = t[n].A; out.B = t[n].B; out.n_req = t[n].n_req; out.sum_p = t[n].sum_p; out.sum_d = t[n].sum_d;
+    out.min_req = t[n].min_req;
+    new_id[n] = (int32_t)b->nodes.size();
+    b->nodes.push_back(out);
+    if (t[n].req >= 0) { b->leaf_node[t[n].req] = new_id[n]; b->leaf_order.push_back(t[n].req); }
+    st.push_back({n, 0});
+  };
+  open(0, -1);
+  while (!st.empty()) {
+    Frame &f = st.back();
+    if (f.next < t[f.n].kids.size()) {
+      const int32_t c = t[f.n].kids[f.next++];
+      const int32_t me = new_id[f.n];
+      open(c, me);
+      b->nodes[me].kids.push_back(new_id[c]);
+    } else {
+      Node &nd = b->nodes[new_id[f.n]];
+      nd.leaf_count = (int32_t)b->leaf_order.size() - nd.first_leaf;
+      st.pop_back();
+    }
+  }
+  b->finalized = true;
+  return BS_OK;
+}
+
+int bs_builder_tree_size(const bs_builder *b, int32_t *n_nodes, int32_t *n_requests) {
+  if (!b || !b->finalized) return BS_EINVAL;
+  if (n_nodes) *n_nodes = (int32_t)b->nodes.size();
+  if (n_requests) *n_requests = (int32_t)b->reqs.size();
+  return BS_OK;
+}
+
+int bs_builder_tree(const bs_builder *b, int32_t *parent, int32_t *start, int32_t *end, int32_t *req,
+                    int32_t *first_leaf, int32_t *leaf_count, int64_t *A, int64_t *B, int32_t *leaf_order) {
+  if (!b || !b->finalized) return BS_EINVAL;
+  for (size_t i = 0; i < b->nodes.size(); ++i) {
+    const Node &n = b->nodes[i];
+    if (parent) parent[i] = n.parent;
+    if (start) start[i] = n.start;
+    if (end) end[i] = n.end;
+    if (req) req[i] = n.req;
+    if (first_leaf) first_leaf[i] = n.first_leaf;
+    if (leaf_count) leaf_count[i] = n.leaf_count;
+    if (A) A[i] = n.A;
+    if (B) B[i] = n.B;
+  }
+  if (leaf_order) std::copy(b->leaf_order.begin(), b->leaf_order.end(), leaf_order);
+  return BS_OK;
+}
+
+void bs_batch_free(bs_batch_owned *o) {
+  if (!o) return;
+  delete[] o->batch.row_start; delete[] o->batch.kv_len; delete[] o->batch.page_start; delete[] o->batch.page_ids;
+  delete[] o->batch.node_parent; delete[] o->batch.node_page_start; delete[] o->batch.node_page_ids;
+  delete[] o->batch.node_seq_first; delete[] o->batch.node_seq_count; delete[] o->batch.seq_leaf_node;
+  delete[] o->seq_request;
+  delete o;
+}
+
+int bs_builder_next_batch(bs_builder *b, int64_t prefill_budget, int64_t decode_budget, bs_batch_owned **out) {
+  if (!b || !out) return BS_EINVAL;
+  *out = nullptr;
+  if (!b->finalized) return fail(b, BS_EINVAL, "finalize the builder first");
+  if (b->reqs.empty()) return fail(b, BS_EINVAL, "no requests");
+  const bs_cost_model &cm = b->cm;
+  const int32_t ps = cm.page_size;
+  const std::vector<Node> &nd = b->nodes;
+
+  // Algorithm 3 on the first branching node's leftmost and rightmost subtree
+  int32_t rt = 0;
+  while (nd[rt].req < 0 && nd[rt].kids.size() == 1) rt = nd[rt].kids[0];
+  int32_t L = rt, R = rt;
+  if (nd[rt].req < 0 && nd[rt].kids.size() >= 2) { L = nd[rt].kids.front(); R = nd[rt].kids.back(); }
+  bs_scan_info info;
+  std::memset(&info, 0, sizeof info);
+  info.rho_rt = rho_of(cm, nd[rt].A, nd[rt].B);
+  info.rho_l = rho_of(cm, nd[L].A, nd[L].B);
+  info.rho_r = rho_of(cm, nd[R].A, nd[R].B);
+  partition(info.rho_rt, info.rho_l, info.rho_r, (double)cm.mem_bytes, &info.m_l, &info.m_r);
+  auto side = [&](const Node &s, double m, int64_t *n_out, int64_t *c_out) {
+    const double p_bar = (double)s.sum_p / (double)s.n_req;
+    const double d_bar = (double)s.sum_d / (double)s.n_req;
+    int64_t n = (int64_t)std::floor(m / ((p_bar + d_bar / 2.0) * (double)cm.kv_bytes));
+    if (n < 1) n = 1;
+    *n_out = n;
+    *c_out = (d_bar == 0.0) ? -1 : (int64_t)std::floor((double)n * p_bar / d_bar);
+  };
+  side(nd[L], info.m_l, &info.n_l, &info.c_l);
+  side(nd[R], info.m_r, &info.n_r, &info.c_r);
+
+  const int64_t INF = (int64_t)1 << 60;
+  int64_t n_l = info.n_l, n_r = info.n_r;
+  int64_t c_l = info.c_l < 0 ? INF : info.c_l, c_r = info.c_r < 0 ? INF : info.c_r;
+  if (prefill_budget > 0 && c_l + c_r > prefill_budget) {
+    if (c_l >= INF && c_r >= INF) c_l = prefill_budget / 2;
+    else if (c_l >= INF) c_l = std::max<int64_t>(0, prefill_budget - c_r);
+    else if (c_r >= INF) c_l = std::min(c_l, prefill_budget);
+    else c_l = (int64_t)(((__int128)c_l * prefill_budget) / (c_l + c_r));
+    c_r = prefill_budget - c_l;
+  }
+  if (decode_budget > 0 && n_l + n_r > decode_budget) {
+    n_l = (int64_t)(((__int128)n_l * decode_budget) / (n_l + n_r));
+    n_r = decode_budget - n_l;
+  }
+
+  struct Pre { int32_t req, chunk; };
+  std::vector<Pre> pre;
+  std::vector<int32_t> dec;  // leaf-order positions of admitted decode requests
+  const std::vector<int32_t> &order = b->leaf_order;
+  auto admit = [&](int32_t pos, bool left) -> bool {
+    const int32_t ri = order[pos];
+    const Req &r = b->reqs[ri];
+    const int32_t p = (int32_t)r.tok.size();
+    if (r.n_cached >= p) {
+      int64_t &n = left ? n_l : n_r;
+      if (n <= 0) return false;
+      --n;
+      dec.push_back(pos);
+      return true;
+    }
+    int64_t &c = left ? c_l : c_r;
+    if (c <= 0) return false;
+    const int32_t chunk = (int32_t)std::min<int64_t>(p - r.n_cached, c);
+    pre.push_back({ri, chunk});
+    c -= chunk;
+    return true;
+  };
+  int32_t i = 0, j = (int32_t)order.size() - 1;
+  bool go_l = true, go_r = true;
+  while (i <= j && (go_l || go_r)) {
+    if (go_l && i <= j) { if (admit(i, true)) ++i; else go_l = false; }
+    if (go_r && i <= j) { if (admit(j, false)) --j; else go_r = false; }
+  }
+  std::sort(dec.begin(), dec.end());
+  info.n_prefill = (int32_t)pre.size();
+  info.n_decode = (int32_t)dec.size();
+
+  // prefix nodes: internal trie nodes with >= 2 admitted decode members and >= 1 whole new page
+  const int32_t n_pre = (int32_t)pre.size(), n_dec = (int32_t)dec.size();
+  std::vector<int32_t> mem_count(nd.size(), 0), mem_first(nd.size(), std::numeric_limits<int32_t>::max());
+  for (int32_t k = 0; k < n_dec; ++k) {
+    int32_t n = nd[b->leaf_node[order[dec[k]]]].parent;
+    while (n >= 0) { ++mem_count[n]; mem_first[n] = std::min(mem_first[n], k); n = nd[n].parent; }
+  }
+  std::vector<int32_t> node_id(nd.size(), -1), cover(nd.size(), 0);
+  std::vector<int32_t> o_parent, o_first, o_count, o_pstart{0}, o_pages;
+  int64_t next_page = 0;
+  for (size_t n = 0; n < nd.size(); ++n) {
+    if (nd[n].req >= 0) continue;
+    const int32_t par = nd[n].parent;
+    const int32_t above = par >= 0 ? cover[par] : 0;
+    const int32_t hi = nd[n].end / ps;
+    if (mem_count[n] >= 2 && hi > above) {
+      int32_t anc = par;
+      while (anc >= 0 && node_id[anc] < 0) anc = nd[anc].parent;
+      node_id[n] = (int32_t)o_parent.size();
+      o_parent.push_back(anc >= 0 ? node_id[anc] : -1);
+      o_first.push_back(n_pre + mem_first[n]);
+      o_count.push_back(mem_count[n]);
+      for (int32_t k = above; k < hi; ++k) o_pages.push_back((int32_t)next_page++);
+      o_pstart.push_back((int32_t)o_pages.size());
+      cover[n] = hi;
+    } else {
+      cover[n] = above;
+    }
+  }
+  std::vector<int32_t> row_start{0}, kv_len, page_start{0}, page_ids, seq_leaf, seq_req;
+  for (const Pre &s : pre) {
+    const Req &r = b->reqs[s.req];
+    const int32_t kv = r.n_cached + s.chunk;
+    const int32_t npg = (kv + ps - 1) / ps;
+    for (int32_t k = 0; k < npg; ++k) page_ids.push_back((int32_t)next_page++);
+    row_start.push_back(row_start.back() + s.chunk);
+    kv_len.push_back(kv); page_start.push_back((int32_t)page_ids.size()); seq_leaf.push_back(-1); seq_req.push_back(s.req);
+  }
+  std::vector<int32_t> path;
+  for (int32_t k = 0; k < n_dec; ++k) {
+    const int32_t ri = order[dec[k]];
+    const Req &r = b->reqs[ri];
+    const int32_t kv = r.n_cached + 1;
+    int32_t n = nd[b->leaf_node[ri]].parent;
+    while (n >= 0 && node_id[n] < 0) n = nd[n].parent;
+    const int32_t leaf = n >= 0 ? node_id[n] : -1;
+    path.clear();
+    for (int32_t q = leaf; q >= 0; q = o_parent[q]) path.push_back(q);
+    int32_t shared = 0;
+    for (size_t q = path.size(); q-- > 0;) {
+      const int32_t id = path[q];
+      page_ids.insert(page_ids.end(), o_pages.begin() + o_pstart[id], o_pages.begin() + o_pstart[id + 1]);
+      shared += o_pstart[id + 1] - o_pstart[id];
+    }
+    const int32_t npg = (kv + ps - 1) / ps;
+    for (int32_t q = shared; q < npg; ++q) page_ids.push_back((int32_t)next_page++);
+    row_start.push_back(row_start.back() + 1);
+    kv_len.push_back(kv); page_start.push_back((int32_t)page_ids.size()); seq_leaf.push_back(leaf); seq_req.push_back(ri);
+  }
+
+  bs_batch_owned *o = new (std::nothrow) bs_batch_owned();
+  if (!o) return fail(b, BS_ENOMEM, "out of memory");
+  std::memset(o, 0, sizeof *o);
+  auto dup = [](const std::vector<int32_t> &v) {
+    int32_t *p = new int32_t[v.size() ? v.size() : 1];
+    if (!v.empty()) std::memcpy(p, v.data(), v.size() * sizeof(int32_t));
+    return p;
+  };
+  o->batch.n_seq = n_pre + n_dec; o->batch.n_prefill = n_pre; o->batch.n_rows = row_start.back();
+  o->batch.row_start = dup(row_start); o->batch.kv_len = dup(kv_len); o->batch.page_start = dup(page_start);
+  o->batch.page_ids = dup(page_ids);
+  o->batch.n_nodes = (int32_t)o_parent.size();
+  o->batch.node_parent = dup(o_parent); o->batch.node_page_start = dup(o_pstart); o->batch.node_page_ids = dup(o_pages);
+  o->batch.node_seq_first = dup(o_first); o->batch.node_seq_count = dup(o_count); o->batch.seq_leaf_node = dup(seq_leaf);
+  o->seq_request = dup(seq_req);
+  o->n_pages = next_page;
+  o->info = info;
+  *out = o;
+  return BS_OK;
+}
+
+}  // extern "C"

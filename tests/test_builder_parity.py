@@ -1,0 +1,142 @@
+"""The C++ batch builder against its oracle: trees, leaf orders, Algorithm 3's
+numbers and the emitted descriptors must agree bit for bit (integers exactly,
+doubles to the last bit: both sides evaluate the same expressions in the same
+order).  No GPU is needed."""
+import numpy as np
+import pytest
+
+from oracle import builder as OB
+from paper_2411_16102_amd import binding
+
+A100_8B = dict(p_model=8_030_000_000, kv_bytes=1024 * 32 * 4, compute=312e12, bandwidth=2.039e12)
+MI355_8B = dict(p_model=8_030_000_000, kv_bytes=1024 * 32 * 2 * 2, compute=2.5e15, bandwidth=8.0e12)
+
+
+def both(reqs, mem_bytes, hw=A100_8B):
+    cm = OB.CostModel(mem_bytes=mem_bytes, page_size=16, **hw)
+    o = OB.BuilderOracle(cm, reqs)
+    b = binding.Builder(hw["p_model"], hw["kv_bytes"], hw["compute"], hw["bandwidth"], mem_bytes, 16)
+    for r in reqs:
+        b.add(r.tokens, r.d_est, r.n_cached)
+    b.finalize()
+    return o, b
+
+
+def assert_same_tree(o, b):
+    want, got = o.tree_arrays(), b.tree()
+    for k in want:
+        assert np.array_equal(want[k], got[k]), k
+
+
+def assert_same_batch(o, b, **kw):
+    wi, wd = o.next_batch(**kw)
+    gi, gd = b.next_batch(**kw)
+    for k in ("rho_rt", "rho_l", "rho_r", "m_l", "m_r"):
+        assert np.float64(wi[k]).tobytes() == np.float64(gi[k]).tobytes(), (k, wi[k], gi[k])
+    for k in ("n_l", "n_r", "c_l", "c_r", "n_prefill", "n_decode"):
+        assert wi[k] == gi[k], (k, wi[k], gi[k])
+    assert set(wd) == set(gd)
+    for k in wd:
+        if isinstance(wd[k], np.ndarray):
+            assert np.array_equal(wd[k], gd[k]), k
+        else:
+            assert wd[k] == gd[k], k
+    return gi, gd
+
+
+def small_pool(seed, n=10, vocab=3, max_len=8):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        L = int(rng.integers(1, max_len + 1))
+        toks = [int(t) for t in rng.integers(0, vocab, L)]
+        dec = rng.random() < 0.5
+        out.append(OB.Request(toks, d_est=int(rng.integers(0, 9)), n_cached=(L + int(rng.integers(0, 40))) if dec else 0))
+    return out
+
+
+def grouped_pool(seed, n_groups=6, per_group=9, n_fresh=12, two_level=False):
+    rng = np.random.default_rng(seed)
+    out = []
+    for g in range(n_groups):
+        prefix = [int(t) for t in rng.integers(0, 50000, int(rng.integers(30, 400)))]
+        subs = [[int(t) for t in rng.integers(0, 50000, int(rng.integers(17, 80)))] for _ in range(3)] if two_level else [[]]
+        for k in range(per_group):
+            own = [int(t) for t in rng.integers(0, 50000, int(rng.integers(1, 60)))]
+            toks = prefix + subs[k % len(subs)] + own
+            out.append(OB.Request(toks, d_est=int(rng.integers(20, 3000)), n_cached=len(toks) + int(rng.integers(0, 500))))
+    for _ in range(n_fresh):
+        toks = [int(t) for t in rng.integers(0, 50000, int(rng.integers(30, 700)))]
+        out.append(OB.Request(toks, d_est=int(rng.integers(1, 40)), n_cached=0))
+    order = rng.permutation(len(out))
+    return [out[i] for i in order]
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_small_pools_tree_and_batch(seed):
+    reqs = small_pool(seed)
+    o, b = both(reqs, mem_bytes=5_000_000)
+    assert_same_tree(o, b)
+    assert_same_batch(o, b)
+    assert_same_batch(o, b, prefill_budget=7, decode_budget=3)
+
+
+@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("two_level", [False, True])
+def test_grouped_pools(seed, two_level):
+    reqs = grouped_pool(seed, two_level=two_level)
+    o, b = both(reqs, mem_bytes=int(2e9), hw=MI355_8B if seed % 2 else A100_8B)
+    assert_same_tree(o, b)
+    info, d = assert_same_batch(o, b, prefill_budget=2048)
+    assert info["n_prefill"] + info["n_decode"] > 0
+    assert_same_batch(o, b, prefill_budget=512, decode_budget=16)
+
+
+def test_duplicates_and_prefix_of_another_prompt():
+    reqs = [OB.Request([1, 2, 3], 5, 10), OB.Request([1, 2, 3], 7, 0), OB.Request([1, 2], 2, 30),
+            OB.Request([1, 2, 3, 4, 5], 9, 0), OB.Request([1], 1, 0), OB.Request([9], 4, 5)]
+    o, b = both(reqs, mem_bytes=10_000_000)
+    assert_same_tree(o, b)
+    assert_same_batch(o, b)
+
+
+def test_blended_config_shape_end_to_end():
+    # a pool shaped like the blended benchmark batch: 32 groups of 16 decoders behind a 1024-token
+    # shared prefix, plus fresh 512-token prompts; the emitted descriptor drives the GPU library's
+    # own validator, and its prefix nodes cover the shared prefix once per group
+    rng = np.random.default_rng(0)
+    reqs = []
+    for g in range(32):
+        prefix = [int(t) for t in rng.integers(0, 128000, 1024)]
+        for _ in range(16):
+            tail = [int(t) for t in rng.integers(0, 128000, int(rng.integers(8, 64)))]
+            ctx = 1024 + len(tail) + int(rng.integers(0, 3000))
+            reqs.append(OB.Request(prefix + tail, d_est=int(rng.integers(200, 4000)), n_cached=ctx))
+    for _ in range(8):
+        reqs.append(OB.Request([int(t) for t in rng.integers(0, 128000, 512)], d_est=8, n_cached=0))
+    o, b = both(reqs, mem_bytes=int(200e9), hw=MI355_8B)
+    assert_same_tree(o, b)
+    info, d = assert_same_batch(o, b, prefill_budget=2048, decode_budget=512)
+    assert info["n_decode"] > 0 and d["n_nodes"] > 0
+    from paper_2411_16102_amd import workloads as W
+    batch = W.Batch(page_size=16, n_seq=d["n_seq"], n_prefill=d["n_prefill"], n_rows=d["n_rows"],
+                    row_start=d["row_start"], kv_len=d["kv_len"], page_start=d["page_start"], page_ids=d["page_ids"],
+                    n_nodes=d["n_nodes"], node_parent=d["node_parent"], node_page_start=d["node_page_start"],
+                    node_page_ids=d["node_page_ids"], node_seq_first=d["node_seq_first"],
+                    node_seq_count=d["node_seq_count"], seq_leaf_node=d["seq_leaf_node"], n_pages=d["n_pages"])
+    lay = binding.Layer(W.LLAMA3_8B, device=-1)
+    assert lay.validate(batch) == 0, lay.last_error()
+    for n in range(d["n_nodes"]):
+        assert d["node_page_start"][n + 1] - d["node_page_start"][n] == 64   # 1024 shared tokens = 64 pages
+
+
+def test_errors():
+    b = binding.Builder(1, 1, 1.0, 1.0, 1, 16)
+    with pytest.raises(binding.BlendStepError):
+        b.add([], 1, 0)
+    with pytest.raises(binding.BlendStepError):
+        b.next_batch()
+    b.add([1, 2], 1, 0)
+    b.finalize()
+    with pytest.raises(binding.BlendStepError):
+        b.add([3], 1, 0)

@@ -227,3 +227,27 @@ def test_malformed_batch_is_an_error_code_on_the_gpu_path(lib):
     # the context still works afterwards
     y = layer.blend_step(dev, batch)
     assert np.isfinite(to_np(y)).all()
+
+
+def test_builder_batch_through_the_layer(lib):
+    # host builder -> descriptor -> blended step, against the layer oracle on the same descriptor
+    from paper_2411_16102_amd import binding
+    rng = np.random.default_rng(5)
+    b = binding.Builder(8_030_000_000, 131072, 2.5e15, 8.0e12, 3_000_000, 16)
+    for g in range(3):
+        prefix = [int(t) for t in rng.integers(0, 1000, int(rng.integers(40, 120)))]
+        for _ in range(6):
+            toks = prefix + [int(t) for t in rng.integers(0, 1000, int(rng.integers(1, 30)))]
+            b.add(toks, int(rng.integers(50, 600)), len(toks) + int(rng.integers(0, 100)))
+    for _ in range(4):
+        b.add([int(t) for t in rng.integers(0, 1000, int(rng.integers(20, 90)))], 4, 0)
+    b.finalize()
+    info, d = b.next_batch(prefill_budget=128)
+    assert info["n_prefill"] > 0 and info["n_decode"] > 0 and d["n_nodes"] > 0
+    batch = W.Batch(page_size=16, n_seq=d["n_seq"], n_prefill=d["n_prefill"], n_rows=d["n_rows"],
+                    row_start=d["row_start"], kv_len=d["kv_len"], page_start=d["page_start"], page_ids=d["page_ids"],
+                    n_nodes=d["n_nodes"], node_parent=d["node_parent"], node_page_start=d["node_page_start"],
+                    node_page_ids=d["node_page_ids"], node_seq_first=d["node_seq_first"],
+                    node_seq_count=d["node_seq_count"], seq_leaf_node=d["seq_leaf_node"], n_pages=d["n_pages"] + 3)
+    tens = W.make_tensors(W.TINY, batch, 5)
+    check_step(lib, W.TINY, batch, tens)
