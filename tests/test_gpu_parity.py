@@ -233,7 +233,7 @@ def test_builder_batch_through_the_layer(lib):
     # host builder -> descriptor -> blended step, against the layer oracle on the same descriptor
     from paper_2411_16102_amd import binding
     rng = np.random.default_rng(5)
-    b = binding.Builder(8_030_000_000, 131072, 2.5e15, 8.0e12, 3_000_000, 16)
+    b = binding.Builder(8_030_000_000, 131072, 2.5e15, 8.0e12, 600_000_000, 16)
     for g in range(3):
         prefix = [int(t) for t in rng.integers(0, 1000, int(rng.integers(40, 120)))]
         for _ in range(6):
