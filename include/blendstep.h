@@ -163,6 +163,10 @@ int bs_profile_reset(bs_ctx *ctx);
  * Smaller chunks give more parallelism and more partial states to merge. */
 int bs_set_chunk_pages(bs_ctx *ctx, int32_t pages);
 
+/* Tuning knob: GEMM tile shape, process-wide: 0 = chosen per problem (default), 1 = 256x256,
+ * 2 = 160x256 (not for the QKV GEMM), 3 = 128x128. */
+int bs_set_gemm_tiles(bs_ctx *ctx, int32_t variant);
+
 /* Stand-alone entry points of the individual operators (the same kernels the
  * step launches), for per-kernel parity tests and roofline measurements.
  *   bs_gemm_nt: C[M,N] = A[M,K] * B[N,K]^T, bf16 in, fp32 accumulate, bf16 out;

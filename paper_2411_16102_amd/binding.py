@@ -104,6 +104,7 @@ def raw():
         lib.bs_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         lib.bs_profile_reset.argtypes = [C.c_void_p]
         lib.bs_set_chunk_pages.argtypes = [C.c_void_p, C.c_int32]
+        lib.bs_set_gemm_tiles.argtypes = [C.c_void_p, C.c_int32]
         lib.bs_gemm_nt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p]
         lib.bs_attention.argtypes = [C.c_void_p, C.POINTER(BatchDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
@@ -288,6 +289,9 @@ class Layer:
 
     def set_chunk_pages(self, pages: int):
         self._check(self.lib.bs_set_chunk_pages(self.h, pages))
+
+    def set_gemm_tiles(self, variant: int):
+        self._check(self.lib.bs_set_gemm_tiles(self.h, variant))
 
     def profile(self, on: bool):
         self._check(self.lib.bs_profile_enable(self.h, 1 if on else 0))

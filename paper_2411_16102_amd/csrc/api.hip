@@ -725,6 +725,13 @@ int bs_profile_read(bs_ctx *c, int which, double *total_ms, int64_t *launches) {
   return BS_OK;
 }
 
+int bs_set_gemm_tiles(bs_ctx *c, int32_t variant) {
+  if (!c) return BS_EINVAL;
+  if (variant < 0 || variant > 3) return fail(c, BS_EINVAL, "gemm tile variant %d (0..3)", variant);
+  gemm_force_variant(variant);
+  return BS_OK;
+}
+
 /* Tuning knob used by the benchmark sweeps: pages per decode-attention chunk. */
 int bs_set_chunk_pages(bs_ctx *c, int32_t pages) {
   if (!c) return BS_EINVAL;

@@ -72,9 +72,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   constexpr int ROWB = BK * 2;                       // bytes of one tile row
   constexpr int X_BYTES = BM * ROWB, W_BYTES = BN * ROWB, STAGE = X_BYTES + W_BYTES;
   constexpr int GROUPS = (BM + BN) / 16;             // 16-row groups = one 1 KB wavefront load each
-  constexpr int LPT = GROUPS / NW;                   // loads per thread per k-tile
+  constexpr int LPT = (GROUPS + NW - 1) / NW;        // loads per thread per k-tile
   static_assert(BK == 32, "swizzle and fragment addressing assume 64-byte tile rows");
-  static_assert(GROUPS % NW == 0 && BM % 16 == 0, "row groups must divide over the wavefronts");
+  static_assert(BM % 32 == 0 && BN % 32 == 0, "tiles are made of 32x32 MFMA blocks");
   static_assert(EPI != EPI_SWIGLU || NI % 2 == 0, "gate and up blocks pair up inside a wave");
   static_assert(EPI != EPI_QKV || (WTN % DH == 0 && DH % 64 == 0), "a wave covers whole heads");
 
@@ -100,7 +100,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   int dst[LPT];        // LDS byte offset of the group inside a stage
 #pragma unroll
   for (int i = 0; i < LPT; ++i) {
-    const int grp = wave + i * NW;
+    // when the groups do not divide over the wavefronts the surplus loads repeat the last
+    // group (same bytes to the same place), so every wavefront issues LPT loads per tile
+    const int grp = (wave + i * NW) < GROUPS ? (wave + i * NW) : GROUPS - 1;
     const int row = grp * 16 + g_row;        // row in the stacked [X tile ; W tile]
     const int chunk = g_slot ^ ((row >> 1) & 3);
     src_k[i] = chunk * 8;
@@ -365,42 +367,67 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// Large tiles once they can fill the chip; otherwise 128 x 128 tiles.
-bool use_big_tiles(int m, int n_tiles_cols_256) {
-  const long tiles = (long)((m + 255) / 256) * n_tiles_cols_256;
-  return m >= 1024 && tiles >= 128;
+// Tile shapes.  BIG: 256x256, 8 wavefronts.  TALL: 160x256, 4 wavefronts of 160x64: 2560 (and
+// 5120) rows by 4096 (8192) columns then make exactly one (four) full rounds of 256
+// workgroups where 256x256 tiles leave 38 % (17 %) of the CUs idle.  SMALL: 128x128.
+enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3 };
+constexpr int N_CU = 256;
+
+int g_forced_variant = V_AUTO;
+
+long n_tiles(int m, int n, int bm, int bn) { return (long)((m + bm - 1) / bm) * ((n + bn - 1) / bn); }
+
+// estimated time = rounds of workgroups x tile area / per-tile efficiency of the shape
+// (efficiencies measured on MI355X relative to the 256x256 tile: both smaller shapes reach 0.8)
+int choose_variant(int m, int n_b_rows, int epilogue, int dh) {
+  if (g_forced_variant != V_AUTO && !(g_forced_variant == V_TALL && epilogue == EPI_QKV)) return g_forced_variant;
+  (void)dh;
+  struct Cand { int v, bm, bn; double q; };
+  const Cand cands[3] = {{V_BIG, 256, 256, 1.0}, {V_TALL, 160, 256, 0.8}, {V_SMALL, 128, 128, 0.8}};
+  int best = V_SMALL;
+  double best_t = 1e300;
+  for (const Cand &c : cands) {
+    if (c.v == V_TALL && epilogue == EPI_QKV) continue;  // a wavefront must cover whole heads
+    const long tiles = n_tiles(m, n_b_rows, c.bm, c.bn);
+    const long rounds = (tiles + N_CU - 1) / N_CU;
+    const double t = (double)rounds * c.bm * c.bn / c.q;
+    if (t < best_t) { best_t = t; best = c.v; }
+  }
+  return best;
+}
+
+template <int EPI, int DH_BIG_M, int DH_BIG_N>
+hipError_t launch_variant(const GemmArgs &a, int v, hipStream_t stream) {
+  if (v == V_BIG) return launch_one<256, 256, DH_BIG_M, DH_BIG_N, EPI, (DH_BIG_M == 4 ? 128 : 64)>(a, stream);
+  if (v == V_TALL) return launch_one<160, 256, 1, 4, EPI, 64>(a, stream);
+  return launch_one<128, 128, 2, 2, EPI, 64>(a, stream);
 }
 
 }  // namespace
 
+void gemm_force_variant(int v) { g_forced_variant = v; }
+
 int gemm_ss_parts(int n, int epilogue, int m, int dh) {
-  (void)epilogue; (void)dh;
-  const bool big = use_big_tiles(m, (n + 255) / 256);
-  // RESID_NORM instances: 256x256 tiles with 4 waves along N, or 128x128 with 2
-  return big ? ((n + 255) / 256) * 4 : ((n + 127) / 128) * 2;
+  const int v = choose_variant(m, n, epilogue, dh);
+  // partial row sums: one per (column tile, wavefront column)
+  return v == V_SMALL ? ((n + 127) / 128) * 2 : ((n + 255) / 256) * 4;
 }
 
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream) {
+  const int b_rows = (epilogue == EPI_SWIGLU) ? 2 * a.N : a.N;
+  const int v = choose_variant(a.M, b_rows, epilogue, dh);
   switch (epilogue) {
-    case EPI_PLAIN:
-      return use_big_tiles(a.M, (a.N + 255) / 256) ? launch_one<256, 256, 2, 4, EPI_PLAIN, 64>(a, stream)
-                                                  : launch_one<128, 128, 2, 2, EPI_PLAIN, 64>(a, stream);
-    case EPI_RESID:
-      return use_big_tiles(a.M, (a.N + 255) / 256) ? launch_one<256, 256, 2, 4, EPI_RESID, 64>(a, stream)
-                                                  : launch_one<128, 128, 2, 2, EPI_RESID, 64>(a, stream);
-    case EPI_RESID_NORM:
-      return use_big_tiles(a.M, (a.N + 255) / 256) ? launch_one<256, 256, 2, 4, EPI_RESID_NORM, 64>(a, stream)
-                                                  : launch_one<128, 128, 2, 2, EPI_RESID_NORM, 64>(a, stream);
-    case EPI_SWIGLU:
-      return use_big_tiles(a.M, (a.N + 127) / 128) ? launch_one<256, 256, 2, 4, EPI_SWIGLU, 64>(a, stream)
-                                                  : launch_one<128, 128, 2, 2, EPI_SWIGLU, 64>(a, stream);
+    case EPI_PLAIN: return launch_variant<EPI_PLAIN, 2, 4>(a, v, stream);
+    case EPI_RESID: return launch_variant<EPI_RESID, 2, 4>(a, v, stream);
+    case EPI_RESID_NORM: return launch_variant<EPI_RESID_NORM, 2, 4>(a, v, stream);
+    case EPI_SWIGLU: return launch_variant<EPI_SWIGLU, 2, 4>(a, v, stream);
     case EPI_QKV:
       if (dh == 128)
-        return use_big_tiles(a.M, (a.N + 255) / 256) ? launch_one<256, 256, 4, 2, EPI_QKV, 128>(a, stream)
-                                                    : launch_one<128, 128, 4, 1, EPI_QKV, 128>(a, stream);
+        return v == V_BIG ? launch_one<256, 256, 4, 2, EPI_QKV, 128>(a, stream)
+                          : launch_one<128, 128, 4, 1, EPI_QKV, 128>(a, stream);
       if (dh == 64)
-        return use_big_tiles(a.M, (a.N + 255) / 256) ? launch_one<256, 256, 2, 4, EPI_QKV, 64>(a, stream)
-                                                    : launch_one<128, 128, 2, 2, EPI_QKV, 64>(a, stream);
+        return v == V_BIG ? launch_one<256, 256, 2, 4, EPI_QKV, 64>(a, stream)
+                          : launch_one<128, 128, 2, 2, EPI_QKV, 64>(a, stream);
       return hipErrorInvalidValue;
     default:
       return hipErrorInvalidValue;

@@ -45,6 +45,7 @@ struct GemmArgs {
 // Picks a tile shape for the problem and launches on `stream`.  dh is the head
 // dimension (used by EPI_QKV only).  Returns hipSuccess or the launch error.
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream);
-int gemm_ss_parts(int n, int epilogue, int m, int dh);  // partial-sum slots a RESID_NORM launch over N columns writes
+int gemm_ss_parts(int n, int epilogue, int m, int dh);
+void gemm_force_variant(int v);  // 0 = choose by shape, 1 = 256x256, 2 = 160x256, 3 = 128x128 tiles (tuning)  // partial-sum slots a RESID_NORM launch over N columns writes
 
 }  // namespace bs
