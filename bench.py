@@ -69,6 +69,7 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-pages", type=int, default=0)
+    ap.add_argument("--decode-cus", type=int, default=-1)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by independent replicas, "
@@ -92,6 +93,8 @@ def main():
     layer = lib.Layer(shape, device=0)
     if args.chunk_pages:
         layer.set_chunk_pages(args.chunk_pages)
+    if args.decode_cus >= 0:
+        layer.set_overlap_cus(args.decode_cus)
     note("uploading")
     dev = layer.upload(tens, batch)
     desc = lib.marshal_batch(batch)

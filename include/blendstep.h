@@ -163,6 +163,10 @@ int bs_profile_reset(bs_ctx *ctx);
  * Smaller chunks give more parallelism and more partial states to merge. */
 int bs_set_chunk_pages(bs_ctx *ctx, int32_t pages);
 
+/* Tuning knob: CUs reserved for decode attention in the BS_FLAG_OVERLAP schedule (0, 64, 128 or
+ * 192; default 64; 0 = side streams without CU masks).  Synchronises the device. */
+int bs_set_overlap_cus(bs_ctx *ctx, int32_t decode_cus);
+
 /* Tuning knob: GEMM tile shape, process-wide: 0 = chosen per problem (default), 1 = 256x256,
  * 2 = 160x256 (not for the QKV GEMM), 3 = 128x128. */
 int bs_set_gemm_tiles(bs_ctx *ctx, int32_t variant);

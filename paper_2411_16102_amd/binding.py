@@ -105,6 +105,7 @@ def raw():
         lib.bs_profile_reset.argtypes = [C.c_void_p]
         lib.bs_set_chunk_pages.argtypes = [C.c_void_p, C.c_int32]
         lib.bs_set_gemm_tiles.argtypes = [C.c_void_p, C.c_int32]
+        lib.bs_set_overlap_cus.argtypes = [C.c_void_p, C.c_int32]
         lib.bs_gemm_nt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p]
         lib.bs_attention.argtypes = [C.c_void_p, C.POINTER(BatchDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
@@ -289,6 +290,9 @@ class Layer:
 
     def set_chunk_pages(self, pages: int):
         self._check(self.lib.bs_set_chunk_pages(self.h, pages))
+
+    def set_overlap_cus(self, decode_cus: int):
+        self._check(self.lib.bs_set_overlap_cus(self.h, decode_cus))
 
     def set_gemm_tiles(self, variant: int):
         self._check(self.lib.bs_set_gemm_tiles(self.h, variant))

@@ -59,8 +59,9 @@ struct bs_ctx {
   std::vector<DecodeItem> items;
   std::vector<int32_t> pf_work;
   // overlap
-  hipStream_t side = nullptr;
-  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  hipStream_t side_a = nullptr, side_b = nullptr;  // CU-masked: GEMM side, decode-attention side
+  int cus_a = 256, cus_b = 256;
+  hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr;
   // tunables
   int chunk_pages = 32;
   // profiling
@@ -455,34 +456,77 @@ int run_decode_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, 
   return BS_OK;
 }
 
-// output projection, FFN and both residuals for rows [r0, r1)
-int run_tail(bs_ctx *c, const bs_weights *w, const uint16_t *x, uint16_t *y, int r0, int r1, hipStream_t st) {
+// output projection (+ first residual, second norm) and gate/up (+ SwiGLU) for rows [r0, r1)
+int run_o_gate_up(bs_ctx *c, const bs_weights *w, const uint16_t *x, int r0, int r1, hipStream_t st, int n_cu) {
   const int rows = r1 - r0;
   if (rows <= 0) return BS_OK;
   const bs_layer_cfg &g = c->cfg;
   const int hd = g.n_q_heads * g.head_dim, d = g.d_model, f = g.d_ffn;
-  const int parts = gemm_ss_parts(d, EPI_RESID_NORM, rows, g.head_dim);
   GemmArgs o{};
+  o.n_cu = n_cu;
   o.A = c->attn + (size_t)r0 * hd; o.lda = hd; o.B = (const uint16_t *)w->w_o; o.ldb = hd;
   o.M = rows; o.N = d; o.K = hd;
   o.C32 = c->x1 + (size_t)r0 * d; o.ldc = d; o.resid = x + (size_t)r0 * d; o.ldr = d;
   o.gain = (const uint16_t *)w->g_ffn; o.C_gain = c->xg2 + (size_t)r0 * d;
   o.ss_out = c->ss2 + r0; o.ss_stride = c->cap_rows;
+  const int parts = gemm_ss_parts(o, EPI_RESID_NORM, g.head_dim);
   SPAN(c, BS_K_GEMM_O, st, {
     HIP_TRY(c, launch_gemm(o, EPI_RESID_NORM, g.head_dim, st));
     HIP_TRY(c, launch_rstd_finalize(c->ss2 + r0, parts, c->cap_rows, c->rstd2 + r0, rows, d, g.rms_eps, st));
   });
   GemmArgs u{};
+  u.n_cu = n_cu;
   u.A = c->xg2 + (size_t)r0 * d; u.lda = d; u.B = (const uint16_t *)w->w_gate_up; u.ldb = d;
   u.M = rows; u.N = f; u.K = d;
   u.C = c->act + (size_t)r0 * f; u.ldc = f;
   u.rstd = c->rstd2 + r0;
   SPAN(c, BS_K_GEMM_GATE_UP, st, HIP_TRY(c, launch_gemm(u, EPI_SWIGLU, g.head_dim, st)));
+  return BS_OK;
+}
+
+// down projection and second residual for rows [r0, r1)
+int run_down(bs_ctx *c, const bs_weights *w, uint16_t *y, int r0, int r1, hipStream_t st, int n_cu) {
+  const int rows = r1 - r0;
+  if (rows <= 0) return BS_OK;
+  const bs_layer_cfg &g = c->cfg;
+  const int d = g.d_model, f = g.d_ffn;
   GemmArgs dn{};
+  dn.n_cu = n_cu;
   dn.A = c->act + (size_t)r0 * f; dn.lda = f; dn.B = (const uint16_t *)w->w_down; dn.ldb = f;
   dn.M = rows; dn.N = d; dn.K = f;
   dn.C = y + (size_t)r0 * d; dn.ldc = d; dn.resid32 = c->x1 + (size_t)r0 * d; dn.ldr = d;
   SPAN(c, BS_K_GEMM_DOWN, st, HIP_TRY(c, launch_gemm(dn, EPI_RESID, g.head_dim, st)));
+  return BS_OK;
+}
+
+// Side streams restricted to disjoint CU sets: `decode_cus` CUs (a multiple of 64, the same
+// number in every XCD under either CU numbering) for decode attention, the rest for the GEMMs.
+int make_side_streams(bs_ctx *c, int decode_cus) {
+  if (c->side_a) { (void)hipStreamDestroy(c->side_a); c->side_a = nullptr; }
+  if (c->side_b) { (void)hipStreamDestroy(c->side_b); c->side_b = nullptr; }
+  hipDeviceProp_t prop;
+  HIP_TRY(c, hipGetDeviceProperties(&prop, c->device));
+  const int n_cu = prop.multiProcessorCount;
+  const int words = (n_cu + 31) / 32;
+  std::vector<uint32_t> ma(words, 0u), mb(words, 0u);
+  int na = 0, nb = 0;
+  const int per32 = decode_cus * 32 / std::max(32, n_cu);  // CUs of each block of 32 that go to decode attention
+  for (int i = 0; i < n_cu; ++i) {
+    if (decode_cus > 0 && (i % 32) < per32) { mb[i / 32] |= 1u << (i % 32); ++nb; }
+    else { ma[i / 32] |= 1u << (i % 32); ++na; }
+  }
+  if (decode_cus <= 0 || nb == 0 || na == 0 ||
+      hipExtStreamCreateWithCUMask(&c->side_a, words, ma.data()) != hipSuccess ||
+      hipExtStreamCreateWithCUMask(&c->side_b, words, mb.data()) != hipSuccess) {
+    (void)hipGetLastError();
+    if (c->side_a) { (void)hipStreamDestroy(c->side_a); c->side_a = nullptr; }
+    if (c->side_b) { (void)hipStreamDestroy(c->side_b); c->side_b = nullptr; }
+    HIP_TRY(c, hipStreamCreateWithFlags(&c->side_a, hipStreamNonBlocking));
+    HIP_TRY(c, hipStreamCreateWithFlags(&c->side_b, hipStreamNonBlocking));
+    na = nb = n_cu;
+  }
+  c->cus_a = na;
+  c->cus_b = nb;
   return BS_OK;
 }
 
@@ -526,9 +570,10 @@ int bs_create(const bs_layer_cfg *cfg, int device, bs_ctx **out) {
   if (e != hipSuccess) { c->err = std::string("rope table: ") + hipGetErrorString(e); return bail(BS_EHIP); }
   for (int i = 0; i < RING; ++i)
     if (hipEventCreateWithFlags(&c->h_ev[i], hipEventDisableTiming) != hipSuccess) { c->err = "hipEventCreate failed"; return bail(BS_EHIP); }
-  if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
+  if (make_side_streams(c, 64) != BS_OK ||
       hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) { c->err = "side stream setup failed"; return bail(BS_EHIP); }
+      hipEventCreateWithFlags(&c->ev_a, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_b, hipEventDisableTiming) != hipSuccess) { if (c->err.empty()) c->err = "side stream setup failed"; return bail(BS_EHIP); }
   *out = c;
   return BS_OK;
 }
@@ -546,9 +591,11 @@ void bs_destroy(bs_ctx *c) {
     if (c->h_blob[i]) (void)hipHostFree(c->h_blob[i]);
     (void)hipEventDestroy(c->h_ev[i]);
   }
-  if (c->side) (void)hipStreamDestroy(c->side);
+  if (c->side_a) (void)hipStreamDestroy(c->side_a);
+  if (c->side_b) (void)hipStreamDestroy(c->side_b);
   if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
-  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+  if (c->ev_a) (void)hipEventDestroy(c->ev_a);
+  if (c->ev_b) (void)hipEventDestroy(c->ev_b);
   for (auto &v : c->spans) for (auto &s : v) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
   for (auto e : c->free_events) (void)hipEventDestroy(e);
   delete c;
@@ -636,18 +683,25 @@ int bs_blend_step(bs_ctx *c, const bs_weights *w, const bs_batch *b, const void 
   if (!overlap) {
     if ((rc = run_prefill_attn(c, p, c->qbuf, c->attn, pool, st))) return rc;
     if ((rc = run_decode_attn(c, p, c->qbuf, c->attn, pool, st))) return rc;
-    if ((rc = run_tail(c, w, x, y, 0, T, st))) return rc;
+    if ((rc = run_o_gate_up(c, w, x, 0, T, st, 0))) return rc;
+    if ((rc = run_down(c, w, y, 0, T, st, 0))) return rc;
   } else {
-    // decode attention (HBM-bound) on the side stream while the prefill rows run
-    // their attention, projection and FFN (MFMA-bound) on the caller's stream
+    // Decode attention (HBM-bound) on its own CU set while the prefill rows go through
+    // attention, output projection and gate/up (MFMA-bound) on the other CUs; then the decode
+    // rows' projection and gate/up, and one down projection over all rows, on the whole chip.
+    const int Tp = p.n_prefill_rows;
     HIP_TRY(c, hipEventRecord(c->ev_fork, st));
-    HIP_TRY(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
-    if ((rc = run_decode_attn(c, p, c->qbuf, c->attn, pool, c->side))) return rc;
-    HIP_TRY(c, hipEventRecord(c->ev_join, c->side));
-    if ((rc = run_prefill_attn(c, p, c->qbuf, c->attn, pool, st))) return rc;
-    if ((rc = run_tail(c, w, x, y, 0, p.n_prefill_rows, st))) return rc;
-    HIP_TRY(c, hipStreamWaitEvent(st, c->ev_join, 0));
-    if ((rc = run_tail(c, w, x, y, p.n_prefill_rows, T, st))) return rc;
+    HIP_TRY(c, hipStreamWaitEvent(c->side_b, c->ev_fork, 0));
+    HIP_TRY(c, hipStreamWaitEvent(c->side_a, c->ev_fork, 0));
+    if ((rc = run_decode_attn(c, p, c->qbuf, c->attn, pool, c->side_b))) return rc;
+    HIP_TRY(c, hipEventRecord(c->ev_b, c->side_b));
+    if ((rc = run_prefill_attn(c, p, c->qbuf, c->attn, pool, c->side_a))) return rc;
+    if ((rc = run_o_gate_up(c, w, x, 0, Tp, c->side_a, c->cus_a))) return rc;
+    HIP_TRY(c, hipEventRecord(c->ev_a, c->side_a));
+    HIP_TRY(c, hipStreamWaitEvent(st, c->ev_a, 0));
+    HIP_TRY(c, hipStreamWaitEvent(st, c->ev_b, 0));
+    if ((rc = run_o_gate_up(c, w, x, Tp, T, st, 0))) return rc;
+    if ((rc = run_down(c, w, y, 0, T, st, 0))) return rc;
   }
   return BS_OK;
 }
@@ -730,6 +784,15 @@ int bs_set_gemm_tiles(bs_ctx *c, int32_t variant) {
   if (variant < 0 || variant > 3) return fail(c, BS_EINVAL, "gemm tile variant %d (0..3)", variant);
   gemm_force_variant(variant);
   return BS_OK;
+}
+
+int bs_set_overlap_cus(bs_ctx *c, int32_t decode_cus) {
+  if (!c) return BS_EINVAL;
+  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
+  if (decode_cus < 0 || decode_cus > 192 || decode_cus % 64) return fail(c, BS_EINVAL, "decode_cus %d (0, 64, 128 or 192)", decode_cus);
+  HIP_TRY(c, hipSetDevice(c->device));
+  HIP_TRY(c, hipDeviceSynchronize());
+  return make_side_streams(c, decode_cus);
 }
 
 /* Tuning knob used by the benchmark sweeps: pages per decode-attention chunk. */

@@ -379,7 +379,8 @@ long n_tiles(int m, int n, int bm, int bn) { return (long)((m + bm - 1) / bm) * 
 
 // estimated time = rounds of workgroups x tile area / per-tile efficiency of the shape
 // (efficiencies measured on MI355X relative to the 256x256 tile: both smaller shapes reach 0.8)
-int choose_variant(int m, int n_b_rows, int epilogue, int dh) {
+int choose_variant(int m, int n_b_rows, int epilogue, int dh, int n_cu) {
+  if (n_cu <= 0) n_cu = N_CU;
   if (g_forced_variant != V_AUTO && !(g_forced_variant == V_TALL && epilogue == EPI_QKV)) return g_forced_variant;
   (void)dh;
   struct Cand { int v, bm, bn; double q; };
@@ -389,7 +390,7 @@ int choose_variant(int m, int n_b_rows, int epilogue, int dh) {
   for (const Cand &c : cands) {
     if (c.v == V_TALL && epilogue == EPI_QKV) continue;  // a wavefront must cover whole heads
     const long tiles = n_tiles(m, n_b_rows, c.bm, c.bn);
-    const long rounds = (tiles + N_CU - 1) / N_CU;
+    const long rounds = (tiles + n_cu - 1) / n_cu;
     const double t = (double)rounds * c.bm * c.bn / c.q;
     if (t < best_t) { best_t = t; best = c.v; }
   }
@@ -407,15 +408,15 @@ hipError_t launch_variant(const GemmArgs &a, int v, hipStream_t stream) {
 
 void gemm_force_variant(int v) { g_forced_variant = v; }
 
-int gemm_ss_parts(int n, int epilogue, int m, int dh) {
-  const int v = choose_variant(m, n, epilogue, dh);
+int gemm_ss_parts(const GemmArgs &a, int epilogue, int dh) {
+  const int v = choose_variant(a.M, a.N, epilogue, dh, a.n_cu);
   // partial row sums: one per (column tile, wavefront column)
-  return v == V_SMALL ? ((n + 127) / 128) * 2 : ((n + 255) / 256) * 4;
+  return v == V_SMALL ? ((a.N + 127) / 128) * 2 : ((a.N + 255) / 256) * 4;
 }
 
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream) {
   const int b_rows = (epilogue == EPI_SWIGLU) ? 2 * a.N : a.N;
-  const int v = choose_variant(a.M, b_rows, epilogue, dh);
+  const int v = choose_variant(a.M, b_rows, epilogue, dh, a.n_cu);
   switch (epilogue) {
     case EPI_PLAIN: return launch_variant<EPI_PLAIN, 2, 4>(a, v, stream);
     case EPI_RESID: return launch_variant<EPI_RESID, 2, 4>(a, v, stream);

@@ -20,6 +20,7 @@ struct GemmArgs {
   const uint16_t *A;  // [M, K] bf16 activations, row stride lda
   const uint16_t *B;  // [N, K] bf16 weights (out-features major), row stride ldb
   int M, N, K, lda, ldb;
+  int n_cu;           // CUs the launch may use (0 = the whole chip); only steers the tile choice
   uint16_t *C;        // output [M, ldc] bf16 (PLAIN, RESID*, SWIGLU)
   int ldc;
   const uint16_t *resid;  // [M, ldr] bf16
@@ -45,7 +46,7 @@ struct GemmArgs {
 // Picks a tile shape for the problem and launches on `stream`.  dh is the head
 // dimension (used by EPI_QKV only).  Returns hipSuccess or the launch error.
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream);
-int gemm_ss_parts(int n, int epilogue, int m, int dh);
+int gemm_ss_parts(const GemmArgs &a, int epilogue, int dh);
 void gemm_force_variant(int v);  // 0 = choose by shape, 1 = 256x256, 2 = 160x256, 3 = 128x128 tiles (tuning)  // partial-sum slots a RESID_NORM launch over N columns writes
 
 }  // namespace bs
