@@ -12,8 +12,10 @@
 // Tiles travel global -> LDS directly (global_load_lds_dwordx4), four stages deep,
 // so three k-tiles are always in flight and no VGPRs are spent on staging.  LDS
 // tile layout: rows of BK = 32 bf16 (64 B) whose four 16-byte chunks are
-// XOR-swizzled with ((row >> 1) & 3), so the ds_read_b128 of a fragment (32 rows,
-// one chunk column) spreads over all banks.  Waits on the LDS-DMA loads are placed
+// XOR-swizzled with ((row >> 2) & 3): four consecutive 64-byte rows already fill the
+// 256-byte bank row, so the swizzle must change every four rows for the ds_read_b128
+// of a fragment (32 rows, one chunk column) to be conflict-free (measured: 155 B/clk/CU
+// against 118 with a swizzle that changes every two rows and 63 without one).  Waits on the LDS-DMA loads are placed
 // by hand (s_waitcnt vmcnt + s_barrier); the compiler does not track them.
 #include "gemm.hpp"
 #include "common.hpp"
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
     // group (same bytes to the same place), so every wavefront issues LPT loads per tile
     const int grp = (wave + i * NW) < GROUPS ? (wave + i * NW) : GROUPS - 1;
     const int row = grp * 16 + g_row;        // row in the stacked [X tile ; W tile]
-    const int chunk = g_slot ^ ((row >> 1) & 3);
+    const int chunk = g_slot ^ ((row >> 2) & 3);
     src_k[i] = chunk * 8;
     dst[i] = grp * 1024;
     if (row < BM) {
@@ -144,40 +146,60 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[ni][mi][r] = 0.f;
 
-  // fragment addresses: tile row of the lane, chunk 2*ks + lg swizzled by ((row >> 1) & 3)
-  const int sw = (lr >> 1) & 3;
+  // fragment addresses: tile row of the lane, chunk 2*ks + lg swizzled by ((row >> 2) & 3)
+  const int sw = (lr >> 2) & 3;
   const int xfrag = (wm0 + lr) * ROWB;
   const int wfrag = X_BYTES + (wn0 + lr) * ROWB;
 
   const int nk = (a.K + BK - 1) / BK;
-  // prologue: STAGES-1 tiles in flight (a tile beyond K is all zeros, harmless)
-#pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s) issue(s);
-  for (int kt = 0; kt < nk; ++kt) {
-    // tile kt has landed once this wavefront's older loads are done and every wavefront
-    // has reached the barrier; the barrier also frees the stage read in iteration kt-1
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm((STAGES - 2) * LPT, true));
-    __builtin_amdgcn_s_barrier();
-    issue(kt + STAGES - 1);
+  // Software pipeline.  DMA: tile kt+3 is requested while tile kt is multiplied (a tile
+  // beyond K is all zeros, harmless).  LDS -> registers: the fragments of the next
+  // 16-wide k-step are requested before the MFMAs of the current one are issued, across
+  // tile boundaries too, so the matrix pipe never waits for a whole LDS read phase; this
+  // needs tile kt+1 to have landed when iteration kt starts.
+  auto read_frags = [&](int kt, int ks, bf16x8_t (&xf)[MI], bf16x8_t (&wf)[NI]) {
     const unsigned char *base = smem + (kt & (STAGES - 1)) * STAGE;
-    bf16x8_t xf[BK / 16][MI], wf[BK / 16][NI];
+    const int ch = ((ks * 2 + lg) ^ sw) << 4;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int ch = ((ks * 2 + lg) ^ sw) << 4;
+    for (int mi = 0; mi < MI; ++mi)
+      xf[mi] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + xfrag + mi * 32 * ROWB + ch));
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+      wf[ni] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + wfrag + ni * 32 * ROWB + ch));
+  };
+  // MFMAs number `first` .. `last`-1 of the NI x MI block grid of one k-step
+  auto multiply = [&](const bf16x8_t (&xf)[MI], const bf16x8_t (&wf)[NI], int first, int last) {
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
-        xf[ks][mi] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + xfrag + mi * 32 * ROWB + ch));
+        if (ni * MI + mi >= first && ni * MI + mi < last)
+          acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
+  };
+  static_assert(BK == 32 && STAGES == 4, "the pipeline below is written for two k-steps per tile, four stages");
+  bf16x8_t xa[MI], wa[NI], xb[MI], wb[NI];
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-        wf[ks][ni] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + wfrag + ni * 32 * ROWB + ch));
-    }
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks)
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-          acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ks][ni], xf[ks][mi], acc[ni][mi], 0, 0, 0);
+  for (int s = 0; s < STAGES - 1; ++s) issue(s);
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm((STAGES - 2) * LPT, true));  // tile 0 has landed
+  __builtin_amdgcn_s_barrier();
+  read_frags(0, 0, xa, wa);
+  for (int kt = 0; kt < nk; ++kt) {
+    // tiles <= kt+1 have landed once this wavefront's older loads are done and every
+    // wavefront has reached the barrier; the barrier also frees the stage of tile kt-1
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm((STAGES - 3) * LPT, true));
+    __builtin_amdgcn_s_barrier();
+    issue(kt + STAGES - 1);
+    read_frags(kt, 1, xb, wb);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(xa, wa, 0, NI * MI);
+    // LDS reads return in order: start the second k-step (its operands were requested a whole
+    // MFMA batch ago) before requesting the next tile's first k-step into the registers just freed
+    multiply(xb, wb, 0, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(kt + 1, 0, xa, wa);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(xb, wb, 2, NI * MI);
+    __builtin_amdgcn_sched_barrier(0);
   }
   // drain the look-ahead loads (zeros or clamped rows) before the stage memory is released
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
