@@ -70,6 +70,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-pages", type=int, default=0)
     ap.add_argument("--decode-cus", type=int, default=-1)
+    ap.add_argument("--gemm-tiles", type=int, default=0, help="force one GEMM tile shape (0: cost model)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB elementwise copy (for scaling HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the path shards by independent replicas, "
@@ -93,11 +96,21 @@ def main():
     layer = lib.Layer(shape, device=0)
     if args.chunk_pages:
         layer.set_chunk_pages(args.chunk_pages)
+    if args.gemm_tiles:
+        layer.set_gemm_tiles(args.gemm_tiles)
     if args.decode_cus >= 0:
         layer.set_overlap_cus(args.decode_cus)
     note("uploading")
     dev = layer.upload(tens, batch)
     desc = lib.marshal_batch(batch)
+    if args.copy_calibration:
+        # a plain copy of known size: reads 2^30 bytes and writes 2^30 bytes per launch
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     note("timing")
     y = torch.empty_like(dev.x)
 

@@ -30,7 +30,7 @@ struct Plan {
        off_part_start = 0, off_pf_work = 0, off_items = 0, off_pages = 0, total_ints = 0;
   long total_node_pages = 0, n_slots = 0;
   int n_pf_work = 0;
-  int n_items = 0;
+  int n_wide = 0, n_narrow = 0;  // decode items with up to 64 / up to 16 query rows (wide ones first)
 };
 
 }  // namespace
@@ -56,7 +56,7 @@ struct bs_ctx {
   int ring_pos = 0;
   // host scratch reused across calls
   std::vector<int32_t> refcount, path_pages, path_chunks, members, blob;
-  std::vector<DecodeItem> items;
+  std::vector<DecodeItem> items, items_wide;
   std::vector<int32_t> pf_work;
   // overlap
   hipStream_t side_a = nullptr, side_b = nullptr;  // CU-masked: GEMM side, decode-attention side
@@ -272,7 +272,8 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
   // chunk counts along each node's root path (path_pages was filled by validate)
   c->path_chunks.assign((size_t)nn, 0);
   c->items.clear();
-  const int max_members = std::max(1, 16 / grp);  // 16 query rows per work item
+  c->items_wide.clear();
+  const int max_members = std::max(1, 64 / grp);  // up to 64 query rows per work item
   for (int n = 0; n < nn; ++n) {
     const int par = b->node_parent[n];
     const int np = b->node_page_start[n + 1] - b->node_page_start[n];
@@ -291,7 +292,7 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
         it.seq_first = b->node_seq_first[n] + lo;
         it.n_members = hi - lo;
         it.slot_off = above + k;
-        c->items.push_back(it);
+        ((hi - lo) * grp > 16 ? c->items_wide : c->items).push_back(it);
       }
     }
   }
@@ -358,10 +359,12 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
   p.n_pf_work = (int)order.size();
   p.off_items = p.off_pf_work + 2L * p.n_pf_work;
   // longest chunks first: the many short tail chunks then fill the gaps at the end of the launch
-  std::stable_sort(c->items.begin(), c->items.end(),
-                   [](const DecodeItem &x, const DecodeItem &y) { return x.n_tokens > y.n_tokens; });
-  const long n_items = (long)c->items.size();
-  p.n_items = (int)n_items;
+  auto longer = [](const DecodeItem &x, const DecodeItem &y) { return x.n_tokens > y.n_tokens; };
+  std::stable_sort(c->items.begin(), c->items.end(), longer);
+  std::stable_sort(c->items_wide.begin(), c->items_wide.end(), longer);
+  p.n_wide = (int)c->items_wide.size();
+  p.n_narrow = (int)c->items.size();
+  const long n_items = (long)p.n_wide + p.n_narrow;
   p.off_pages = p.off_items + 8 * n_items;
   p.total_ints = p.off_pages + p.total_node_pages + n_tab;
   blob.resize((size_t)p.total_ints);
@@ -369,7 +372,8 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
     blob[p.off_pf_work + 2 * i] = order[i].second.first;
     blob[p.off_pf_work + 2 * i + 1] = order[i].second.second;
   }
-  if (n_items) std::memcpy(&blob[p.off_items], c->items.data(), sizeof(DecodeItem) * n_items);
+  if (p.n_wide) std::memcpy(&blob[p.off_items], c->items_wide.data(), sizeof(DecodeItem) * p.n_wide);
+  if (p.n_narrow) std::memcpy(&blob[p.off_items + 8L * p.n_wide], c->items.data(), sizeof(DecodeItem) * p.n_narrow);
   if (p.total_node_pages) std::memcpy(&blob[p.off_pages], b->node_page_ids, sizeof(int32_t) * p.total_node_pages);
   if (n_tab) std::memcpy(&blob[p.off_pages + p.total_node_pages], b->page_ids, sizeof(int32_t) * n_tab);
   return BS_OK;
@@ -447,7 +451,10 @@ int run_decode_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, 
   a.row_start = c->d_blob + p.off_row_start; a.part_start = c->d_blob + p.off_part_start;
   a.q = q; a.kv_pool = pool;
   a.part_acc = c->part_acc; a.part_m = c->part_m; a.part_l = c->part_l;
-  SPAN(c, BS_K_ATTN_DECODE, st, HIP_TRY(c, launch_decode_attn(a, p.n_items, st)));
+  SPAN(c, BS_K_ATTN_DECODE, st, {
+    HIP_TRY(c, launch_decode_attn(a, 0, p.n_wide, 4, st));
+    HIP_TRY(c, launch_decode_attn(a, p.n_wide, p.n_narrow, 1, st));
+  });
   MergeArgs m;
   m.s = a.s; m.n_prefill = p.n_prefill; m.n_decode = p.n_decode;
   m.row_start = a.row_start; m.part_start = a.part_start;
@@ -781,7 +788,7 @@ int bs_profile_read(bs_ctx *c, int which, double *total_ms, int64_t *launches) {
 
 int bs_set_gemm_tiles(bs_ctx *c, int32_t variant) {
   if (!c) return BS_EINVAL;
-  if (variant < 0 || variant > 3) return fail(c, BS_EINVAL, "gemm tile variant %d (0..3)", variant);
+  if (variant < 0 || variant > 4) return fail(c, BS_EINVAL, "gemm tile variant %d (0..4)", variant);
   gemm_force_variant(variant);
   return BS_OK;
 }

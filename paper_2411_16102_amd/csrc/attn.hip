@@ -49,7 +49,7 @@ __device__ __forceinline__ u32x2_t mask_tokens(u32x2_t v, int t0, int limit) {
 }
 
 // ------------------------------------------------------------------------------
-// decode attention: one wavefront per (item, KV head), up to 16 query rows
+// decode attention: one wavefront per (item, KV head), up to 16 * NQB query rows
 // ------------------------------------------------------------------------------
 // The online softmax keeps a per-row reference exponent m that only moves when a
 // new score exceeds it by more than TAU (in log2 units): probabilities are then
@@ -57,9 +57,8 @@ __device__ __forceinline__ u32x2_t mask_tokens(u32x2_t v, int t0, int limit) {
 // the accumulators are rescaled a few times per chunk instead of once per page.
 constexpr float TAU = 8.0f;
 
-template <int DH>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void decode_attn_kernel(const DecodeArgs a,
-                                                                                                     int n_units) {
+template <int DH, int NQB>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NQB > 1 ? 1 : 2, NQB > 1 ? 1 : 2))) void decode_attn_kernel(const DecodeArgs a, int item_base, int n_units) {
   constexpr int KC = DH / 32;  // 32-wide chunks of the head dimension (QK^T contraction)
   constexpr int DB = DH / 16;  // 16-row blocks of the head dimension (PV output rows)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -67,7 +66,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int unit = blockIdx.x * 4 + wave;
   if (unit >= n_units) return;
   const int hkv = a.s.n_kv_heads, hq = a.s.n_q_heads, grp = hq / hkv;
-  const int item = unit / hkv;
+  const int item = item_base + unit / hkv;
   const int kvh = unit % hkv;
   const DecodeItem it = a.items[item];
   const int n_rows = it.n_members * grp;
@@ -77,25 +76,50 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const size_t tile = (size_t)16 * DH;
   const float sc = a.s.scale_log2e;
 
-  // query fragments: B operand of S^T = K Q^T; lane (jq, g4) holds Q[row jq][32c + 8 g4 ..+7]
-  bf16x8_t qf[KC];
-  const bool row_ok = jq < n_rows;
-  const int my_seq = it.seq_first + (row_ok ? jq / grp : 0);
-  const int my_head = kvh * grp + (row_ok ? jq % grp : 0);
-  {
-    const uint16_t *p = a.q + (size_t)a.row_start[my_seq] * (hq * DH) + my_head * DH + 8 * g4;
+  // query fragments: B operand of S^T = K Q^T; lane (jq, g4) holds Q[row 16 qb + jq][32c + 8 g4 ..+7].
+  // With four blocks of head dimension 128 they would not fit beside the accumulators
+  // and the two K/V register sets, so they stay in LDS (each lane re-reads only what it
+  // wrote itself: no barrier is needed) and are fetched again for every pair of pages.
+  constexpr bool Q_LDS = NQB > 1 && DH > 64;
+  constexpr int QLD = DH + 8;  // padded row: 16-byte reads of 16 consecutive rows spread over all banks
+  __shared__ __align__(16) uint16_t q_sh[Q_LDS ? 4 * NQB * 16 * QLD : 8];
+  bf16x8_t qf[Q_LDS ? 1 : NQB][Q_LDS ? 1 : KC];
+  uint32_t q_off = (uint32_t)((wave * NQB * 16 + jq) * QLD + 8 * g4);
+  bool row_ok[NQB];
+  int my_seq[NQB], my_head[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int r = qb * 16 + jq;
+    row_ok[qb] = r < n_rows;
+    my_seq[qb] = it.seq_first + (row_ok[qb] ? r / grp : 0);
+    my_head[qb] = kvh * grp + (row_ok[qb] ? r % grp : 0);
+    const uint16_t *p = a.q + (size_t)a.row_start[my_seq[qb]] * (hq * DH) + my_head[qb] * DH + 8 * g4;
 #pragma unroll
     for (int c = 0; c < KC; ++c) {
       u32x4_t v = {0u, 0u, 0u, 0u};
-      if (row_ok) v = ld16(p + 32 * c);
-      qf[c] = as_bf16x8(v);
+      if (row_ok[qb]) v = ld16(p + 32 * c);
+      if constexpr (Q_LDS)
+        *reinterpret_cast<u32x4_t *>(&q_sh[q_off + qb * 16 * QLD + 32 * c]) = v;
+      else
+        qf[qb][c] = as_bf16x8(v);
     }
   }
+  auto q_frag = [&](int qb, int c) -> bf16x8_t {
+    if constexpr (Q_LDS)
+      return as_bf16x8(*reinterpret_cast<const u32x4_t *>(&q_sh[q_off + qb * 16 * QLD + 32 * c]));
+    else
+      return qf[qb][c];
+  };
 
-  f32x4_t o[DB];
+  f32x4_t o[NQB][DB];
+  float m[NQB], l[NQB];
 #pragma unroll
-  for (int db = 0; db < DB; ++db) o[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  float m = NEG_BIG, l = 0.f;
+  for (int qb = 0; qb < NQB; ++qb) {
+    m[qb] = NEG_BIG;
+    l[qb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) o[qb][db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
 
   // The chunk's page ids sit in one register (lane i holds page i; chunks have at most
   // 64 pages), so the loop never waits on a scalar memory load to form an address.
@@ -106,7 +130,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // pair is being computed the other pair (16 KB per wavefront) is in flight, and the
   // set just consumed is refilled at once.  Loads are unconditional (past the end they
   // re-read the last pair, whose tokens are then all masked), which keeps the loop
-  // straight-line so that every wait covers exactly the loads it needs.
+  // straight-line so that every wait covers exactly the loads it needs.  A pair is
+  // loaded once and used by all NQB blocks of 16 query rows.
   struct Frags {
     u32x4_t k[2][KC];
     u32x2_t v0[DB], v1[DB];
@@ -135,62 +160,69 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   auto compute = [&](int pr, Frags &f) {
     const int tb = pr * 32;
     const bool ragged = tb + 32 > n_tok;  // the last pair of a chunk, or a step past the end
-    f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int c = 0; c < KC; ++c) {
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[0][c]), qf[c], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[1][c]), qf[c], s1, 0, 0, 0);
-    }
-    float sv[8];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      sv[r] = s0[r] * sc;
-      sv[4 + r] = s1[r] * sc;
-    }
-    if (ragged) {  // mask scores, and never let stale slots (possibly NaN bits) meet a zero probability
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        if (tb + 4 * g4 + r >= n_tok) sv[r] = NEG_BIG;
-        if (tb + 16 + 4 * g4 + r >= n_tok) sv[4 + r] = NEG_BIG;
-      }
+    if constexpr (Q_LDS) asm volatile("" : "+v"(q_off));  // keep the query reads inside the loop
+    if (ragged) {  // never let stale slots (possibly NaN bit patterns) meet a zero probability
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         f.v0[db] = mask_tokens(f.v0[db], tb + 4 * g4, n_tok);
         f.v1[db] = mask_tokens(f.v1[db], tb + 16 + 4 * g4, n_tok);
       }
     }
-    float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    if (__builtin_amdgcn_ballot_w64(mx > m + TAU) != 0) {  // wave-uniform: somebody's reference must move
-      const float m_new = fmaxf(m, mx);
-      const float alpha = fast_exp2(m - m_new);
-      m = m_new;
-      l *= alpha;
 #pragma unroll
-      for (int db = 0; db < DB; ++db) o[db] *= alpha;
-    }
-    float ps = 0.f;
+    for (int qb = 0; qb < NQB; ++qb) {
+      f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      sv[r] = fast_exp2(sv[r] - m);
-      ps += sv[r];
-    }
-    l += ps;
-    u32x4_t pw;
-    pw.x = pack_bf16x2(sv[0], sv[1]);
-    pw.y = pack_bf16x2(sv[2], sv[3]);
-    pw.z = pack_bf16x2(sv[4], sv[5]);
-    pw.w = pack_bf16x2(sv[6], sv[7]);
-    const bf16x8_t pf = as_bf16x8(pw);
+      for (int c = 0; c < KC; ++c) {
+        const bf16x8_t qv = q_frag(qb, c);
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[0][c]), qv, s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.k[1][c]), qv, s1, 0, 0, 0);
+      }
+      float sv[8];
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      u32x4_t vw;
-      vw.x = f.v0[db].x;
-      vw.y = f.v0[db].y;
-      vw.z = f.v1[db].x;
-      vw.w = f.v1[db].y;
-      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vw), pf, o[db], 0, 0, 0);
+      for (int r = 0; r < 4; ++r) {
+        sv[r] = s0[r] * sc;
+        sv[4 + r] = s1[r] * sc;
+      }
+      if (ragged) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          if (tb + 4 * g4 + r >= n_tok) sv[r] = NEG_BIG;
+          if (tb + 16 + 4 * g4 + r >= n_tok) sv[4 + r] = NEG_BIG;
+        }
+      }
+      float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      if (__builtin_amdgcn_ballot_w64(mx > m[qb] + TAU) != 0) {  // wave-uniform: somebody's reference must move
+        const float m_new = fmaxf(m[qb], mx);
+        const float alpha = fast_exp2(m[qb] - m_new);
+        m[qb] = m_new;
+        l[qb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) o[qb][db] *= alpha;
+      }
+      float ps = 0.f;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        sv[r] = fast_exp2(sv[r] - m[qb]);
+        ps += sv[r];
+      }
+      l[qb] += ps;
+      u32x4_t pw;
+      pw.x = pack_bf16x2(sv[0], sv[1]);
+      pw.y = pack_bf16x2(sv[2], sv[3]);
+      pw.z = pack_bf16x2(sv[4], sv[5]);
+      pw.w = pack_bf16x2(sv[6], sv[7]);
+      const bf16x8_t pf = as_bf16x8(pw);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        u32x4_t vw;
+        vw.x = f.v0[db].x;
+        vw.y = f.v0[db].y;
+        vw.z = f.v1[db].x;
+        vw.w = f.v1[db].y;
+        o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vw), pf, o[qb][db], 0, 0, 0);
+      }
     }
   };
 
@@ -199,21 +231,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   load(1, fb);
   for (int pr = 0; pr < n_pairs; pr += 2) {
     compute(pr, fa);
+    if constexpr (NQB > 1) __builtin_amdgcn_sched_barrier(0);  // refill only once the set is dead
     load(pr + 2, fa);
+    if constexpr (NQB > 1) __builtin_amdgcn_sched_barrier(0);
     compute(pr + 1, fb);
+    if constexpr (NQB > 1) __builtin_amdgcn_sched_barrier(0);
     load(pr + 3, fb);
+    if constexpr (NQB > 1) __builtin_amdgcn_sched_barrier(0);
   }
 
-  // partial state out: lane (jq, g4) holds, of query row jq, dh = 16 db + 4 g4 .. +3
-  l += __shfl_xor(l, 16, 64);
-  l += __shfl_xor(l, 32, 64);
-  if (row_ok) {
-    const size_t base = (size_t)(a.part_start[my_seq] + it.slot_off) * hq + my_head;
+  // partial state out: lane (jq, g4) holds, of query row 16 qb + jq, dh = 16 db + 4 g4 .. +3
 #pragma unroll
-    for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4_t *>(a.part_acc + base * DH + 16 * db + 4 * g4) = o[db];
-    if (g4 == 0) {
-      a.part_m[base] = m;
-      a.part_l[base] = l;
+  for (int qb = 0; qb < NQB; ++qb) {
+    float ls = l[qb];
+    ls += __shfl_xor(ls, 16, 64);
+    ls += __shfl_xor(ls, 32, 64);
+    if (row_ok[qb]) {
+      const size_t base = (size_t)(a.part_start[my_seq[qb]] + it.slot_off) * hq + my_head[qb];
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        *reinterpret_cast<f32x4_t *>(a.part_acc + base * DH + 16 * db + 4 * g4) = o[qb][db];
+      if (g4 == 0) {
+        a.part_m[base] = m[qb];
+        a.part_l[base] = ls;
+      }
     }
   }
 }
@@ -381,14 +422,19 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
 
 }  // namespace
 
-hipError_t launch_decode_attn(const DecodeArgs &a, int n_items, hipStream_t stream) {
+hipError_t launch_decode_attn(const DecodeArgs &a, int item_base, int n_items, int nqb, hipStream_t stream) {
   const int n_units = n_items * a.s.n_kv_heads;
   if (n_units <= 0) return hipSuccess;
   const dim3 grid((n_units + 3) / 4), block(256);
-  if (a.s.head_dim == 128)
-    hipLaunchKernelGGL((decode_attn_kernel<128>), grid, block, 0, stream, a, n_units);
-  else if (a.s.head_dim == 64)
-    hipLaunchKernelGGL((decode_attn_kernel<64>), grid, block, 0, stream, a, n_units);
+  const int dh = a.s.head_dim;
+  if (dh == 128 && nqb == 1)
+    hipLaunchKernelGGL((decode_attn_kernel<128, 1>), grid, block, 0, stream, a, item_base, n_units);
+  else if (dh == 128 && nqb == 4)
+    hipLaunchKernelGGL((decode_attn_kernel<128, 4>), grid, block, 0, stream, a, item_base, n_units);
+  else if (dh == 64 && nqb == 1)
+    hipLaunchKernelGGL((decode_attn_kernel<64, 1>), grid, block, 0, stream, a, item_base, n_units);
+  else if (dh == 64 && nqb == 4)
+    hipLaunchKernelGGL((decode_attn_kernel<64, 4>), grid, block, 0, stream, a, item_base, n_units);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

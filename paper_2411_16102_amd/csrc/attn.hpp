@@ -14,7 +14,7 @@ struct DecodeItem {
   int32_t page_off;   // first page of the chunk in item_pages
   int32_t n_tokens;   // tokens in the chunk (the last page may be partial)
   int32_t seq_first;  // first member sequence
-  int32_t n_members;  // member sequences (n_members * group <= 16 query rows)
+  int32_t n_members;  // member sequences (n_members * group <= 16 * nqb query rows of the launch)
   int32_t slot_off;   // partial-state slot of this chunk inside every member's slot range
   int32_t pad[3];
 };
@@ -36,7 +36,8 @@ struct DecodeArgs {
   float *part_m, *part_l;     // [slots][Hq]
 };
 
-hipError_t launch_decode_attn(const DecodeArgs &a, int n_items, hipStream_t stream);
+// items [item_base, item_base + n_items) each hold at most 16 * nqb query rows (nqb = 1 or 4)
+hipError_t launch_decode_attn(const DecodeArgs &a, int item_base, int n_items, int nqb, hipStream_t stream);
 
 struct MergeArgs {
   AttnShape s;

@@ -9,14 +9,18 @@
 // (i, i + dh/2) and a SwiGLU (gate, up) pair sit in two accumulator blocks of the
 // same lane, and results leave as 8-byte bf16x4 stores.
 //
-// Tiles travel global -> LDS directly (global_load_lds_dwordx4), four stages deep,
-// so three k-tiles are always in flight and no VGPRs are spent on staging.  LDS
-// tile layout: rows of BK = 32 bf16 (64 B) whose four 16-byte chunks are
-// XOR-swizzled with ((row >> 2) & 3): four consecutive 64-byte rows already fill the
-// 256-byte bank row, so the swizzle must change every four rows for the ds_read_b128
-// of a fragment (32 rows, one chunk column) to be conflict-free (measured: 155 B/clk/CU
-// against 118 with a swizzle that changes every two rows and 63 without one).  Waits on the LDS-DMA loads are placed
-// by hand (s_waitcnt vmcnt + s_barrier); the compiler does not track them.
+// Tiles travel global -> LDS directly (global_load_lds_dwordx4), so no VGPRs are spent
+// on staging.  A k-tile is BK = 64 wide: a tile row is then one whole 128-byte cache
+// line, which the memory pipeline delivers about 1.5 times faster than the two 64-byte
+// halves fetched separately (measured: 41 against 26 B/clk/CU into LDS).  LDS is a ring
+// of five 32 KB units, one unit holding the activation panel or the weight panel of one
+// k-tile, so two and a half k-tiles fit in the 160 KB: while tile kt is multiplied,
+// tile kt+1 has landed or is landing and the activation panel of tile kt+2 is in
+// flight.  Rows are 128 B whose eight 16-byte chunks are XOR-swizzled with
+// ((row >> 1) & 7): two consecutive rows fill the 256-byte bank row, so the swizzle
+// must change every two rows for the ds_read_b128 of a fragment (32 rows, one chunk
+// column) to be conflict-free.  Waits on the LDS-DMA loads are placed by hand
+// (s_waitcnt vmcnt + s_barrier); the compiler does not track them.
 #include "gemm.hpp"
 #include "common.hpp"
 
@@ -27,11 +31,13 @@ __device__ __align__(16) uint16_t g_gemm_zero_chunk[8];
 
 namespace {
 
-constexpr int BK = 32;      // k-extent of one LDS stage
-constexpr int STAGES = 4;   // LDS ring: one stage being read, three in flight
+constexpr int BK = 64;      // k-extent of one k-tile: rows of 128 bytes
+constexpr int NU = 5;       // LDS ring, in units of one operand panel of one k-tile
 constexpr int XCDS = 8;
 
 struct TileCoord { int tm, tn; };
+struct Yes { static constexpr bool value = true; };
+struct No { static constexpr bool value = false; };
 
 // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous
 // range of tiles and walk that range in groups of GM tile rows, so the tiles in
@@ -72,13 +78,14 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   constexpr int ROWB = BK * 2;                       // bytes of one tile row
-  constexpr int X_BYTES = BM * ROWB, W_BYTES = BN * ROWB, STAGE = X_BYTES + W_BYTES;
-  constexpr int GROUPS = (BM + BN) / 16;             // 16-row groups = one 1 KB wavefront load each
-  constexpr int LPT = (GROUPS + NW - 1) / NW;        // loads per thread per k-tile
-  static_assert(BK == 32, "swizzle and fragment addressing assume 64-byte tile rows");
+  constexpr int UNIT = (BM > BN ? BM : BN) * ROWB;   // one ring unit holds either panel
+  constexpr int GA = BM / 8, GB = BN / 8;            // 8-row groups = one 1 KB wavefront load each
+  constexpr int LA = (GA + NW - 1) / NW, LB = (GB + NW - 1) / NW;  // loads per thread per panel
+  static_assert(BK == 64, "swizzle and fragment addressing assume 128-byte tile rows");
   static_assert(BM % 32 == 0 && BN % 32 == 0, "tiles are made of 32x32 MFMA blocks");
   static_assert(EPI != EPI_SWIGLU || NI % 2 == 0, "gate and up blocks pair up inside a wave");
   static_assert(EPI != EPI_QKV || (WTN % DH == 0 && DH % 64 == 0), "a wave covers whole heads");
+  static_assert(2 * LA + 2 * LB < 64, "outstanding loads must fit the vmcnt field");
 
   extern __shared__ __align__(16) unsigned char smem[];
 
@@ -92,50 +99,64 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   const int lr = lane & 31, lg = lane >> 5;
 
   // ---- global -> LDS, without passing through registers ---------------------------
-  // One wavefront load moves 16 tile rows (1 KB): lane i lands at LDS byte 16 i of the
-  // group, i.e. row i/4, 16-byte slot i%4, and fetches the chunk that the XOR swizzle
-  // assigns to that slot.  Rows past the matrix edge are clamped to the last row (their
-  // accumulators are never stored); chunks past K read a block of zeros instead.
-  const int g_row = lane >> 2, g_slot = lane & 3;
-  const uint16_t *src[LPT];
-  int src_k[LPT];      // element offset of this lane's chunk inside a k-tile
-  int dst[LPT];        // LDS byte offset of the group inside a stage
+  // One wavefront load moves 8 tile rows (1 KB): lane i lands at LDS byte 16 i of the
+  // group, i.e. row i/8, 16-byte slot i%8, and fetches the chunk that the XOR swizzle
+  // assigns to that slot, so the eight lanes of a row cover one whole cache line.  Rows
+  // past the matrix edge are clamped to the last row (their accumulators are never
+  // stored); chunks past K read a block of zeros instead.
+  const int g_row = lane >> 3, g_slot = lane & 7;
+  // byte offsets from the matrix base (the host checks that they fit 32 bits): the address
+  // of a load is then a uniform 64-bit base, advanced per k-tile by scalar code, plus a
+  // per-lane offset that never changes
+  uint32_t off_a[LA], off_b[LB];
+  int ka[LA], kb[LB];        // element offset of this lane's chunk inside a k-tile
+  int dst_a[LA], dst_b[LB];  // LDS byte offset of the group inside a unit
 #pragma unroll
-  for (int i = 0; i < LPT; ++i) {
+  for (int i = 0; i < LA; ++i) {
     // when the groups do not divide over the wavefronts the surplus loads repeat the last
-    // group (same bytes to the same place), so every wavefront issues LPT loads per tile
-    const int grp = (wave + i * NW) < GROUPS ? (wave + i * NW) : GROUPS - 1;
-    const int row = grp * 16 + g_row;        // row in the stacked [X tile ; W tile]
-    const int chunk = g_slot ^ ((row >> 2) & 3);
-    src_k[i] = chunk * 8;
-    dst[i] = grp * 1024;
-    if (row < BM) {
-      int gm = m0 + row;
-      gm = gm < a.M ? gm : a.M - 1;
-      src[i] = a.A + (size_t)gm * a.lda + chunk * 8;
-    } else {
-      const int wr = row - BM;
-      int gn;
-      if (EPI == EPI_SWIGLU) {
-        const int blk = wr >> 5;
-        int col = n0 + (blk >> 1) * 32 + (wr & 31);
-        col = col < a.N ? col : a.N - 1;
-        gn = col + ((blk & 1) ? a.N : 0);
-      } else {
-        gn = n0 + wr;
-        gn = gn < a.N ? gn : a.N - 1;
-      }
-      src[i] = a.B + (size_t)gn * a.ldb + chunk * 8;
-    }
+    // group (same bytes to the same place), so every wavefront issues LA loads per panel
+    const int grp = (wave + i * NW) < GA ? (wave + i * NW) : GA - 1;
+    const int row = grp * 8 + g_row;
+    const int chunk = g_slot ^ ((row >> 1) & 7);
+    ka[i] = chunk * 8;
+    dst_a[i] = grp * 1024;
+    int gm = m0 + row;
+    gm = gm < a.M ? gm : a.M - 1;
+    off_a[i] = (uint32_t)(((size_t)gm * a.lda + chunk * 8) * 2);
   }
-  auto issue = [&](int kt) {
-    unsigned char *stage = smem + (kt & (STAGES - 1)) * STAGE;
-    const int k0 = kt * BK;
 #pragma unroll
-    for (int i = 0; i < LPT; ++i) {
-      const uint16_t *p = (k0 + src_k[i] < a.K) ? src[i] + k0 : g_gemm_zero_chunk;
-      __builtin_amdgcn_global_load_lds(reinterpret_cast<const void *>(p), (__attribute__((address_space(3))) void *)(stage + dst[i]), 16, 0, 0);
+  for (int i = 0; i < LB; ++i) {
+    const int grp = (wave + i * NW) < GB ? (wave + i * NW) : GB - 1;
+    const int wr = grp * 8 + g_row;
+    const int chunk = g_slot ^ ((wr >> 1) & 7);
+    kb[i] = chunk * 8;
+    dst_b[i] = grp * 1024;
+    int gn;
+    if (EPI == EPI_SWIGLU) {
+      const int blk = wr >> 5;
+      int col = n0 + (blk >> 1) * 32 + (wr & 31);
+      col = col < a.N ? col : a.N - 1;
+      gn = col + ((blk & 1) ? a.N : 0);
+    } else {
+      gn = n0 + wr;
+      gn = gn < a.N ? gn : a.N - 1;
     }
+    off_b[i] = (uint32_t)(((size_t)gn * a.ldb + chunk * 8) * 2);
+  }
+  // load number i of panel X(kt) / W(kt) into ring slot `slot`; `checked` handles chunks past K
+  auto dma_a = [&](int kt, int slot, int i, auto checked) {
+    const unsigned char *base = reinterpret_cast<const unsigned char *>(a.A) + (size_t)kt * ROWB;
+    const void *p = base + off_a[i];
+    if constexpr (decltype(checked)::value)
+      if (kt * BK + ka[i] >= a.K) p = g_gemm_zero_chunk;
+    __builtin_amdgcn_global_load_lds(p, (__attribute__((address_space(3))) void *)(smem + slot * UNIT + dst_a[i]), 16, 0, 0);
+  };
+  auto dma_b = [&](int kt, int slot, int i, auto checked) {
+    const unsigned char *base = reinterpret_cast<const unsigned char *>(a.B) + (size_t)kt * ROWB;
+    const void *p = base + off_b[i];
+    if constexpr (decltype(checked)::value)
+      if (kt * BK + kb[i] >= a.K) p = g_gemm_zero_chunk;
+    __builtin_amdgcn_global_load_lds(p, (__attribute__((address_space(3))) void *)(smem + slot * UNIT + dst_b[i]), 16, 0, 0);
   };
 
   f32x16_t acc[NI][MI];
@@ -146,62 +167,99 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[ni][mi][r] = 0.f;
 
-  // fragment addresses: tile row of the lane, chunk 2*ks + lg swizzled by ((row >> 2) & 3)
-  const int sw = (lr >> 2) & 3;
+  // fragment addresses: tile row of the lane, chunk 2*ks + lg swizzled by ((row >> 1) & 7)
+  const int sw = (lr >> 1) & 7;
   const int xfrag = (wm0 + lr) * ROWB;
-  const int wfrag = X_BYTES + (wn0 + lr) * ROWB;
+  const int wfrag = (wn0 + lr) * ROWB;
 
   const int nk = (a.K + BK - 1) / BK;
-  // Software pipeline.  DMA: tile kt+3 is requested while tile kt is multiplied (a tile
-  // beyond K is all zeros, harmless).  LDS -> registers: the fragments of the next
-  // 16-wide k-step are requested before the MFMAs of the current one are issued, across
-  // tile boundaries too, so the matrix pipe never waits for a whole LDS read phase; this
-  // needs tile kt+1 to have landed when iteration kt starts.
-  auto read_frags = [&](int kt, int ks, bf16x8_t (&xf)[MI], bf16x8_t (&wf)[NI]) {
-    const unsigned char *base = smem + (kt & (STAGES - 1)) * STAGE;
+  constexpr int NF = MI + NI;   // fragment reads per 16-wide k-step
+  constexpr int NMF = MI * NI;  // MFMAs per 16-wide k-step
+  // read number o of k-step ks (16 wide, four per tile) of the panels in ring slots sa, sb
+  auto frag = [&](int sa, int sb, int ks, int o, bf16x8_t (&xf)[MI], bf16x8_t (&wf)[NI]) {
     const int ch = ((ks * 2 + lg) ^ sw) << 4;
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-      xf[mi] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + xfrag + mi * 32 * ROWB + ch));
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-      wf[ni] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(base + wfrag + ni * 32 * ROWB + ch));
+    if (o < MI)
+      xf[o] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(smem + sa * UNIT + xfrag + o * 32 * ROWB + ch));
+    else
+      wf[o - MI] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(smem + sb * UNIT + wfrag + (o - MI) * 32 * ROWB + ch));
   };
-  // MFMAs number `first` .. `last`-1 of the NI x MI block grid of one k-step
-  auto multiply = [&](const bf16x8_t (&xf)[MI], const bf16x8_t (&wf)[NI], int first, int last) {
+  // One k-step: its NMF MFMAs in program order, with the `n_ops` side operations (LDS
+  // reads of the next k-step, DMA requests) dealt out behind the first MFMAs, `per` at a
+  // time, so that the matrix pipe is never left idle behind a run of memory instructions.
+  auto step = [&](const bf16x8_t (&xf)[MI], const bf16x8_t (&wf)[NI], int n_ops, int per, auto &&op) {
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
+    for (int j = 0; j < NMF; ++j) {
+      const int ni = j / MI, mi = j % MI;
+      acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi)
-        if (ni * MI + mi >= first && ni * MI + mi < last)
-          acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
+      for (int q = 0; q < per; ++q)
+        if (j * per + q < n_ops) op(j * per + q);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
-  static_assert(BK == 32 && STAGES == 4, "the pipeline below is written for two k-steps per tile, four stages");
+  auto next_slot = [](int s, int by) { s += by; return s >= NU ? s - NU : s; };
+  static_assert(NU == 5, "the pipeline below is written for a ring of five panels");
+  // Software pipeline.  Panels are numbered in issue order, X(0) W(0) X(1) W(1) ..., and
+  // panel u lives in ring slot u % 5.  Once the last fragments of tile kt are in
+  // registers, at the one barrier of the iteration, W(kt+2) and X(kt+3) are requested
+  // into the two slots that tile kt frees.  LDS -> registers: the fragments of the next
+  // 16-wide k-step are requested while the MFMAs of the current one are issued, across
+  // tile boundaries too, so the matrix pipe never waits for a whole LDS read phase.
+  // The compiler counts an LDS-DMA load as a pending LDS operation of unknown order, so
+  // every wait it places before an MFMA is lgkmcnt(0); waiting explicitly at the start of
+  // a k-step, for reads issued during the first MFMAs of the previous one, keeps those
+  // waits from covering reads that were only just issued.
+  constexpr int LGKM0 = waitcnt_imm(63, true);
+  constexpr int PER_F = (NF + NMF - 1) / NMF > 2 ? (NF + NMF - 1) / NMF : 2;
+  constexpr int N_P = NF + LB + LA;
+  constexpr int PER_P = (N_P + NMF - 1) / NMF > 2 ? (N_P + NMF - 1) / NMF : 2;
   bf16x8_t xa[MI], wa[NI], xb[MI], wb[NI];
 #pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s) issue(s);
-  __builtin_amdgcn_s_waitcnt(waitcnt_imm((STAGES - 2) * LPT, true));  // tile 0 has landed
+  for (int i = 0; i < LA; ++i) dma_a(0, 0, i, Yes{});
+#pragma unroll
+  for (int i = 0; i < LB; ++i) dma_b(0, 1, i, Yes{});
+#pragma unroll
+  for (int i = 0; i < LA; ++i) dma_a(1, 2, i, Yes{});
+#pragma unroll
+  for (int i = 0; i < LB; ++i) dma_b(1, 3, i, Yes{});
+#pragma unroll
+  for (int i = 0; i < LA; ++i) dma_a(2, 4, i, Yes{});
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LA + LB, true));  // tile 0 has landed
   __builtin_amdgcn_s_barrier();
-  read_frags(0, 0, xa, wa);
-  for (int kt = 0; kt < nk; ++kt) {
-    // tiles <= kt+1 have landed once this wavefront's older loads are done and every
-    // wavefront has reached the barrier; the barrier also frees the stage of tile kt-1
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm((STAGES - 3) * LPT, true));
+  int sa = 0, sb = 1;  // slots of the tile being multiplied
+#pragma unroll
+  for (int o = 0; o < NF; ++o) frag(sa, sb, 0, o, xa, wa);
+  auto tile = [&](int kt, auto checked) {
+    __builtin_amdgcn_s_waitcnt(LGKM0);
+    step(xa, wa, NF, PER_F, [&](int o) { frag(sa, sb, 1, o, xb, wb); });
+    __builtin_amdgcn_s_waitcnt(LGKM0);
+    step(xb, wb, NF, PER_F, [&](int o) { frag(sa, sb, 2, o, xa, wa); });
+    __builtin_amdgcn_s_waitcnt(LGKM0);
+    step(xa, wa, NF, PER_F, [&](int o) { frag(sa, sb, 3, o, xb, wb); });
+    // Every fragment of tile kt is in registers once the LDS reads have returned, and
+    // tile kt+1 has landed once this wavefront's loads other than the youngest panel,
+    // X(kt+2), are done; after the barrier both hold for every wavefront, so the two
+    // slots of tile kt can be refilled and tile kt+1 can be read.
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(LA, true));
     __builtin_amdgcn_s_barrier();
-    issue(kt + STAGES - 1);
-    read_frags(kt, 1, xb, wb);
-    __builtin_amdgcn_sched_barrier(0);
-    multiply(xa, wa, 0, NI * MI);
-    // LDS reads return in order: start the second k-step (its operands were requested a whole
-    // MFMA batch ago) before requesting the next tile's first k-step into the registers just freed
-    multiply(xb, wb, 0, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(kt + 1, 0, xa, wa);
-    __builtin_amdgcn_sched_barrier(0);
-    multiply(xb, wb, 2, NI * MI);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  // drain the look-ahead loads (zeros or clamped rows) before the stage memory is released
+    const int na = next_slot(sa, 2), nb = next_slot(sb, 2);
+    step(xb, wb, N_P, PER_P, [&](int o) {
+      if (o < NF)
+        frag(na, nb, 0, o, xa, wa);
+      else if (o < NF + LB)
+        dma_b(kt + 2, sa, o - NF, checked);
+      else
+        dma_a(kt + 3, sb, o - NF - LB, checked);
+    });
+    sa = na;
+    sb = nb;
+  };
+  int kt = 0;
+  const int n_plain = a.K / BK - 3;  // tiles kt for which W(kt+2) and X(kt+3) lie wholly inside K
+  for (; kt < n_plain; ++kt) tile(kt, No{});
+  for (; kt < nk; ++kt) tile(kt, Yes{});
+  // drain the look-ahead loads (zeros or clamped rows) before the LDS is released
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
 
   // ---- epilogues ---------------------------------------------------------------
@@ -374,7 +432,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH>
 hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
   constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  constexpr int LDS = STAGES * (BM + BN) * BK * 2;
+  constexpr int LDS = NU * (BM > BN ? BM : BN) * BK * 2;
   auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI, DH>;
   static bool configured = false;
   if (!configured) {
@@ -392,7 +450,7 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
 // Tile shapes.  BIG: 256x256, 8 wavefronts.  TALL: 160x256, 4 wavefronts of 160x64: 2560 (and
 // 5120) rows by 4096 (8192) columns then make exactly one (four) full rounds of 256
 // workgroups where 256x256 tiles leave 38 % (17 %) of the CUs idle.  SMALL: 128x128.
-enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3 };
+enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3, V_QUAD = 4 };
 constexpr int N_CU = 256;
 
 int g_forced_variant = V_AUTO;
@@ -423,6 +481,7 @@ template <int EPI, int DH_BIG_M, int DH_BIG_N>
 hipError_t launch_variant(const GemmArgs &a, int v, hipStream_t stream) {
   if (v == V_BIG) return launch_one<256, 256, DH_BIG_M, DH_BIG_N, EPI, (DH_BIG_M == 4 ? 128 : 64)>(a, stream);
   if (v == V_TALL) return launch_one<160, 256, 1, 4, EPI, 64>(a, stream);
+  if (v == V_QUAD) return launch_one<256, 256, 2, 2, EPI, 64>(a, stream);
   return launch_one<128, 128, 2, 2, EPI, 64>(a, stream);
 }
 
@@ -433,11 +492,15 @@ void gemm_force_variant(int v) { g_forced_variant = v; }
 int gemm_ss_parts(const GemmArgs &a, int epilogue, int dh) {
   const int v = choose_variant(a.M, a.N, epilogue, dh, a.n_cu);
   // partial row sums: one per (column tile, wavefront column)
+  if (v == V_QUAD) return ((a.N + 255) / 256) * 2;
   return v == V_SMALL ? ((a.N + 127) / 128) * 2 : ((a.N + 255) / 256) * 4;
 }
 
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream) {
   const int b_rows = (epilogue == EPI_SWIGLU) ? 2 * a.N : a.N;
+  // the kernels address operand rows with 32-bit byte offsets from the matrix base
+  if ((size_t)a.M * a.lda * 2 >= ((size_t)1 << 32) || (size_t)b_rows * a.ldb * 2 >= ((size_t)1 << 32))
+    return hipErrorInvalidValue;
   const int v = choose_variant(a.M, b_rows, epilogue, dh, a.n_cu);
   switch (epilogue) {
     case EPI_PLAIN: return launch_variant<EPI_PLAIN, 2, 4>(a, v, stream);
@@ -446,11 +509,13 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stre
     case EPI_SWIGLU: return launch_variant<EPI_SWIGLU, 2, 4>(a, v, stream);
     case EPI_QKV:
       if (dh == 128)
-        return v == V_BIG ? launch_one<256, 256, 4, 2, EPI_QKV, 128>(a, stream)
-                          : launch_one<128, 128, 4, 1, EPI_QKV, 128>(a, stream);
+        return v == V_QUAD  ? launch_one<256, 256, 2, 2, EPI_QKV, 128>(a, stream)
+               : v == V_BIG ? launch_one<256, 256, 4, 2, EPI_QKV, 128>(a, stream)
+                            : launch_one<128, 128, 4, 1, EPI_QKV, 128>(a, stream);
       if (dh == 64)
-        return v == V_BIG ? launch_one<256, 256, 2, 4, EPI_QKV, 64>(a, stream)
-                          : launch_one<128, 128, 2, 2, EPI_QKV, 64>(a, stream);
+        return v == V_QUAD  ? launch_one<256, 256, 2, 2, EPI_QKV, 64>(a, stream)
+               : v == V_BIG ? launch_one<256, 256, 2, 4, EPI_QKV, 64>(a, stream)
+                            : launch_one<128, 128, 2, 2, EPI_QKV, 64>(a, stream);
       return hipErrorInvalidValue;
     default:
       return hipErrorInvalidValue;

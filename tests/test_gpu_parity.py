@@ -116,6 +116,39 @@ def test_attention_alone(lib, shape, seed):
     assert maxrel <= MAXREL and mae <= 2 * MAE
 
 
+@pytest.mark.parametrize("shape", [W.LayerShape(256, 4, 2, 64, 256), W.LayerShape(512, 8, 2, 128, 256),
+                                   W.LayerShape(1024, 8, 1, 128, 256)])
+@pytest.mark.parametrize("members", [[2, 9], [5, 17, 33], [8, 16, 70]])
+def test_attention_node_member_counts(lib, shape, members):
+    # prefix nodes whose members fill one to several blocks of 16 query rows, some of
+    # them partly: a root of 35 tokens per member count, one child node under the first
+    import torch
+    nodes, seqs = [], [(7, 40, -1)]
+    rng = np.random.default_rng(sum(members))
+    for k, n in enumerate(members):
+        root = len(nodes)
+        nodes.append((-1, 2 + k))
+        leaf = root
+        if k == 0:
+            nodes.append((root, 3))
+            leaf = root + 1
+        for j in range(n):
+            shared = 16 * ((2 + k) + (3 if leaf != root else 0))
+            nd = leaf if j < (n + 1) // 2 or leaf == root else root
+            sh = shared if nd == leaf else 16 * (2 + k)
+            seqs.append((1, sh + 1 + int(rng.integers(0, 90)), nd))
+    # members of the child node come first within the root's run: already so by construction
+    batch = W.assemble_batch(16, seqs, 1, nodes, rng)
+    tens = W.make_tensors(shape, batch, 5)
+    q = W.round_to_bf16(rng.standard_normal((batch.n_rows, shape.n_q_heads * shape.head_dim), dtype=np.float32))
+    layer = lib.Layer(shape, device=0)
+    pool = layer.pack_pool(tens.k_pool, tens.v_pool)
+    out = to_np(layer.attention(batch, torch.from_numpy(q).cuda().to(torch.bfloat16), pool, batch.n_pages))
+    ref = attention_reference(shape, batch, q.astype(np.float64), tens.k_pool, tens.v_pool)
+    maxrel, mae = errs(out, ref)
+    assert maxrel <= MAXREL and mae <= 2 * MAE
+
+
 def test_attention_ignores_stale_slots(lib):
     # slots past kv_len in the last page hold NaN bit patterns: they must never reach the output
     import torch
