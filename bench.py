@@ -21,6 +21,26 @@ PEAK_MFMA_BF16 = 2.5e15  # dense bf16 MFMA, FLOP/s (MI355X datasheet)
 PEAK_HBM = 8.0e12        # HBM3E, B/s
 
 
+def measured_traffic(profile_name, sources):
+    """HBM-side bytes per launch of the roofline kernel from the committed counter summary under
+    profiles/, or None when the kernel's sources have changed since the counters were taken."""
+    import hashlib
+    import re
+    root = os.path.dirname(os.path.abspath(__file__))
+    try:
+        text = open(os.path.join(root, "profiles", profile_name)).read()
+        h = hashlib.sha256()
+        for f in sources:
+            h.update(open(os.path.join(root, "paper_2411_16102_amd", "csrc", f), "rb").read())
+    except OSError:
+        return None
+    sha = re.search(r"source_sha256:\s*([0-9a-f]{64})", text)
+    val = re.search(r"traffic_bytes_per_launch:\s*(\d+)", text)
+    if not sha or not val or sha.group(1) != h.hexdigest():
+        return None
+    return int(val.group(1))
+
+
 def cpu_baseline(shape, batch, tens, target_flops=1.2e12):
     """The oracle, as it stands, on a bounded sample of the same batch: whole
     prefill segments and evenly spaced decode sequences in the batch's own
@@ -150,7 +170,10 @@ def main():
     if bound == "mfma":
         roofline = {"bound": "mfma", "kernel": "gemm_gate_up (SwiGLU epilogue)",
                     "achieved": gu_flops_per_launch / (gu_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_BF16 / 1e12,
-                    "unit": "TFLOP/s", "traffic": None}
+                    "unit": "TFLOP/s",
+                    "traffic": (measured_traffic("blended_8b_gemm_gate_up_hbm_traffic.txt",
+                                                 ["gemm.hip", "gemm.hpp", "common.hpp"])
+                                if args.workload == "blended_8b" else None)}
     else:
         dec_ms = prof["attn_decode"][0] / max(1, prof["attn_decode"][1])
         kv_bytes = work["kv_tokens_once"] * shape.kv_bytes_per_token
