@@ -1,7 +1,8 @@
 /*
  * blendstep_builder.h - host-side batch builder: BlendServe's resource-aware
- * prefix tree (Section 5.1), layer-wise sort (Section 5.2, Algorithm 1) and dual
- * scan with memory partition (Section 5.3, Algorithm 3), in the single-step form
+ * prefix tree (Section 5.1), layer-wise sort and conditional node splitting
+ * (Section 5.2, Algorithms 1 and 2) and dual scan with memory partition
+ * (Section 5.3, Algorithm 3), in the single-step form
  * that feeds bs_blend_step.  Pure CPU code: no HIP call is made.
  *
  * All pointers are HOST memory.  Functions return 0 or a negative bs_status
@@ -48,6 +49,28 @@ int bs_builder_add(bs_builder *b, const int32_t *tokens, int32_t n_tokens, int32
  * A1 B2 against A2 B1 in 128-bit integers; B = 0 is +infinity; ties to the subtree
  * with the smaller request index), and number the nodes in DFS pre-order. */
 int bs_builder_finalize(bs_builder *b);
+
+/* Conditional node splitting (Section 5.2, Algorithm 2, with the stopping conditions of
+ * Section 5.4).  Rounds of: stop if the leaf densities (p + d) / (2 p d + d^2), left to
+ * right, are non-increasing (C1); take as outliers the leaves l below a non-root node X
+ * such that X without l would change places with the sibling Q next to it while l belongs
+ * on the far side of all of Q (the density of a node is sum A / sum B, so one
+ * memory-intensive request drags every subtree that holds it); if there is none, the
+ * leaves outside a longest non-increasing subsequence (patience procedure) that are not
+ * already direct children of the root - where the outlier of an adjacent violation is
+ * such a child, its neighbour instead; of those whose shared prefix (the tokens recomputed once
+ * they stop sharing it) is at most t, cheapest first (ties: smaller request index), cut as
+ * many as the total budget of recomputed tokens allows (budget_tokens < 0: no limit) and
+ * re-insert them as direct children of the root; none taken = stop (C2); rebuild, re-sort.
+ * Every leaf moves at most once.  Call after bs_builder_finalize; the tree, the leaf
+ * order and the batches reflect the result.  `info` may be NULL. */
+typedef struct bs_split_info {
+  int32_t n_split;            /* leaves relocated by this call */
+  int32_t rounds;             /* rounds that relocated at least one leaf */
+  int32_t monotone;           /* 1 if the final leaf densities are non-increasing */
+  int64_t recompute_tokens;   /* sum of the relocated leaves' shared prefix lengths */
+} bs_split_info;
+int bs_builder_split(bs_builder *b, int64_t t, int64_t budget_tokens, bs_split_info *info);
 
 /* The sorted tree in DFS pre-order.  bs_builder_tree_size gives the array lengths;
  * bs_builder_tree fills caller-provided arrays: per node its parent (-1 for the

@@ -37,13 +37,47 @@ exact integer / rational arithmetic where a decision depends on a comparison.
      at least two admitted decode members and at least one whole KV page, each
      node's pages allocated once.
 
+  6. Conditional node splitting (Section 5.2, Algorithm 2, and the stopping conditions
+     of Section 5.4).  The printed pseudo-code and the prose disagree (the listing
+     splits when prefix length x children exceeds t and divides t among children; the
+     text relocates a leaf when its recomputation cost is BELOW t); this follows the
+     text and the convergence argument.  One round:
+       a. the leaf densities rho(r) = (p + d) / (2 p d + d^2), left to right, are
+          examined; if they are non-increasing the search stops (C1);
+       b. outliers, first kind (the figure's case: a request of low density among
+          compute-intensive ones drags the density of every subtree that holds it,
+          since rho of a node is sum A / sum B): a leaf l below a non-root node X such
+          that X without l would change places with the sibling Q next to it, while l
+          itself belongs on the far side of all of Q (X jumps left over Q and l is
+          less dense than every leaf of Q, or the mirror image);
+          second kind, only when there is none of the first: the leaves outside a
+          longest non-increasing subsequence (patience procedure of
+          `longest_non_increasing`, which fixes the choice among equally long ones); a
+          leaf that is already a direct child of the root cannot move, so where such a
+          leaf is the outlier of an adjacent violation rho(i) < rho(i+1), its
+          neighbour is taken instead;
+       c. a candidate's cost is its shared prefix length (the tokens recomputed once
+          it no longer shares them); candidates with cost <= t are taken cheapest
+          first (ties: smaller request index) while the total stays within the
+          budget; none taken = stop (C2);
+       d. every taken leaf is cut from its parent and re-inserted as a direct child of
+          the root with its whole prompt as its own segment; the trie of the others is
+          rebuilt (a parent left with one child merges with it), densities are
+          recomputed and Algorithm 1 runs again.
+     Every leaf is split at most once, so there are at most N_leaf rounds.
+
 Pins (tests/test_oracle_builder.py): the memory-partition example printed with
 Figure 6; the batch-density = request-density identity of Section 4.2; linearity of
 the memory model in loaded tokens (the ratios of Table 1); brute-force shared-prefix
 lengths, distinct-token counts and sibling order on small random pools; the
 invariants that sorting keeps every parent's child set and that every node's
 requests are contiguous in leaf order.  Absolute densities of the paper's traces
-need its datasets: parity unpinned for those.
+need its datasets: parity unpinned for those.  Node splitting: pinned by its bounds
+and invariants only (no round without a split, at most N_leaf splits, t = 0 changes
+nothing, unlimited t ends in a non-increasing leaf order, sharing lost = the sum of the
+costs, the worked example of Figure 3 where the low-density request moves to the right
+end); which leaves are outliers where several choices are equally good is this
+file's reading: parity unpinned for that choice.
 """
 from __future__ import annotations
 
@@ -84,6 +118,8 @@ class TNode:
     sum_p: int = 0
     sum_d: int = 0
     min_req: int = 0
+    lo: Tuple[int, int] = (0, 1)    # (A, B) of the least / most compute-intensive leaf below
+    hi: Tuple[int, int] = (0, 1)
 
 
 def density_fraction(A: int, B: int) -> Optional[Fraction]:
@@ -124,20 +160,124 @@ def memory_partition(rho_rt: float, rho_l: float, rho_r: float, M: float) -> Tup
     return m_l, M - m_l
 
 
+def longest_non_increasing(keys: Sequence[Tuple[int, int]]) -> List[int]:
+    """Indices of a longest non-increasing subsequence of densities (A, B), by patience:
+    pile k holds the index of the densest last element of any non-increasing subsequence of
+    length k + 1 seen so far; a new element goes to the first pile whose last element is
+    strictly less dense than it (else it opens a new pile) and remembers the top of the
+    pile before; the answer is read back from the top of the last pile."""
+    tails: List[int] = []
+    pred = [-1] * len(keys)
+    for i, k in enumerate(keys):
+        lo, hi = 0, len(tails)
+        while lo < hi:                              # first pile whose tail is strictly less dense than k
+            mid = (lo + hi) // 2
+            if denser(k, keys[tails[mid]]) > 0:
+                hi = mid
+            else:
+                lo = mid + 1
+        pred[i] = tails[lo - 1] if lo > 0 else -1
+        if lo == len(tails):
+            tails.append(i)
+        else:
+            tails[lo] = i
+    out: List[int] = []
+    i = tails[-1] if tails else -1
+    while i >= 0:
+        out.append(i)
+        i = pred[i]
+    out.reverse()
+    return out
+
+
 class BuilderOracle:
     def __init__(self, cm: CostModel, requests: Sequence[Request]):
         self.cm = cm
         self.reqs = list(requests)
         self.nodes: List[TNode] = []
+        self.detached: set = set()             # requests re-inserted under the root by node splitting
+        self._rebuild()
+
+    def _rebuild(self):
+        self.nodes = []
         self._build_trie()
+        for r in sorted(self.detached):
+            leaf = len(self.nodes)
+            self.nodes.append(TNode(0, len(self.reqs[r].tokens), 0, req=r))
+            self.nodes[0].children.append(leaf)
         self._annotate(0)
         self._layer_sort(0)
         self._number()
 
+    # -- step 6: conditional node splitting ----------------------------------------------
+    def leaf_keys(self) -> List[Tuple[int, int]]:
+        leaf_of = {nd.req: nd for nd in self.nodes if nd.req >= 0}
+        return [(leaf_of[r].A, leaf_of[r].B) for r in self.leaf_order]
+
+    def split(self, t: int, budget: int = -1):
+        """Relocate outlier leaves whose shared prefix is at most t tokens, spending at most
+        `budget` recomputed tokens in total (< 0: no limit)."""
+        spent = rounds = n_split = 0
+        while True:
+            keys = self.leaf_keys()
+            n = len(keys)
+            kept = set(longest_non_increasing(keys))
+            if len(kept) == n:
+                break                                              # C1
+            leaf_of = {nd.req: nd for nd in self.nodes if nd.req >= 0}
+            movable = [leaf_of[r].parent != 0 for r in self.leaf_order]
+            cand = set()
+            for i, r in enumerate(self.leaf_order):                # first kind
+                lf = leaf_of[r]
+                if not movable[i]:
+                    continue
+                gone = (lf.A - lf.start, lf.B)                      # what every ancestor loses with the leaf
+                x = lf.parent
+                while x != 0 and i not in cand:
+                    X = self.nodes[x]
+                    sib = self.nodes[X.parent].children
+                    j = sib.index(x)
+                    rest = (X.A - gone[0], X.B - gone[1])
+                    if j > 0:
+                        Q = self.nodes[sib[j - 1]]
+                        if denser(rest, (Q.A, Q.B)) > 0 and denser((lf.A, lf.B), Q.lo) < 0:
+                            cand.add(i)
+                    if j + 1 < len(sib):
+                        Q = self.nodes[sib[j + 1]]
+                        if denser(rest, (Q.A, Q.B)) < 0 and denser((lf.A, lf.B), Q.hi) > 0:
+                            cand.add(i)
+                    x = X.parent
+            if not cand:                                           # second kind
+                cand = {i for i in range(n) if i not in kept and movable[i]}
+                for i in range(n - 1):
+                    if denser(keys[i], keys[i + 1]) < 0 and i not in cand and (i + 1) not in cand:
+                        # the outlier of this violation sits under the root already: move its neighbour
+                        if i not in kept and movable[i + 1]:
+                            cand.add(i + 1)
+                        elif (i + 1) not in kept and movable[i]:
+                            cand.add(i)
+            todo = sorted((leaf_of[self.leaf_order[i]].start, self.leaf_order[i]) for i in cand
+                          if leaf_of[self.leaf_order[i]].start <= t)
+            took = 0
+            for cost, r in todo:
+                if budget >= 0 and spent + cost > budget:
+                    break
+                self.detached.add(r)
+                spent += cost
+                took += 1
+            if took == 0:
+                break                                              # C2
+            n_split += took
+            rounds += 1
+            self._rebuild()
+        keys = self.leaf_keys()
+        monotone = all(denser(keys[i], keys[i + 1]) >= 0 for i in range(len(keys) - 1))
+        return dict(n_split=n_split, rounds=rounds, recompute_tokens=spent, monotone=monotone)
+
     # -- step 1: compressed trie through sorted prompts and longest common prefixes --------
     def _build_trie(self):
         reqs = self.reqs
-        order = sorted(range(len(reqs)), key=lambda i: (list(reqs[i].tokens), i))
+        order = sorted((i for i in range(len(reqs)) if i not in self.detached), key=lambda i: (list(reqs[i].tokens), i))
         self.nodes = [TNode(0, 0, -1)]          # root: empty segment
         stack = [0]                             # path of internal nodes, root first
         prev_tokens: Optional[Sequence[int]] = None
@@ -180,13 +320,16 @@ class BuilderOracle:
             own = nd.end - nd.start
             nd.B = 2 * p * d + d * d
             below = own + d                       # distinct tokens strictly below the node's start
+            nd.lo = nd.hi = (nd.start + below, nd.B)
         else:
             below = nd.end - nd.start
             nd.n_req = nd.sum_p = nd.sum_d = nd.B = 0
             nd.min_req = 1 << 62
-            for c in nd.children:
+            for k, c in enumerate(nd.children):
                 self._annotate(c)
                 ch = self.nodes[c]
+                nd.lo = ch.lo if k == 0 or denser(ch.lo, nd.lo) < 0 else nd.lo
+                nd.hi = ch.hi if k == 0 or denser(ch.hi, nd.hi) > 0 else nd.hi
                 nd.n_req += ch.n_req
                 nd.sum_p += ch.sum_p
                 nd.sum_d += ch.sum_d

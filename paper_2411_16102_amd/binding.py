@@ -43,6 +43,11 @@ class BatchDesc(C.Structure):
                 ("seq_leaf_node", _i32p)]
 
 
+class SplitInfo(C.Structure):
+    _fields_ = [("n_split", C.c_int32), ("rounds", C.c_int32), ("monotone", C.c_int32),
+                ("recompute_tokens", C.c_int64)]
+
+
 class CostModel(C.Structure):
     _fields_ = [("p_model", C.c_int64), ("kv_bytes", C.c_int64), ("compute", C.c_double), ("bandwidth", C.c_double),
                 ("mem_bytes", C.c_int64), ("page_size", C.c_int32)]
@@ -118,6 +123,7 @@ def raw():
         lib.bs_builder_last_error.restype = C.c_char_p
         lib.bs_builder_add.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_int32, C.c_int32]
         lib.bs_builder_finalize.argtypes = [C.c_void_p]
+        lib.bs_builder_split.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.POINTER(SplitInfo)]
         lib.bs_builder_tree_size.argtypes = [C.c_void_p, _i32p, _i32p]
         lib.bs_builder_tree.argtypes = [C.c_void_p] + [_i32p] * 6 + [_i64p, _i64p, _i32p]
         lib.bs_builder_next_batch.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.POINTER(C.POINTER(BatchOwned))]
@@ -345,6 +351,13 @@ class Builder:
 
     def finalize(self):
         self._check(self.lib.bs_builder_finalize(self.h))
+
+    def split(self, t, budget_tokens=-1):
+        """Conditional node splitting; returns what bs_split_info reports."""
+        info = SplitInfo()
+        self._check(self.lib.bs_builder_split(self.h, int(t), int(budget_tokens), C.byref(info)))
+        return dict(n_split=info.n_split, rounds=info.rounds, monotone=bool(info.monotone),
+                    recompute_tokens=info.recompute_tokens)
 
     def tree(self):
         nn, nr = C.c_int32(), C.c_int32()

@@ -1,5 +1,6 @@
-// Host-side batch builder: resource-aware prefix tree, layer-wise sort and dual
-// scan of BlendServe (Sections 5.1-5.3, Algorithms 1 and 3), single-step form.
+// Host-side batch builder: resource-aware prefix tree, layer-wise sort, conditional
+// node splitting and dual scan of BlendServe (Sections 5.1-5.4, Algorithms 1-3),
+// single-step form.
 // Plain C++, no GPU calls.  Built with floating-point contraction off: the few
 // double-precision expressions are evaluated exactly as written.
 #include <algorithm>
@@ -36,6 +37,7 @@ struct Grow {
 struct Node {
   int32_t parent, start, end, req, first_leaf, leaf_count;
   int64_t A, B, n_req, sum_p, sum_d;
+  int64_t lo_a, lo_b, hi_a, hi_b;    // (A, B) of the least / most compute-intensive leaf below
   int32_t min_req;
   std::vector<int32_t> kids;
 };
@@ -49,6 +51,7 @@ struct bs_builder {
   std::vector<Node> nodes;          // valid after finalize
   std::vector<int32_t> leaf_order;
   std::vector<int32_t> leaf_node;   // request -> node
+  std::vector<char> detached;       // request was re-inserted under the root by node splitting
   bool finalized = false;
 };
 
@@ -140,9 +143,139 @@ struct Grower {
 struct Tmp {  // unsorted finished tree
   int32_t parent, start, end, req;
   int64_t A = 0, B = 0, n_req = 0, sum_p = 0, sum_d = 0;
+  int64_t lo_a = 0, lo_b = 1, hi_a = 0, hi_b = 1;
   int32_t min_req = 0;
   std::vector<int32_t> kids;
 };
+
+// Build the sorted, numbered tree over the requests: the trie of those not detached, the
+// detached ones as direct children of the root with their whole prompt as own segment.
+void rebuild(bs_builder *b) {
+  const int32_t nr = (int32_t)b->reqs.size();
+  b->detached.resize(nr, 0);
+  Grower gr(b->reqs);
+  for (int32_t r = 0; r < nr; ++r)
+    if (!b->detached[r]) gr.insert(r);
+  // flatten: requests that end at an internal node become leaves with an empty segment
+  std::vector<Tmp> t(gr.g.size());
+  for (size_t i = 0; i < gr.g.size(); ++i) {
+    t[i].parent = gr.g[i].parent; t[i].start = gr.g[i].start; t[i].end = gr.g[i].end; t[i].req = gr.g[i].req;
+    for (auto &kv : gr.g[i].kids) t[i].kids.push_back(kv.second);
+  }
+  for (size_t i = 0; i < gr.g.size(); ++i)
+    for (int32_t r : gr.g[i].ends_here) {
+      Tmp leaf;
+      leaf.parent = (int32_t)i; leaf.start = leaf.end = gr.g[i].end; leaf.req = r;
+      t.push_back(leaf);
+      t[i].kids.push_back((int32_t)t.size() - 1);
+    }
+  for (int32_t r = 0; r < nr; ++r)
+    if (b->detached[r]) {
+      Tmp leaf;
+      leaf.parent = 0; leaf.start = 0; leaf.end = (int32_t)b->reqs[r].tok.size(); leaf.req = r;
+      t.push_back(leaf);
+      t[0].kids.push_back((int32_t)t.size() - 1);
+    }
+  // bottom-up annotation in reverse creation order is not enough (splits re-parent), so walk explicitly
+  std::vector<int32_t> order;  // pre-order
+  order.reserve(t.size());
+  {
+    std::vector<int32_t> st{0};
+    while (!st.empty()) {
+      const int32_t n = st.back(); st.pop_back();
+      order.push_back(n);
+      for (int32_t c : t[n].kids) st.push_back(c);
+    }
+  }
+  for (size_t k = order.size(); k-- > 0;) {
+    Tmp &n = t[order[k]];
+    int64_t below;
+    if (n.req >= 0) {
+      const Req &r = b->reqs[n.req];
+      const int64_t p = (int64_t)r.tok.size(), d = r.d_est;
+      n.n_req = 1; n.sum_p = p; n.sum_d = d; n.min_req = n.req;
+      n.B = 2 * p * d + d * d;
+      below = (n.end - n.start) + d;
+      n.lo_a = n.hi_a = n.start + below; n.lo_b = n.hi_b = n.B;
+    } else {
+      below = n.end - n.start;
+      n.min_req = std::numeric_limits<int32_t>::max();
+      bool first = true;
+      for (int32_t c : n.kids) {
+        const Tmp &ch = t[c];
+        if (first || cmp_density(ch.lo_a, ch.lo_b, n.lo_a, n.lo_b) < 0) { n.lo_a = ch.lo_a; n.lo_b = ch.lo_b; }
+        if (first || cmp_density(ch.hi_a, ch.hi_b, n.hi_a, n.hi_b) > 0) { n.hi_a = ch.hi_a; n.hi_b = ch.hi_b; }
+        first = false;
+        n.n_req += ch.n_req; n.sum_p += ch.sum_p; n.sum_d += ch.sum_d; n.B += ch.B;
+        n.min_req = std::min(n.min_req, ch.min_req);
+        below += ch.A - ch.start;
+      }
+    }
+    n.A = n.start + below;
+  }
+  // Algorithm 1: order every node's children by density, compute-intensive first
+  for (Tmp &n : t)
+    std::sort(n.kids.begin(), n.kids.end(), [&](int32_t x, int32_t y) {
+      const int c = cmp_density(t[x].A, t[x].B, t[y].A, t[y].B);
+      if (c) return c > 0;
+      return t[x].min_req < t[y].min_req;
+    });
+  // DFS pre-order numbering of the sorted tree
+  b->nodes.clear();
+  b->leaf_order.clear();
+  b->leaf_node.assign(nr, -1);
+  std::vector<int32_t> new_id(t.size(), -1);
+  struct Frame { int32_t n; size_t next; };
+  std::vector<Frame> st;
+  auto open = [&](int32_t n, int32_t parent_new) {
+    Node out;
+    out.parent = parent_new; out.start = t[n].start; out.end = t[n].end; out.req = t[n].req;
+    out.first_leaf = (int32_t)b->leaf_order.size(); out.leaf_count = 0;
+    out.A = t[n].A; out.B = t[n].B; out.n_req = t[n].n_req; out.sum_p = t[n].sum_p; out.sum_d = t[n].sum_d;
+    out.min_req = t[n].min_req;
+    out.lo_a = t[n].lo_a; out.lo_b = t[n].lo_b; out.hi_a = t[n].hi_a; out.hi_b = t[n].hi_b;
+    new_id[n] = (int32_t)b->nodes.size();
+    b->nodes.push_back(out);
+    if (t[n].req >= 0) { b->leaf_node[t[n].req] = new_id[n]; b->leaf_order.push_back(t[n].req); }
+    st.push_back({n, 0});
+  };
+  open(0, -1);
+  while (!st.empty()) {
+    Frame &f = st.back();
+    if (f.next < t[f.n].kids.size()) {
+      const int32_t c = t[f.n].kids[f.next++];
+      const int32_t me = new_id[f.n];
+      open(c, me);
+      b->nodes[me].kids.push_back(new_id[c]);
+    } else {
+      Node &nd = b->nodes[new_id[f.n]];
+      nd.leaf_count = (int32_t)b->leaf_order.size() - nd.first_leaf;
+      st.pop_back();
+    }
+  }
+}
+
+// Indices of a longest non-increasing subsequence of the densities (A[i], B[i]), by patience:
+// pile k holds the index of the densest last element of any such subsequence of length k + 1
+// seen so far; a new element goes to the first pile whose last element is strictly less dense
+// (else it opens a new pile) and remembers the top of the pile before.
+std::vector<int32_t> longest_non_increasing(const std::vector<int64_t> &A, const std::vector<int64_t> &B) {
+  const int32_t n = (int32_t)A.size();
+  std::vector<int32_t> tails, pred(n, -1);
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t lo = 0, hi = (int32_t)tails.size();
+    while (lo < hi) {
+      const int32_t mid = (lo + hi) / 2;
+      if (cmp_density(A[i], B[i], A[tails[mid]], B[tails[mid]]) > 0) hi = mid; else lo = mid + 1;
+    }
+    pred[i] = lo > 0 ? tails[lo - 1] : -1;
+    if (lo == (int32_t)tails.size()) tails.push_back(i); else tails[lo] = i;
+  }
+  std::vector<int32_t> out;
+  for (int32_t i = tails.empty() ? -1 : tails.back(); i >= 0; i = pred[i]) out.push_back(i);
+  std::reverse(out.begin(), out.end());
+  return out;
+}
 
 }  // namespace
 
@@ -181,94 +314,92 @@ int bs_builder_add(bs_builder *b, const int32_t *tokens, int32_t n_tokens, int32
 int bs_builder_finalize(bs_builder *b) {
   if (!b) return BS_EINVAL;
   if (b->finalized) return BS_OK;
-  const int32_t nr = (int32_t)b->reqs.size();
-  Grower gr(b->reqs);
-  for (int32_t r = 0; r < nr; ++r) gr.insert(r);
-  // flatten: requests that end at an internal node become leaves with an empty segment
-  std::vector<Tmp> t(gr.g.size());
-  for (size_t i = 0; i < gr.g.size(); ++i) {
-    t[i].parent = gr.g[i].parent; t[i].start = gr.g[i].start; t[i].end = gr.g[i].end; t[i].req = gr.g[i].req;
-    for (auto &kv : gr.g[i].kids) t[i].kids.push_back(kv.second);
-  }
-  for (size_t i = 0; i < gr.g.size(); ++i)
-    for (int32_t r : gr.g[i].ends_here) {
-      Tmp leaf;
-      leaf.parent = (int32_t)i; leaf.start = leaf.end = gr.g[i].end; leaf.req = r;
-      t.push_back(leaf);
-      t[i].kids.push_back((int32_t)t.size() - 1);
-    }
-  // bottom-up annotation in reverse creation order is not enough (splits re-parent), so walk explicitly
-  std::vector<int32_t> order;  // pre-order
-  order.reserve(t.size());
-  {
-    std::vector<int32_t> st{0};
-    while (!st.empty()) {
-      const int32_t n = st.back(); st.pop_back();
-      order.push_back(n);
-      for (int32_t c : t[n].kids) st.push_back(c);
-    }
-  }
-  for (size_t k = order.size(); k-- > 0;) {
-    Tmp &n = t[order[k]];
-    int64_t below;
-    if (n.req >= 0) {
-      const Req &r = b->reqs[n.req];
-      const int64_t p = (int64_t)r.tok.size(), d = r.d_est;
-      n.n_req = 1; n.sum_p = p; n.sum_d = d; n.min_req = n.req;
-      n.B = 2 * p * d + d * d;
-      below = (n.end - n.start) + d;
-    } else {
-      below = n.end - n.start;
-      n.min_req = std::numeric_limits<int32_t>::max();
-      for (int32_t c : n.kids) {
-        const Tmp &ch = t[c];
-        n.n_req += ch.n_req; n.sum_p += ch.sum_p; n.sum_d += ch.sum_d; n.B += ch.B;
-        n.min_req = std::min(n.min_req, ch.min_req);
-        below += ch.A - ch.start;
-      }
-    }
-    n.A = n.start + below;
-  }
-  // Algorithm 1: order every node's children by density, compute-intensive first
-  for (Tmp &n : t)
-    std::sort(n.kids.begin(), n.kids.end(), [&](int32_t x, int32_t y) {
-      const int c = cmp_density(t[x].A, t[x].B, t[y].A, t[y].B);
-      if (c) return c > 0;
-      return t[x].min_req < t[y].min_req;
-    });
-  // DFS pre-order numbering of the sorted tree
-  b->nodes.clear();
-  b->leaf_order.clear();
-  b->leaf_node.assign(nr, -1);
-  std::vector<int32_t> new_id(t.size(), -1);
-  struct Frame { int32_t n; size_t next; };
-  std::vector<Frame> st;
-  auto open = [&](int32_t n, int32_t parent_new) {
-    Node out;
-    out.parent = parent_new; out.start = t[n].start; out.end = t[n].end; out.req = t[n].req;
-    out.first_leaf = (int32_t)b->leaf_order.size(); out.leaf_count = 0;
-    out.A = t[n].A; out.B = t[n].B; out.n_req = t[n].n_req; out.sum_p = t[n].sum_p; out.sum_d = t[n].sum_d;
-    out.min_req = t[n].min_req;
-    new_id[n] = (int32_t)b->nodes.size();
-    b->nodes.push_back(out);
-    if (t[n].req >= 0) { b->leaf_node[t[n].req] = new_id[n]; b->leaf_order.push_back(t[n].req); }
-    st.push_back({n, 0});
-  };
-  open(0, -1);
-  while (!st.empty()) {
-    Frame &f = st.back();
-    if (f.next < t[f.n].kids.size()) {
-      const int32_t c = t[f.n].kids[f.next++];
-      const int32_t me = new_id[f.n];
-      open(c, me);
-      b->nodes[me].kids.push_back(new_id[c]);
-    } else {
-      Node &nd = b->nodes[new_id[f.n]];
-      nd.leaf_count = (int32_t)b->leaf_order.size() - nd.first_leaf;
-      st.pop_back();
-    }
-  }
+  rebuild(b);
   b->finalized = true;
+  return BS_OK;
+}
+
+int bs_builder_split(bs_builder *b, int64_t t, int64_t budget_tokens, bs_split_info *info) {
+  if (!b) return BS_EINVAL;
+  if (!b->finalized) return fail(b, BS_EINVAL, "bs_builder_split before bs_builder_finalize");
+  if (t < 0) return fail(b, BS_EINVAL, "threshold t must be >= 0");
+  int64_t spent = 0;
+  int32_t rounds = 0, n_split = 0;
+  std::vector<int64_t> A, B;
+  for (;;) {
+    const int32_t n = (int32_t)b->leaf_order.size();
+    A.resize(n); B.resize(n);
+    for (int32_t i = 0; i < n; ++i) {
+      const Node &lf = b->nodes[b->leaf_node[b->leaf_order[i]]];
+      A[i] = lf.A; B[i] = lf.B;
+    }
+    const std::vector<int32_t> keep = longest_non_increasing(A, B);
+    if ((int32_t)keep.size() == n) break;  // C1
+    std::vector<char> kept(n, 0), movable(n, 0), cand(n, 0);
+    for (int32_t i : keep) kept[i] = 1;
+    bool any = false;
+    // first kind: a leaf that drags a subtree X to the wrong side of the sibling Q next to it
+    // while belonging, itself, on the far side of all of Q
+    for (int32_t i = 0; i < n; ++i) {
+      const Node &lf = b->nodes[b->leaf_node[b->leaf_order[i]]];
+      movable[i] = lf.parent != 0;
+      if (!movable[i]) continue;
+      const int64_t gone_a = lf.A - lf.start, gone_b = lf.B;  // what every ancestor loses with the leaf
+      for (int32_t x = lf.parent; x != 0 && !cand[i]; x = b->nodes[x].parent) {
+        const Node &X = b->nodes[x];
+        const std::vector<int32_t> &sib = b->nodes[X.parent].kids;
+        const size_t j = (size_t)(std::find(sib.begin(), sib.end(), x) - sib.begin());
+        const int64_t ra = X.A - gone_a, rb = X.B - gone_b;
+        if (j > 0) {
+          const Node &Q = b->nodes[sib[j - 1]];
+          if (cmp_density(ra, rb, Q.A, Q.B) > 0 && cmp_density(lf.A, lf.B, Q.lo_a, Q.lo_b) < 0) cand[i] = 1;
+        }
+        if (j + 1 < sib.size()) {
+          const Node &Q = b->nodes[sib[j + 1]];
+          if (cmp_density(ra, rb, Q.A, Q.B) < 0 && cmp_density(lf.A, lf.B, Q.hi_a, Q.hi_b) > 0) cand[i] = 1;
+        }
+      }
+      any = any || cand[i];
+    }
+    if (!any) {
+      // second kind: the leaves outside the longest non-increasing subsequence
+      for (int32_t i = 0; i < n; ++i) cand[i] = !kept[i] && movable[i];
+      for (int32_t i = 0; i + 1 < n; ++i)
+        if (cmp_density(A[i], B[i], A[i + 1], B[i + 1]) < 0 && !cand[i] && !cand[i + 1]) {
+          // the outlier of this violation sits under the root already: move its neighbour
+          if (!kept[i] && movable[i + 1]) cand[i + 1] = 1;
+          else if (!kept[i + 1] && movable[i]) cand[i] = 1;
+        }
+    }
+    std::vector<std::pair<int64_t, int32_t>> todo;  // (cost = shared prefix length, request)
+    for (int32_t i = 0; i < n; ++i)
+      if (cand[i]) {
+        const int32_t r = b->leaf_order[i];
+        const int64_t cost = b->nodes[b->leaf_node[r]].start;
+        if (cost <= t) todo.emplace_back(cost, r);
+      }
+    std::sort(todo.begin(), todo.end());
+    int32_t took = 0;
+    for (const auto &c : todo) {
+      if (budget_tokens >= 0 && spent + c.first > budget_tokens) break;
+      b->detached[c.second] = 1;
+      spent += c.first;
+      ++took;
+    }
+    if (took == 0) break;  // C2
+    n_split += took;
+    ++rounds;
+    rebuild(b);
+  }
+  if (info) {
+    const int32_t n = (int32_t)b->leaf_order.size();
+    int32_t mono = 1;
+    for (int32_t i = 0; i + 1 < n && mono; ++i) {
+      const Node &x = b->nodes[b->leaf_node[b->leaf_order[i]]], &y = b->nodes[b->leaf_node[b->leaf_order[i + 1]]];
+      if (cmp_density(x.A, x.B, y.A, y.B) < 0) mono = 0;
+    }
+    info->n_split = n_split; info->rounds = rounds; info->monotone = mono; info->recompute_tokens = spent;
+  }
   return BS_OK;
 }
 

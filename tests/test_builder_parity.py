@@ -130,6 +130,31 @@ def test_blended_config_shape_end_to_end():
         assert d["node_page_start"][n + 1] - d["node_page_start"][n] == 64   # 1024 shared tokens = 64 pages
 
 
+# ---------------------------------------------------------------------------
+# conditional node splitting (Section 5.2, Algorithm 2; Section 5.4, stopping conditions)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("t,budget", [(0, -1), (40, -1), (10**9, 150), (10**9, -1)])
+def test_split_matches_oracle(seed, t, budget):
+    reqs = grouped_pool(seed, two_level=bool(seed % 2))
+    o, b = both(reqs, mem_bytes=int(2e9), hw=MI355_8B)
+    io = o.split(t, budget)
+    ib = b.split(t, budget)
+    assert io == ib
+    assert_same_tree(o, b)
+    assert_same_batch(o, b, prefill_budget=1024)
+    # a second call continues from the relocated tree, identically on both sides
+    assert o.split(10**9) == b.split(10**9)
+    assert_same_tree(o, b)
+
+
+def test_split_before_finalize_is_an_error():
+    b = binding.Builder(1, 1, 1.0, 1.0, 1, 16)
+    b.add([1, 2], 1, 0)
+    with pytest.raises(binding.BlendStepError):
+        b.split(10)
+
+
 def test_errors():
     b = binding.Builder(1, 1, 1.0, 1.0, 1, 16)
     with pytest.raises(binding.BlendStepError):

@@ -311,3 +311,103 @@ def test_scanners_take_from_both_ends():
     assert info["n_prefill"] >= 1 and info["n_decode"] >= 1
     assert info["rho_l"] > info["rho_rt"] > info["rho_r"]
     assert 0 < info["m_l"] < 200_000_000
+
+
+# ---------------------------------------------------------------------------
+# conditional node splitting (Section 5.2, Algorithm 2; Section 5.4, stopping conditions)
+# ---------------------------------------------------------------------------
+def leaf_density(o):
+    return [None if b == 0 else Fraction(a, b) for a, b in o.leaf_keys()]
+
+
+def non_increasing(fr):
+    big = Fraction(10 ** 30)
+    v = [big if f is None else f for f in fr]
+    return all(v[i] >= v[i + 1] for i in range(len(v) - 1))
+
+
+def brute_force_longest_non_increasing(vals):
+    best = 0
+    n = len(vals)
+    for mask in range(1 << n):
+        pick = [vals[i] for i in range(n) if mask >> i & 1]
+        if all(pick[i] >= pick[i + 1] for i in range(len(pick) - 1)):
+            best = max(best, len(pick))
+    return best
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_longest_non_increasing_against_brute_force(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(1, 11))
+    keys = [(int(rng.integers(1, 6)), int(rng.integers(0, 5))) for _ in range(n)]   # B = 0 is +infinity
+    got = B.longest_non_increasing(keys)
+    vals = [Fraction(10 ** 9) if b == 0 else Fraction(a, b) for a, b in keys]
+    assert got == sorted(got) and len(set(got)) == len(got)
+    assert all(vals[got[i]] >= vals[got[i + 1]] for i in range(len(got) - 1))
+    assert len(got) == brute_force_longest_non_increasing(vals)
+
+
+def distinct_tokens(o):
+    return o.nodes[0].A - sum(int(r.d_est) for r in o.reqs)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_split_bounds_and_invariants(seed):
+    reqs = mixed_pool(seed, n_groups=4, per_group=6, n_fresh=5)
+    base = B.BuilderOracle(cm(), reqs)
+    # t = 0: nothing shares zero tokens and sits below an internal node, so nothing moves
+    o0 = B.BuilderOracle(cm(), reqs)
+    assert o0.split(0) == dict(n_split=0, rounds=0, recompute_tokens=0, monotone=non_increasing(leaf_density(base)))
+    assert o0.leaf_order == base.leaf_order
+    # unlimited threshold: ends with a non-increasing leaf order (C1), every leaf moved at most once
+    o = B.BuilderOracle(cm(), reqs)
+    info = o.split(10 ** 9)
+    assert info["monotone"] and non_increasing(leaf_density(o))
+    assert info["n_split"] == len(o.detached) <= len(reqs)
+    assert 0 < info["rounds"] <= info["n_split"] or info["n_split"] == 0
+    for r in o.detached:                      # relocated leaves hang under the root with their whole prompt
+        nd = [n for n in o.nodes if n.req == r][0]
+        assert nd.parent == 0 and nd.start == 0 and nd.end == len(reqs[r].tokens)
+    # sharing lost is at most the recomputed tokens, and nothing else changed: same requests, same B
+    assert 0 <= distinct_tokens(o) - distinct_tokens(base) <= info["recompute_tokens"]
+    assert sorted(o.leaf_order) == list(range(len(reqs))) and o.nodes[0].B == base.nodes[0].B
+    # a finite threshold and a budget are both respected; relocated leaves are a subset of movable ones
+    for t, budget in ((30, -1), (10 ** 9, 120), (45, 60)):
+        ot = B.BuilderOracle(cm(), reqs)
+        it = ot.split(t, budget)
+        assert it["recompute_tokens"] <= (budget if budget >= 0 else 10 ** 18)
+        for r in ot.detached:
+            leaf = [n for n in base.nodes if n.req == r][0]
+            assert leaf.parent != 0 and leaf.start <= t or r in o.detached
+        if it["n_split"] == 0:
+            assert ot.leaf_order == base.leaf_order
+
+
+def test_split_separates_the_low_density_request_of_the_overview_figure():
+    # Figure 3 (design overview), step 3, and Section 5.2: a request of low compute density that
+    # shares its prefix with compute-intensive requests is separated from them and placed at the
+    # memory-intensive end, its prefix recomputed.  Requests 0 and 1 (short outputs) share a
+    # prefix with request 2 (long output); two memory-intensive requests without sharing follow.
+    # rho of a node is sum A / sum B, so request 2 drags its whole group behind them: before the
+    # split the compute-intensive requests 0 and 1 sit in the right half of the order.
+    P = list(range(100, 140))
+    Q = list(range(200, 220))
+    reqs = [B.Request(P + Q + [1, 2, 3], d_est=4),        # compute-intensive
+            B.Request(P + [7, 8, 9, 10], d_est=4),        # compute-intensive
+            B.Request(P + Q + [4, 5, 6], d_est=10000),    # the outlier
+            B.Request([50 + i for i in range(30)], d_est=400),
+            B.Request([90 - i for i in range(30)], d_est=300)]
+    o = B.BuilderOracle(cm(), reqs)
+    assert not non_increasing(leaf_density(o))
+    assert set(o.leaf_order[:2]) == {3, 4} and o.leaf_order[-1] == 2
+    info = o.split(t=len(P) + len(Q))
+    assert info == dict(n_split=1, rounds=1, recompute_tokens=len(P) + len(Q), monotone=True)
+    assert o.detached == {2} and o.leaf_order[-1] == 2 and set(o.leaf_order[:2]) == {0, 1}
+    # requests 0 and 1 still share their prefix: only the relocated request lost it
+    assert distinct_tokens(o) - distinct_tokens(B.BuilderOracle(cm(), reqs)) == len(P) + len(Q)
+    # with a threshold below its shared prefix the request cannot move (C2): the cheaper of the
+    # compute-intensive requests goes instead, the other one stays out of order
+    o2 = B.BuilderOracle(cm(), reqs)
+    i2 = o2.split(t=len(P) + len(Q) - 1)
+    assert 2 not in o2.detached and not i2["monotone"]
