@@ -46,6 +46,8 @@ struct bs_ctx {
   float *x1 = nullptr, *rstd1 = nullptr, *rstd2 = nullptr, *ss2 = nullptr;
   long cap_slots = 0;
   float *part_acc = nullptr, *part_m = nullptr, *part_l = nullptr;
+  float *splitk_ws = nullptr;  // fp32 partial products of the split-K GEMMs (few-row steps)
+  size_t cap_splitk = 0;
   // descriptor blob: pinned host ring and one device copy
   long cap_blob = 0;
   int32_t *d_blob = nullptr;
@@ -131,6 +133,15 @@ int ensure_slots(bs_ctx *c, long slots) {
   if ((rc = dev_alloc(c, &c->part_m, (size_t)cap * hq))) return rc;
   if ((rc = dev_alloc(c, &c->part_l, (size_t)cap * hq))) return rc;
   c->cap_slots = cap;
+  return BS_OK;
+}
+
+int ensure_splitk(bs_ctx *c, size_t floats) {
+  if (floats <= c->cap_splitk) return BS_OK;
+  c->cap_splitk = 0;
+  int rc = dev_alloc(c, &c->splitk_ws, floats);
+  if (rc) return rc;
+  c->cap_splitk = floats;
   return BS_OK;
 }
 
@@ -476,6 +487,12 @@ int run_o_gate_up(bs_ctx *c, const bs_weights *w, const uint16_t *x, int r0, int
   o.C32 = c->x1 + (size_t)r0 * d; o.ldc = d; o.resid = x + (size_t)r0 * d; o.ldr = d;
   o.gain = (const uint16_t *)w->g_ffn; o.C_gain = c->xg2 + (size_t)r0 * d;
   o.ss_out = c->ss2 + r0; o.ss_stride = c->cap_rows;
+  o.k_splits = gemm_splitk_choice(rows, d, hd, EPI_RESID_NORM, n_cu);
+  if (o.k_splits > 1) {
+    int rc = ensure_splitk(c, (size_t)o.k_splits * rows * d);
+    if (rc) return rc;
+    o.splitk_ws = c->splitk_ws;
+  }
   const int parts = gemm_ss_parts(o, EPI_RESID_NORM, g.head_dim);
   SPAN(c, BS_K_GEMM_O, st, {
     HIP_TRY(c, launch_gemm(o, EPI_RESID_NORM, g.head_dim, st));
@@ -502,6 +519,12 @@ int run_down(bs_ctx *c, const bs_weights *w, uint16_t *y, int r0, int r1, hipStr
   dn.A = c->act + (size_t)r0 * f; dn.lda = f; dn.B = (const uint16_t *)w->w_down; dn.ldb = f;
   dn.M = rows; dn.N = d; dn.K = f;
   dn.C = y + (size_t)r0 * d; dn.ldc = d; dn.resid32 = c->x1 + (size_t)r0 * d; dn.ldr = d;
+  dn.k_splits = gemm_splitk_choice(rows, d, f, EPI_RESID, n_cu);
+  if (dn.k_splits > 1) {
+    int rc = ensure_splitk(c, (size_t)dn.k_splits * rows * d);
+    if (rc) return rc;
+    dn.splitk_ws = c->splitk_ws;
+  }
   SPAN(c, BS_K_GEMM_DOWN, st, HIP_TRY(c, launch_gemm(dn, EPI_RESID, g.head_dim, st)));
   return BS_OK;
 }
@@ -592,7 +615,7 @@ void bs_destroy(bs_ctx *c) {
   (void)hipDeviceSynchronize();
   for (void *p : {(void *)c->rope_cos, (void *)c->rope_sin, (void *)c->xg, (void *)c->qbuf, (void *)c->attn, (void *)c->x1,
                   (void *)c->xg2, (void *)c->act, (void *)c->rstd1, (void *)c->rstd2, (void *)c->ss2, (void *)c->part_acc, (void *)c->part_m,
-                  (void *)c->part_l, (void *)c->d_blob})
+                  (void *)c->part_l, (void *)c->d_blob, (void *)c->splitk_ws})
     if (p) (void)hipFree(p);
   for (int i = 0; i < RING; ++i) {
     if (c->h_blob[i]) (void)hipHostFree(c->h_blob[i]);
@@ -683,6 +706,11 @@ int bs_blend_step(bs_ctx *c, const bs_weights *w, const bs_batch *b, const void 
   q.rope_cos = c->rope_cos; q.rope_sin = c->rope_sin;
   q.row_pos = c->d_blob + p.off_row_pos; q.row_page = c->d_blob + p.off_row_page; q.row_slot = c->d_blob + p.off_row_slot;
   q.q_out = c->qbuf; q.kv_pool = pool;
+  q.k_splits = gemm_splitk_choice(q.M, q.N, q.K, EPI_QKV, 0);
+  if (q.k_splits > 1) {
+    if ((rc = ensure_splitk(c, (size_t)q.k_splits * q.M * q.N))) return rc;
+    q.splitk_ws = c->splitk_ws;
+  }
   SPAN(c, BS_K_GEMM_QKV, st, HIP_TRY(c, launch_gemm(q, EPI_QKV, g.head_dim, st)));
   (void)hd;
 

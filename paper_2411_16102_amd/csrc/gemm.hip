@@ -21,6 +21,7 @@
 // must change every two rows for the ds_read_b128 of a fragment (32 rows, one chunk
 // column) to be conflict-free.  Waits on the LDS-DMA loads are placed by hand
 // (s_waitcnt vmcnt + s_barrier); the compiler does not track them.
+#include <algorithm>
 #include "gemm.hpp"
 #include "common.hpp"
 
@@ -90,7 +91,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + OUT_BN - 1) / OUT_BN;
-  const TileCoord tc = map_tile(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n);
+  // split-K: consecutive workgroups are the k-ranges of one tile
+  const int split = (EPI == EPI_PARTIAL) ? (int)blockIdx.x % a.k_splits : 0;
+  const int tile_id = (EPI == EPI_PARTIAL) ? (int)blockIdx.x / a.k_splits : (int)blockIdx.x;
+  const TileCoord tc = map_tile(tile_id, tiles_m * tiles_n, tiles_m, tiles_n);
   const int m0 = tc.tm * BM, n0 = tc.tn * OUT_BN;
 
   const int t = threadIdx.x, lane = t & 63;
@@ -172,7 +176,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   const int xfrag = (wm0 + lr) * ROWB;
   const int wfrag = (wn0 + lr) * ROWB;
 
-  const int nk = (a.K + BK - 1) / BK;
+  const int nk_all = (a.K + BK - 1) / BK;
+  // this workgroup's k-tiles [kt0, kt1): all of them, or one of k_splits nearly equal ranges
+  const int kt0 = (EPI == EPI_PARTIAL) ? (int)((long)nk_all * split / a.k_splits) : 0;
+  const int kt1 = (EPI == EPI_PARTIAL) ? (int)((long)nk_all * (split + 1) / a.k_splits) : nk_all;
   constexpr int NF = MI + NI;   // fragment reads per 16-wide k-step
   constexpr int NMF = MI * NI;  // MFMAs per 16-wide k-step
   // read number o of k-step ks (16 wide, four per tile) of the panels in ring slots sa, sb
@@ -216,15 +223,15 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   constexpr int PER_P = (N_P + NMF - 1) / NMF > 2 ? (N_P + NMF - 1) / NMF : 2;
   bf16x8_t xa[MI], wa[NI], xb[MI], wb[NI];
 #pragma unroll
-  for (int i = 0; i < LA; ++i) dma_a(0, 0, i, Yes{});
+  for (int i = 0; i < LA; ++i) dma_a(kt0, 0, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LB; ++i) dma_b(0, 1, i, Yes{});
+  for (int i = 0; i < LB; ++i) dma_b(kt0, 1, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LA; ++i) dma_a(1, 2, i, Yes{});
+  for (int i = 0; i < LA; ++i) dma_a(kt0 + 1, 2, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LB; ++i) dma_b(1, 3, i, Yes{});
+  for (int i = 0; i < LB; ++i) dma_b(kt0 + 1, 3, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LA; ++i) dma_a(2, 4, i, Yes{});
+  for (int i = 0; i < LA; ++i) dma_a(kt0 + 2, 4, i, Yes{});
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LA + LB, true));  // tile 0 has landed
   __builtin_amdgcn_s_barrier();
   int sa = 0, sb = 1;  // slots of the tile being multiplied
@@ -255,10 +262,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
     sa = na;
     sb = nb;
   };
-  int kt = 0;
+  int kt = kt0;
   const int n_plain = a.K / BK - 3;  // tiles kt for which W(kt+2) and X(kt+3) lie wholly inside K
-  for (; kt < n_plain; ++kt) tile(kt, No{});
-  for (; kt < nk; ++kt) tile(kt, Yes{});
+  for (; kt < n_plain && kt < kt1; ++kt) tile(kt, No{});
+  for (; kt < kt1; ++kt) tile(kt, Yes{});
   // drain the look-ahead loads (zeros or clamped rows) before the LDS is released
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
 
@@ -271,6 +278,24 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
     for (int mi = 0; mi < MI; ++mi) {
       const int m = m0 + wm0 + mi * 32 + lr;
       rstd[mi] = (m < a.M) ? a.rstd[m] : 0.f;
+    }
+  }
+
+  if (EPI == EPI_PARTIAL) {
+    float *ws = a.splitk_ws + (size_t)split * a.M * a.N;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int m = m0 + wm0 + mi * 32 + lr;
+      if (m >= a.M) continue;
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int n = n0 + wn0 + ni * 32 + 8 * q + 4 * lg;
+          if (n >= a.N) continue;
+          *reinterpret_cast<f32x4_t *>(ws + (size_t)m * a.N + n) =
+              f32x4_t{acc[ni][mi][4 * q], acc[ni][mi][4 * q + 1], acc[ni][mi][4 * q + 2], acc[ni][mi][4 * q + 3]};
+        }
     }
   }
 
@@ -429,6 +454,101 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   }
 }
 
+constexpr int MAX_SPLITS = 8;
+
+// four consecutive columns of one row, summed over the k-ranges in a fixed order; the loads are
+// independent of one another and go out together
+__device__ __forceinline__ f32x4_t splitk_sum(const float *p, size_t plane, int k_splits) {
+  f32x4_t part[MAX_SPLITS];
+#pragma unroll
+  for (int s = 0; s < MAX_SPLITS; ++s)
+    part[s] = s < k_splits ? *reinterpret_cast<const f32x4_t *>(p + s * plane) : f32x4_t{0.f, 0.f, 0.f, 0.f};
+  f32x4_t v = part[0];
+#pragma unroll
+  for (int s = 1; s < MAX_SPLITS; ++s) v += part[s];
+  return v;
+}
+
+// Second half of a split-K product: adds the k_splits partial rows and applies the epilogue.
+// RESID: y = resid + sum, one thread per four columns.
+__global__ __launch_bounds__(256) void splitk_reduce_resid_kernel(const GemmArgs a) {
+  const int m = blockIdx.x, n = (blockIdx.y * 256 + threadIdx.x) * 4;
+  if (n >= a.N) return;
+  f32x4_t v = splitk_sum(a.splitk_ws + (size_t)m * a.N + n, (size_t)a.M * a.N, a.k_splits);
+  if (a.resid32) {
+    v += *reinterpret_cast<const f32x4_t *>(a.resid32 + (size_t)m * a.ldr + n);
+  } else {
+    const u32x2_t rr = *reinterpret_cast<const u32x2_t *>(a.resid + (size_t)m * a.ldr + n);
+    v[0] += __uint_as_float(rr.x << 16);
+    v[1] += __uint_as_float(rr.x & 0xFFFF0000u);
+    v[2] += __uint_as_float(rr.y << 16);
+    v[3] += __uint_as_float(rr.y & 0xFFFF0000u);
+  }
+  store_bf16x4(a.C + (size_t)m * a.ldc + n, v[0], v[1], v[2], v[3]);
+}
+
+// RESID_NORM: x1 = resid + sum in fp32, bf16(x1 * gain), and the row's sum of squares, complete,
+// in ss_out slot 0; one workgroup per row.
+__global__ __launch_bounds__(256) void splitk_reduce_resid_norm_kernel(const GemmArgs a) {
+  const int m = blockIdx.x;
+  float ss = 0.f;
+  for (int n = threadIdx.x * 4; n < a.N; n += 256 * 4) {
+    f32x4_t v = splitk_sum(a.splitk_ws + (size_t)m * a.N + n, (size_t)a.M * a.N, a.k_splits);
+    const u32x2_t rr = *reinterpret_cast<const u32x2_t *>(a.resid + (size_t)m * a.ldr + n);
+    v[0] += __uint_as_float(rr.x << 16);
+    v[1] += __uint_as_float(rr.x & 0xFFFF0000u);
+    v[2] += __uint_as_float(rr.y << 16);
+    v[3] += __uint_as_float(rr.y & 0xFFFF0000u);
+    const u32x2_t gg = *reinterpret_cast<const u32x2_t *>(a.gain + n);
+    const float g0 = __uint_as_float(gg.x << 16), g1 = __uint_as_float(gg.x & 0xFFFF0000u);
+    const float g2 = __uint_as_float(gg.y << 16), g3 = __uint_as_float(gg.y & 0xFFFF0000u);
+    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+    *reinterpret_cast<f32x4_t *>(a.C32 + (size_t)m * a.ldc + n) = v;
+    store_bf16x4(a.C_gain + (size_t)m * a.ldc + n, v[0] * g0, v[1] * g1, v[2] * g2, v[3] * g3);
+  }
+  __shared__ float part[4];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) a.ss_out[m] = (part[0] + part[1]) + (part[2] + part[3]);
+}
+
+// QKV: scale by the row's RMSNorm factor, rotate the q and k heads (pairs i, i + dh/2), store q
+// to its buffer, k and v into the row's page slot (v transposed).  One thread per four
+// consecutive pairs (q and k heads) or four consecutive v elements.
+__global__ __launch_bounds__(256) void splitk_reduce_qkv_kernel(const GemmArgs a, int dh) {
+  const int m = blockIdx.x;
+  const int item = blockIdx.y * 256 + threadIdx.x;
+  const size_t plane = (size_t)a.M * a.N;
+  const float *ws = a.splitk_ws + (size_t)m * a.N;
+  const float rs = a.rstd[m];
+  const int half = dh / 2, q4 = half / 4;
+  const size_t page = a.row_page[m];
+  const int slot = a.row_slot[m];
+  const size_t tile_elems = (size_t)16 * dh;
+  const int n_rot = (a.n_q_heads + a.n_kv_heads) * q4;
+  if (item < n_rot) {
+    const int head = item / q4, i = (item % q4) * 4, pos = a.row_pos[m];
+    const f32x4_t l = splitk_sum(ws + head * dh + i, plane, a.k_splits) * rs;
+    const f32x4_t h = splitk_sum(ws + head * dh + half + i, plane, a.k_splits) * rs;
+    const f32x4_t c = *reinterpret_cast<const f32x4_t *>(a.rope_cos + (size_t)pos * half + i);
+    const f32x4_t sn = *reinterpret_cast<const f32x4_t *>(a.rope_sin + (size_t)pos * half + i);
+    uint16_t *dst = head < a.n_q_heads
+                        ? a.q_out + (size_t)m * (a.n_q_heads * dh) + head * dh
+                        : a.kv_pool + ((page * 2 + 0) * a.n_kv_heads + (head - a.n_q_heads)) * tile_elems + (size_t)slot * dh;
+    const f32x4_t lo = l * c - h * sn, hi = h * c + l * sn;
+    store_bf16x4(dst + i, lo[0], lo[1], lo[2], lo[3]);
+    store_bf16x4(dst + half + i, hi[0], hi[1], hi[2], hi[3]);
+  } else if (item < n_rot + a.n_kv_heads * (dh / 4)) {
+    const int w = (item - n_rot) * 4, head = w / dh, e = w % dh;
+    const f32x4_t v = splitk_sum(ws + (a.n_q_heads + a.n_kv_heads) * dh + w, plane, a.k_splits) * rs;
+    uint16_t *dst = a.kv_pool + ((page * 2 + 1) * a.n_kv_heads + head) * tile_elems + slot;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dst[(e + j) * 16] = f32_to_bf16(v[j]);
+  }
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH>
 hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
   constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
@@ -441,7 +561,7 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
     if (e != hipSuccess) return e;
     configured = true;
   }
-  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + OUT_BN - 1) / OUT_BN);
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + OUT_BN - 1) / OUT_BN) * (EPI == EPI_PARTIAL ? a.k_splits : 1);
   if (tiles <= 0) return hipSuccess;
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(WAVES_M * WAVES_N * 64), LDS, stream, a);
   return hipGetLastError();
@@ -489,7 +609,19 @@ hipError_t launch_variant(const GemmArgs &a, int v, hipStream_t stream) {
 
 void gemm_force_variant(int v) { g_forced_variant = v; }
 
+int gemm_splitk_choice(int M, int N, int K, int epilogue, int n_cu) {
+  if (epilogue != EPI_RESID && epilogue != EPI_RESID_NORM && epilogue != EPI_QKV) return 1;
+  if (n_cu <= 0) n_cu = N_CU;
+  if (choose_variant(M, N, epilogue, 64, n_cu) != V_SMALL) return 1;  // only where the smallest tile is already in use
+  const long tiles = n_tiles(M, N, 128, 128);
+  const long room = 2L * n_cu / tiles;          // two 128x128 workgroups fit one CU
+  const long by_k = ((K + BK - 1) / BK) / 8;    // at least eight k-tiles per range
+  const long s = std::min((long)MAX_SPLITS, std::min(room, by_k));
+  return s >= 2 ? (int)s : 1;
+}
+
 int gemm_ss_parts(const GemmArgs &a, int epilogue, int dh) {
+  if (a.k_splits > 1) return 1;  // the split-K reduction leaves whole row sums
   const int v = choose_variant(a.M, a.N, epilogue, dh, a.n_cu);
   // partial row sums: one per (column tile, wavefront column)
   if (v == V_QUAD) return ((a.N + 255) / 256) * 2;
@@ -497,6 +629,21 @@ int gemm_ss_parts(const GemmArgs &a, int epilogue, int dh) {
 }
 
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream) {
+  if (a.k_splits > 1) {
+    if ((epilogue != EPI_RESID && epilogue != EPI_RESID_NORM && epilogue != EPI_QKV) || !a.splitk_ws || a.N % 4)
+      return hipErrorInvalidValue;
+    hipError_t e = launch_one<128, 128, 2, 2, EPI_PARTIAL, 64>(a, stream);
+    if (e != hipSuccess) return e;
+    if (epilogue == EPI_QKV) {
+      const int items = ((a.n_q_heads + a.n_kv_heads) * (dh / 2) + a.n_kv_heads * dh) / 4;
+      hipLaunchKernelGGL(splitk_reduce_qkv_kernel, dim3(a.M, (items + 255) / 256), dim3(256), 0, stream, a, dh);
+    } else if (epilogue == EPI_RESID) {
+      hipLaunchKernelGGL(splitk_reduce_resid_kernel, dim3(a.M, (a.N / 4 + 255) / 256), dim3(256), 0, stream, a);
+    } else {
+      hipLaunchKernelGGL(splitk_reduce_resid_norm_kernel, dim3(a.M), dim3(256), 0, stream, a);
+    }
+    return hipGetLastError();
+  }
   const int b_rows = (epilogue == EPI_SWIGLU) ? 2 * a.N : a.N;
   // the kernels address operand rows with 32-bit byte offsets from the matrix base
   if ((size_t)a.M * a.lda * 2 >= ((size_t)1 << 32) || (size_t)b_rows * a.ldb * 2 >= ((size_t)1 << 32))

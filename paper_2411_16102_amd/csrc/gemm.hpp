@@ -13,7 +13,8 @@ enum GemmEpilogue {
   EPI_QKV = 1,        // row scale (RMSNorm), RoPE on q and k heads, q to its buffer, k and v into KV pages
   EPI_RESID_NORM = 2, // x1 = resid + A B^T in fp32; also bf16(x1 * gain) and partial row sums of x1^2 for the next norm
   EPI_SWIGLU = 3,     // out = silu(s * gate) * (s * up), s = per-row RMSNorm scale
-  EPI_RESID = 4       // y = resid + A B^T (resid in bf16, or in fp32 when resid32 is set)
+  EPI_RESID = 4,      // y = resid + A B^T (resid in bf16, or in fp32 when resid32 is set)
+  EPI_PARTIAL = 5     // internal: fp32 partial products of one k-range into the split-K workspace
 };
 
 struct GemmArgs {
@@ -34,6 +35,12 @@ struct GemmArgs {
   float *C32;            // [M, ldc] x1 in fp32
   uint16_t *C_gain;      // [M, ldc] bf16(x1 * gain)
   float *ss_out;         // [tiles_n * waves_n][ss_stride] partial row sums of x1^2
+  // Split-K (QKV, RESID and RESID_NORM with few tiles): k_splits > 1 cuts K into that many ranges,
+  // each (tile, range) is one workgroup that leaves fp32 partial products in splitk_ws
+  // [k_splits][M][N]; a second kernel adds them up in a fixed order and applies the epilogue.
+  // The caller takes k_splits from gemm_splitk_choice and provides the workspace.
+  int k_splits;
+  float *splitk_ws;
   // SWIGLU: B holds F gate rows then F up rows; N = F
   // QKV extras
   int n_q_heads, n_kv_heads;
@@ -46,7 +53,11 @@ struct GemmArgs {
 // Picks a tile shape for the problem and launches on `stream`.  dh is the head
 // dimension (used by EPI_QKV only).  Returns hipSuccess or the launch error.
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream);
+// partial-sum slots a RESID_NORM launch over N columns writes
 int gemm_ss_parts(const GemmArgs &a, int epilogue, int dh);
-void gemm_force_variant(int v);  // 0 = choose by shape, 1 = 256x256, 2 = 160x256, 3 = 128x128 tiles (tuning)  // partial-sum slots a RESID_NORM launch over N columns writes
+// Number of k-ranges worth using for this problem (1 = no split): only when the tiles would
+// leave most of the chip idle and every range keeps at least eight k-tiles.
+int gemm_splitk_choice(int M, int N, int K, int epilogue, int n_cu);
+void gemm_force_variant(int v);  // 0 = choose by shape, 1 = 256x256, 2 = 160x256, 3 = 128x128 tiles (tuning)
 
 }  // namespace bs
