@@ -90,12 +90,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
 
   extern __shared__ __align__(16) unsigned char smem[];
 
-  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + OUT_BN - 1) / OUT_BN;
+  const int n_lim = a.n_count ? a.n_begin + a.n_count : a.N;  // end of the output columns of this launch
+  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (n_lim - a.n_begin + OUT_BN - 1) / OUT_BN;
   // split-K: consecutive workgroups are the k-ranges of one tile
   const int split = (EPI == EPI_PARTIAL) ? (int)blockIdx.x % a.k_splits : 0;
   const int tile_id = (EPI == EPI_PARTIAL) ? (int)blockIdx.x / a.k_splits : (int)blockIdx.x;
   const TileCoord tc = map_tile(tile_id, tiles_m * tiles_n, tiles_m, tiles_n);
-  const int m0 = tc.tm * BM, n0 = tc.tn * OUT_BN;
+  const int m0 = tc.tm * BM, n0 = a.n_begin + tc.tn * OUT_BN;
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -309,7 +310,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int n = n0 + wn0 + ni * 32 + 8 * q + 4 * lg;
-          if (n >= a.N) continue;
+          if (n >= n_lim) continue;
           float v[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = acc[ni][mi][4 * q + e];
@@ -378,7 +379,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int n = n0 + (wn0 >> 1) + p * 32 + 8 * q + 4 * lg;
-          if (n >= a.N) continue;
+          if (n >= n_lim) continue;
           float v[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
@@ -561,7 +562,8 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
     if (e != hipSuccess) return e;
     configured = true;
   }
-  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + OUT_BN - 1) / OUT_BN) * (EPI == EPI_PARTIAL ? a.k_splits : 1);
+  const int n_cols = a.n_count ? a.n_count : a.N;
+  const int tiles = ((a.M + BM - 1) / BM) * ((n_cols + OUT_BN - 1) / OUT_BN) * (EPI == EPI_PARTIAL ? a.k_splits : 1);
   if (tiles <= 0) return hipSuccess;
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(WAVES_M * WAVES_N * 64), LDS, stream, a);
   return hipGetLastError();
@@ -648,7 +650,26 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stre
   // the kernels address operand rows with 32-bit byte offsets from the matrix base
   if ((size_t)a.M * a.lda * 2 >= ((size_t)1 << 32) || (size_t)b_rows * a.ldb * 2 >= ((size_t)1 << 32))
     return hipErrorInvalidValue;
-  const int v = choose_variant(a.M, b_rows, epilogue, dh, a.n_cu);
+  if (a.n_count && epilogue != EPI_SWIGLU && epilogue != EPI_PLAIN) return hipErrorInvalidValue;
+  const int n_cols = a.n_count ? a.n_count : a.N;
+  const int v = choose_variant(a.M, (epilogue == EPI_SWIGLU) ? 2 * n_cols : n_cols, epilogue, dh, a.n_cu);
+  if (epilogue == EPI_SWIGLU && v == V_BIG && g_forced_variant == V_AUTO) {
+    // Whole rounds of 256x256 tiles first; if the last round would leave more than a quarter
+    // of the chip idle, its columns go to a second launch with whatever shape suits them.
+    const int n_cu = a.n_cu > 0 ? a.n_cu : N_CU;
+    const long tm = (a.M + 255) / 256, tn = (n_cols + 127) / 128;  // a tile yields 128 output columns
+    const long tiles = tm * tn, full = tiles / n_cu, idle = (full + 1) * n_cu - tiles;
+    const long cols_big = full * n_cu / tm;
+    if (full >= 1 && tiles % n_cu != 0 && idle * 4 > n_cu && cols_big >= 1 && cols_big < tn) {
+      GemmArgs head = a, tail = a;
+      head.n_count = (int)cols_big * 128;
+      tail.n_begin = a.n_begin + head.n_count;
+      tail.n_count = n_cols - head.n_count;
+      hipError_t e = launch_one<256, 256, 2, 4, EPI_SWIGLU, 64>(head, stream);
+      if (e != hipSuccess) return e;
+      return launch_gemm(tail, epilogue, dh, stream);
+    }
+  }
   switch (epilogue) {
     case EPI_PLAIN: return launch_variant<EPI_PLAIN, 2, 4>(a, v, stream);
     case EPI_RESID: return launch_variant<EPI_RESID, 2, 4>(a, v, stream);

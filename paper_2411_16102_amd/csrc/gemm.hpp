@@ -22,6 +22,7 @@ struct GemmArgs {
   const uint16_t *B;  // [N, K] bf16 weights (out-features major), row stride ldb
   int M, N, K, lda, ldb;
   int n_cu;           // CUs the launch may use (0 = the whole chip); only steers the tile choice
+  int n_begin, n_count;  // output columns [n_begin, n_begin + n_count) only (n_count = 0: all N); SWIGLU and PLAIN
   uint16_t *C;        // output [M, ldc] bf16 (PLAIN, RESID*, SWIGLU)
   int ldc;
   const uint16_t *resid;  // [M, ldr] bf16
