@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--chunk-pages", type=int, default=0)
     ap.add_argument("--decode-cus", type=int, default=-1)
     ap.add_argument("--gemm-tiles", type=int, default=0, help="force one GEMM tile shape (0: cost model)")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="a step = this many layers back to back through bs_blend_layers (same weights and pool "
+                         "for every layer: timing only); value stays per layer")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (for scaling HBM traffic counters)")
     args = ap.parse_args()
@@ -138,7 +141,10 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(n):
-            layer.blend_step(dev, batch, flags=flags, y=y, desc=desc)
+            if args.layers > 1:
+                layer.blend_layers([dev] * args.layers, batch, flags=flags, y=y, desc=desc)
+            else:
+                layer.blend_step(dev, batch, flags=flags, y=y, desc=desc)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / max(1, n)
 
@@ -150,7 +156,7 @@ def main():
         t_overlap = run(max(3, args.warmup // 2), 1)
         flags = 1 if t_overlap < t_serial else 0
     run(args.warmup, flags)
-    sec = run(args.steps, flags)
+    sec = run(args.steps, flags) / args.layers
 
     # per-kernel durations: the same loop again with HIP events around every kernel class
     layer.profile(True)
@@ -163,7 +169,7 @@ def main():
     gu_flops = 2.0 * T * d * 2 * f
     gu_launches = max(1, prof["gemm_gate_up"][1])
     gu_ms = prof["gemm_gate_up"][0] / gu_launches            # average launch duration
-    gu_flops_per_launch = gu_flops * args.steps / gu_launches
+    gu_flops_per_launch = gu_flops * args.steps * args.layers / gu_launches
     t_flop = work["flops"] / PEAK_MFMA_BF16
     t_byte = work["bytes_once"] / PEAK_HBM
     bound = "mfma" if t_flop >= t_byte else "hbm"
@@ -188,7 +194,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "rows": T, "prefill_rows": int(batch.row_start[batch.n_prefill]),
                    "decode_seqs": batch.n_seq - batch.n_prefill, "prefix_nodes": batch.n_nodes,
-                   "d_model": d, "n_q_heads": shape.n_q_heads, "n_kv_heads": shape.n_kv_heads,
+                   "layers_per_call": args.layers, "d_model": d, "n_q_heads": shape.n_q_heads, "n_kv_heads": shape.n_kv_heads,
                    "head_dim": shape.head_dim, "d_ffn": f, "seed": args.seed,
                    "schedule": "overlap" if flags else "serial"},
         "step_roofline": {"flops": work["flops"], "bytes": work["bytes_once"], "bytes_if_expanded": work["bytes_expanded"],

@@ -141,6 +141,17 @@ int bs_blend_step(bs_ctx *ctx, const bs_weights *w, const bs_batch *batch,
                   const void *x, void *y, void *kv_pool, int64_t n_pages,
                   void *stream, uint32_t flags);
 
+/* The same step through n_layers layers back to back, as a serving engine runs it
+ * (Section 2.2: every decoding step passes through all layers; Appendix A.2: the backend
+ * runs whole batches layer after layer): layer l has weights w[l] and its own pool
+ * kv_pools[l] (all pools have n_pages pages and share the one descriptor, i.e. the same
+ * page table), reads the output of layer l-1 (x for l = 0) and the last layer writes y.
+ * The descriptor is validated, planned and uploaded once.  w and kv_pools are HOST arrays
+ * of n_layers entries, read during the call. */
+int bs_blend_layers(bs_ctx *ctx, int32_t n_layers, const bs_weights *w, const bs_batch *batch,
+                    const void *x, void *y, void *const *kv_pools, int64_t n_pages,
+                    void *stream, uint32_t flags);
+
 /* Host-only check of a descriptor against a pool of n_pages pages (the same
  * validation bs_blend_step performs); touches no GPU. */
 int bs_validate_batch(bs_ctx *ctx, const bs_batch *batch, int64_t n_pages);

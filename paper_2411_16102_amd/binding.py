@@ -101,6 +101,8 @@ def raw():
         lib.bs_kv_page_bytes.restype = C.c_int64
         lib.bs_kv_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         lib.bs_kv_unpack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        lib.bs_blend_layers.argtypes = [C.c_void_p, C.c_int32, C.POINTER(Weights), C.POINTER(BatchDesc), C.c_void_p, C.c_void_p,
+                                        C.POINTER(C.c_void_p), C.c_int64, C.c_void_p, C.c_uint32]
         lib.bs_blend_step.argtypes = [C.c_void_p, C.POINTER(Weights), C.POINTER(BatchDesc), C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_int64, C.c_void_p, C.c_uint32]
         lib.bs_validate_batch.argtypes = [C.c_void_p, C.POINTER(BatchDesc), C.c_int64]
@@ -263,6 +265,19 @@ class Layer:
         self._check(self.lib.bs_blend_step(self.h, C.byref(dev.weights), C.byref(d), C.c_void_p(dev.x.data_ptr()),
                                            C.c_void_p(y.data_ptr()), C.c_void_p(dev.kv_pool.data_ptr()),
                                            dev.n_pages, self._stream(stream), flags))
+        return y
+
+    def blend_layers(self, devs, batch, flags: int = 0, stream=None, y=None, desc=None):
+        """The step through len(devs) layers back to back: layer l uses devs[l].weights and
+        devs[l].kv_pool; the input is devs[0].x."""
+        d, keep = desc if desc is not None else marshal_batch(batch)
+        if y is None:
+            y = self.torch.empty_like(devs[0].x)
+        n = len(devs)
+        w = (Weights * n)(*[dv.weights for dv in devs])
+        pools = (C.c_void_p * n)(*[dv.kv_pool.data_ptr() for dv in devs])
+        self._check(self.lib.bs_blend_layers(self.h, n, w, C.byref(d), C.c_void_p(devs[0].x.data_ptr()),
+                                             C.c_void_p(y.data_ptr()), pools, devs[0].n_pages, self._stream(stream), flags))
         return y
 
     def attention(self, batch, q, kv_pool, n_pages: int, flags: int = 0, stream=None):

@@ -46,6 +46,7 @@ struct bs_ctx {
   float *x1 = nullptr, *rstd1 = nullptr, *rstd2 = nullptr, *ss2 = nullptr;
   long cap_slots = 0;
   float *part_acc = nullptr, *part_m = nullptr, *part_l = nullptr;
+  uint16_t *hid[2] = {nullptr, nullptr};  // activations between the layers of bs_blend_layers
   float *splitk_ws = nullptr;  // fp32 partial products of the split-K GEMMs (few-row steps)
   size_t cap_splitk = 0;
   // descriptor blob: pinned host ring and one device copy
@@ -110,6 +111,8 @@ int ensure_rows(bs_ctx *c, int rows) {
   int rc;
   c->cap_rows = 0;
   if ((rc = dev_alloc(c, &c->xg, (size_t)cap * g.d_model))) return rc;
+  if ((rc = dev_alloc(c, &c->hid[0], (size_t)cap * g.d_model))) return rc;
+  if ((rc = dev_alloc(c, &c->hid[1], (size_t)cap * g.d_model))) return rc;
   if ((rc = dev_alloc(c, &c->qbuf, (size_t)cap * hd))) return rc;
   if ((rc = dev_alloc(c, &c->attn, (size_t)cap * hd))) return rc;
   if ((rc = dev_alloc(c, &c->x1, (size_t)cap * g.d_model))) return rc;
@@ -615,7 +618,7 @@ void bs_destroy(bs_ctx *c) {
   (void)hipDeviceSynchronize();
   for (void *p : {(void *)c->rope_cos, (void *)c->rope_sin, (void *)c->xg, (void *)c->qbuf, (void *)c->attn, (void *)c->x1,
                   (void *)c->xg2, (void *)c->act, (void *)c->rstd1, (void *)c->rstd2, (void *)c->ss2, (void *)c->part_acc, (void *)c->part_m,
-                  (void *)c->part_l, (void *)c->d_blob, (void *)c->splitk_ws})
+                  (void *)c->part_l, (void *)c->d_blob, (void *)c->splitk_ws, (void *)c->hid[0], (void *)c->hid[1]})
     if (p) (void)hipFree(p);
   for (int i = 0; i < RING; ++i) {
     if (c->h_blob[i]) (void)hipHostFree(c->h_blob[i]);
@@ -675,26 +678,14 @@ int bs_resolve_rows(bs_ctx *c, const bs_batch *b, int32_t *page_out, int32_t *sl
   return BS_OK;
 }
 
-int bs_blend_step(bs_ctx *c, const bs_weights *w, const bs_batch *b, const void *x_, void *y_, void *pool_,
-                  int64_t n_pages, void *stream_, uint32_t flags) {
-  if (!c) return BS_EINVAL;
-  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
-  if (!w || !w->w_qkv || !w->w_o || !w->w_gate_up || !w->w_down || !w->g_attn || !w->g_ffn)
-    return fail(c, BS_EINVAL, "a weight pointer is NULL");
-  int rc = validate(c, b, n_pages);
-  if (rc) return rc;
-  if (b->n_rows == 0) return BS_OK;
-  if (!x_ || !y_ || !pool_ || x_ == y_) return fail(c, BS_EINVAL, "x, y, kv_pool must be distinct non-NULL device pointers");
-  HIP_TRY(c, hipSetDevice(c->device));
-  hipStream_t st = (hipStream_t)stream_;
-  const uint16_t *x = (const uint16_t *)x_;
-  uint16_t *y = (uint16_t *)y_, *pool = (uint16_t *)pool_;
-  Plan p;
-  if ((rc = build_plan(c, b, p, true))) return rc;
-  if ((rc = ensure_rows(c, p.n_rows))) return rc;
-  if ((rc = ensure_slots(c, p.n_slots))) return rc;
-  if ((rc = upload_plan(c, p, st))) return rc;
+}  // extern "C"
 
+namespace {
+
+// every kernel of one layer for the planned batch: x -> y, appending to `pool`
+int run_layer(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, uint16_t *y, uint16_t *pool, hipStream_t st,
+              uint32_t flags) {
+  int rc;
   const bs_layer_cfg &g = c->cfg;
   const int T = p.n_rows, d = g.d_model, hd = g.n_q_heads * g.head_dim;
   SPAN(c, BS_K_PREP, st, HIP_TRY(c, launch_norm_prep(x, (const uint16_t *)w->g_attn, c->xg, c->rstd1, T, d, g.rms_eps, st)));
@@ -737,6 +728,62 @@ int bs_blend_step(bs_ctx *c, const bs_weights *w, const bs_batch *b, const void 
     HIP_TRY(c, hipStreamWaitEvent(st, c->ev_b, 0));
     if ((rc = run_o_gate_up(c, w, x, Tp, T, st, 0))) return rc;
     if ((rc = run_down(c, w, y, 0, T, st, 0))) return rc;
+  }
+  return BS_OK;
+}
+
+bool weights_ok(const bs_weights *w) {
+  return w && w->w_qkv && w->w_o && w->w_gate_up && w->w_down && w->g_attn && w->g_ffn;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bs_blend_step(bs_ctx *c, const bs_weights *w, const bs_batch *b, const void *x_, void *y_, void *pool_,
+                  int64_t n_pages, void *stream_, uint32_t flags) {
+  if (!c) return BS_EINVAL;
+  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
+  if (!weights_ok(w)) return fail(c, BS_EINVAL, "a weight pointer is NULL");
+  int rc = validate(c, b, n_pages);
+  if (rc) return rc;
+  if (b->n_rows == 0) return BS_OK;
+  if (!x_ || !y_ || !pool_ || x_ == y_) return fail(c, BS_EINVAL, "x, y, kv_pool must be distinct non-NULL device pointers");
+  HIP_TRY(c, hipSetDevice(c->device));
+  hipStream_t st = (hipStream_t)stream_;
+  Plan p;
+  if ((rc = build_plan(c, b, p, true))) return rc;
+  if ((rc = ensure_rows(c, p.n_rows))) return rc;
+  if ((rc = ensure_slots(c, p.n_slots))) return rc;
+  if ((rc = upload_plan(c, p, st))) return rc;
+  return run_layer(c, p, w, (const uint16_t *)x_, (uint16_t *)y_, (uint16_t *)pool_, st, flags);
+}
+
+int bs_blend_layers(bs_ctx *c, int32_t n_layers, const bs_weights *w, const bs_batch *b, const void *x_, void *y_,
+                    void *const *pools, int64_t n_pages, void *stream_, uint32_t flags) {
+  if (!c) return BS_EINVAL;
+  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
+  if (n_layers < 1 || !w || !pools) return fail(c, BS_EINVAL, "bs_blend_layers: n_layers %d, weights or pools NULL", n_layers);
+  for (int l = 0; l < n_layers; ++l)
+    if (!weights_ok(&w[l]) || !pools[l]) return fail(c, BS_EINVAL, "layer %d: a weight or pool pointer is NULL", l);
+  int rc = validate(c, b, n_pages);
+  if (rc) return rc;
+  if (b->n_rows == 0) return BS_OK;
+  if (!x_ || !y_ || x_ == y_) return fail(c, BS_EINVAL, "x and y must be distinct non-NULL device pointers");
+  HIP_TRY(c, hipSetDevice(c->device));
+  hipStream_t st = (hipStream_t)stream_;
+  Plan p;
+  if ((rc = build_plan(c, b, p, true))) return rc;
+  if ((rc = ensure_rows(c, p.n_rows))) return rc;
+  if ((rc = ensure_slots(c, p.n_slots))) return rc;
+  if ((rc = upload_plan(c, p, st))) return rc;
+  // one descriptor, validated, planned and uploaded once; activations alternate between two
+  // workspace buffers so that neither x nor y is touched before / after its own layer
+  const uint16_t *in = (const uint16_t *)x_;
+  for (int l = 0; l < n_layers; ++l) {
+    uint16_t *out = (l == n_layers - 1) ? (uint16_t *)y_ : c->hid[l & 1];
+    if ((rc = run_layer(c, p, &w[l], in, out, (uint16_t *)pools[l], st, flags))) return rc;
+    in = out;
   }
   return BS_OK;
 }

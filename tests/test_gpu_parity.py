@@ -225,6 +225,35 @@ def test_shared_and_expanded_kv_agree(lib):
     assert np.mean(np.abs(y - y2)) < MAE
 
 
+def test_layers_back_to_back(lib):
+    # three layers with their own weights and pools behind one descriptor; the activations passed
+    # between layers are bf16 (that is the boundary's dtype), so the oracle chain rounds them too
+    import dataclasses
+    import torch
+    shape = W.TINY
+    batch = W.batch_random(11, n_prefill=3, n_decode=12, max_q=50, max_ctx=300)
+    tens = [W.make_tensors(shape, batch, 20 + l, gains="random") for l in range(3)]
+    layer = lib.Layer(shape, device=0)
+    devs = [layer.upload(t, batch) for t in tens]
+    y = layer.blend_layers(devs, batch)
+    torch.cuda.synchronize()
+    x = tens[0].x
+    for l, t in enumerate(tens):
+        ref = O.layer_step(shape, dataclasses.replace(t, x=x), batch)
+        x = W.round_to_bf16(ref["y"].astype(np.float32))
+        k, v = layer.unpack_pool(devs[l].kv_pool, devs[l].n_pages)
+        kn = to_np(k)[ref["dest"][:, 0], ref["dest"][:, 1]]
+        assert errs(kn, ref["k_new"])[0] <= MAXREL, "layer %d keys" % l
+    maxrel, mae = errs(to_np(y), ref["y"])
+    print("3 layers: maxrel=%.3e mae=%.3e" % (maxrel, mae))
+    assert maxrel <= MAXREL and mae <= 3 * MAE
+    # one layer through the same entry point equals the single-step call bit for bit
+    y1 = layer.blend_layers([layer.upload(tens[0], batch)], batch)
+    y0 = layer.blend_step(layer.upload(tens[0], batch), batch)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+
+
 def test_overlap_mode_matches_serial(lib):
     batch = W.batch_random(4, n_prefill=4, n_decode=30, max_q=120, max_ctx=500)
     tens = W.make_tensors(W.TINY, batch, 4)
