@@ -345,17 +345,41 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
 
   const int last_tok = first_pos + n_q - 1;
   const int n_tb = last_tok / 32 + 1;
-  for (int tb = 0; tb < n_tb; ++tb) {
-    const size_t p0 = pages[2 * tb];
-    const size_t p1 = (2 * tb + 1 < n_pg) ? pages[2 * tb + 1] : p0;
+  // Software pipeline: the keys of block tb+1 and the values of block tb are requested
+  // before the score MFMAs of block tb are issued, so both loads have a whole block of
+  // arithmetic to arrive.  A step past the end re-reads the last block (never used).
+  auto page_pair = [&](int tb, size_t &p0, size_t &p1) {
+    const int t = tb < n_tb ? tb : n_tb - 1;
+    p0 = pages[2 * t];
+    p1 = (2 * t + 1 < n_pg) ? pages[2 * t + 1] : p0;
+  };
+  auto load_k = [&](int tb, u32x4_t (&kf)[KC]) {
+    size_t p0, p1;
+    page_pair(tb, p0, p1);
     const size_t pk = (lr < 16) ? p0 : p1;
     const uint16_t *kp = a.kv_pool + ((pk * 2 + 0) * hkv + kvh) * tile + (lr & 15) * DH + 8 * g2;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) kf[c] = ld16(kp + 16 * c);
+  };
+  auto block = [&](int tb, const u32x4_t (&kf)[KC]) {
+    size_t p0, p1;
+    page_pair(tb, p0, p1);
+    u32x2_t va[DB][4];  // values of the block: [32-row block of dh][8-token group]
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const uint16_t *v0 = a.kv_pool + ((p0 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
+      const uint16_t *v1 = a.kv_pool + ((p1 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
+      va[db][0] = ld8(v0);
+      va[db][1] = ld8(v0 + 8);
+      va[db][2] = ld8(v1);
+      va[db][3] = ld8(v1 + 8);
+    }
     f32x16_t s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
     for (int c = 0; c < KC; ++c)
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ld16(kp + 16 * c)), qf[c], s, 0, 0, 0);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[c]), qf[c], s, 0, 0, 0);
     // element r: token tb*32 + 8*(r/4) + 4*g2 + r%4 against the query at my_pos
     float mx = NEG_BIG;
 #pragma unroll
@@ -365,16 +389,23 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
       mx = fmaxf(mx, s[r]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m, mx);
-    const float alpha = fast_exp2(m - m_new);
-    m = m_new;
+    // lazy reference exponent, as in the decode kernel: rescale only when somebody's maximum
+    // has grown by more than 2^TAU
+    if (__builtin_amdgcn_ballot_w64(mx > m + TAU) != 0) {
+      const float m_new = fmaxf(m, mx);
+      const float alpha = fast_exp2(m - m_new);
+      m = m_new;
+      l *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) o[db] *= alpha;
+    }
     float ps = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      s[r] = fast_exp2(s[r] - m_new);
+      s[r] = fast_exp2(s[r] - m);
       ps += s[r];
     }
-    l = l * alpha + ps;
+    l += ps;
     u32x4_t pw0, pw1;
     pw0.x = pack_bf16x2(s[0], s[1]);
     pw0.y = pack_bf16x2(s[2], s[3]);
@@ -387,21 +418,28 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
     const bool ragged = tb * 32 + 32 > kv_len;
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
-      const uint16_t *v0 = a.kv_pool + ((p0 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
-      const uint16_t *v1 = a.kv_pool + ((p1 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
-      u32x2_t a0 = ld8(v0), a1 = ld8(v0 + 8), b0 = ld8(v1), b1 = ld8(v1 + 8);
+      u32x2_t a0 = va[db][0], a1 = va[db][1], b0 = va[db][2], b1 = va[db][3];
       if (ragged) {
         a0 = mask_tokens(a0, tb * 32 + 4 * g2, kv_len);
         a1 = mask_tokens(a1, tb * 32 + 8 + 4 * g2, kv_len);
         b0 = mask_tokens(b0, tb * 32 + 16 + 4 * g2, kv_len);
         b1 = mask_tokens(b1, tb * 32 + 24 + 4 * g2, kv_len);
       }
-      u32x4_t va, vb;
-      va.x = a0.x; va.y = a0.y; va.z = a1.x; va.w = a1.y;
-      vb.x = b0.x; vb.y = b0.y; vb.z = b1.x; vb.w = b1.y;
-      o[db] *= alpha;
-      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va), as_bf16x8(pw0), o[db], 0, 0, 0);
-      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vb), as_bf16x8(pw1), o[db], 0, 0, 0);
+      u32x4_t xa, xb;
+      xa.x = a0.x; xa.y = a0.y; xa.z = a1.x; xa.w = a1.y;
+      xb.x = b0.x; xb.y = b0.y; xb.z = b1.x; xb.w = b1.y;
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(xa), as_bf16x8(pw0), o[db], 0, 0, 0);
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(xb), as_bf16x8(pw1), o[db], 0, 0, 0);
+    }
+  };
+  u32x4_t ka[KC], kb[KC];
+  load_k(0, ka);
+  for (int tb = 0; tb < n_tb; tb += 2) {
+    load_k(tb + 1, kb);
+    block(tb, ka);
+    if (tb + 1 < n_tb) {
+      load_k(tb + 2, ka);
+      block(tb + 1, kb);
     }
   }
   l += __shfl_xor(l, 32, 64);
