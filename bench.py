@@ -163,13 +163,17 @@ def main():
     run(args.steps, flags)
     prof = layer.profile_read()
     layer.profile(False)
-    kernels = {k: {"ms": (ms / n if n else 0.0), "launches_per_step": n / args.steps} for k, (ms, n) in prof.items()}
+    # per kernel class: milliseconds per step and layer (all launches of the class added up)
+    kernels = {k: {"ms": ms / (args.steps * args.layers), "launches_per_step": n / (args.steps * args.layers)}
+               for k, (ms, n) in prof.items()}
 
     T, d, f = batch.n_rows, shape.d_model, shape.d_ffn
     gu_flops = 2.0 * T * d * 2 * f
-    gu_launches = max(1, prof["gemm_gate_up"][1])
-    gu_ms = prof["gemm_gate_up"][0] / gu_launches            # average launch duration
-    gu_flops_per_launch = gu_flops * args.steps * args.layers / gu_launches
+    # the gate/up GEMM may go out as two launches (whole rounds of tiles, then the rest): its
+    # duration is the sum of its launches' durations, averaged over the GEMMs of the pass
+    n_gemms = args.steps * args.layers
+    gu_ms = prof["gemm_gate_up"][0] / n_gemms
+    gu_flops_per_launch = gu_flops
     t_flop = work["flops"] / PEAK_MFMA_BF16
     t_byte = work["bytes_once"] / PEAK_HBM
     bound = "mfma" if t_flop >= t_byte else "hbm"
@@ -181,7 +185,7 @@ def main():
                                                  ["gemm.hip", "gemm.hpp", "common.hpp"])
                                 if args.workload == "blended_8b" else None)}
     else:
-        dec_ms = prof["attn_decode"][0] / max(1, prof["attn_decode"][1])
+        dec_ms = prof["attn_decode"][0] / n_gemms
         kv_bytes = work["kv_tokens_once"] * shape.kv_bytes_per_token
         roofline = {"bound": "hbm", "kernel": "decode_attn (paged, prefix-aware)",
                     "achieved": kv_bytes / (dec_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",

@@ -507,7 +507,13 @@ int run_o_gate_up(bs_ctx *c, const bs_weights *w, const uint16_t *x, int r0, int
   u.M = rows; u.N = f; u.K = d;
   u.C = c->act + (size_t)r0 * f; u.ldc = f;
   u.rstd = c->rstd2 + r0;
-  SPAN(c, BS_K_GEMM_GATE_UP, st, HIP_TRY(c, launch_gemm(u, EPI_SWIGLU, g.head_dim, st)));
+  GemmArgs head, tail;
+  if (gemm_round_split(u, EPI_SWIGLU, g.head_dim, &head, &tail)) {
+    SPAN(c, BS_K_GEMM_GATE_UP, st, HIP_TRY(c, launch_gemm(head, EPI_SWIGLU, g.head_dim, st)));
+    SPAN(c, BS_K_GEMM_GATE_UP, st, HIP_TRY(c, launch_gemm(tail, EPI_SWIGLU, g.head_dim, st)));
+  } else {
+    SPAN(c, BS_K_GEMM_GATE_UP, st, HIP_TRY(c, launch_gemm(u, EPI_SWIGLU, g.head_dim, st)));
+  }
   return BS_OK;
 }
 
@@ -863,7 +869,7 @@ int bs_profile_read(bs_ctx *c, int which, double *total_ms, int64_t *launches) {
 
 int bs_set_gemm_tiles(bs_ctx *c, int32_t variant) {
   if (!c) return BS_EINVAL;
-  if (variant < 0 || variant > 4) return fail(c, BS_EINVAL, "gemm tile variant %d (0..4)", variant);
+  if (variant < 0 || variant > 3) return fail(c, BS_EINVAL, "gemm tile variant %d (0..3)", variant);
   gemm_force_variant(variant);
   return BS_OK;
 }

@@ -26,16 +26,6 @@ namespace bs {
 namespace {
 
 constexpr float NEG_BIG = -1.0e30f;
-constexpr int XCDS = 8;
-
-// contiguous ranges of workgroups per XCD (ids are dealt round-robin to the XCDs),
-// so that neighbouring work, which reads the same pages, meets in one L2
-__device__ __forceinline__ int xcd_contiguous(int pid, int n) {
-  const int per = n / XCDS, rem = n % XCDS;
-  const int xcd = pid % XCDS, idx = pid / XCDS;
-  return xcd * per + (xcd < rem ? xcd : rem) + idx;
-}
-
 __device__ __forceinline__ u32x4_t ld16(const uint16_t *p) { return *reinterpret_cast<const u32x4_t *>(p); }
 __device__ __forceinline__ u32x2_t ld8(const uint16_t *p) { return *reinterpret_cast<const u32x2_t *>(p); }
 

@@ -572,7 +572,7 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
 // Tile shapes.  BIG: 256x256, 8 wavefronts.  TALL: 160x256, 4 wavefronts of 160x64: 2560 (and
 // 5120) rows by 4096 (8192) columns then make exactly one (four) full rounds of 256
 // workgroups where 256x256 tiles leave 38 % (17 %) of the CUs idle.  SMALL: 128x128.
-enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3, V_QUAD = 4 };
+enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3 };
 constexpr int N_CU = 256;
 
 int g_forced_variant = V_AUTO;
@@ -603,13 +603,29 @@ template <int EPI, int DH_BIG_M, int DH_BIG_N>
 hipError_t launch_variant(const GemmArgs &a, int v, hipStream_t stream) {
   if (v == V_BIG) return launch_one<256, 256, DH_BIG_M, DH_BIG_N, EPI, (DH_BIG_M == 4 ? 128 : 64)>(a, stream);
   if (v == V_TALL) return launch_one<160, 256, 1, 4, EPI, 64>(a, stream);
-  if (v == V_QUAD) return launch_one<256, 256, 2, 2, EPI, 64>(a, stream);
   return launch_one<128, 128, 2, 2, EPI, 64>(a, stream);
 }
 
 }  // namespace
 
 void gemm_force_variant(int v) { g_forced_variant = v; }
+
+bool gemm_round_split(const GemmArgs &a, int epilogue, int dh, GemmArgs *head, GemmArgs *tail) {
+  if (epilogue != EPI_SWIGLU || g_forced_variant != V_AUTO || a.k_splits > 1) return false;
+  const int n_cols = a.n_count ? a.n_count : a.N;
+  if (choose_variant(a.M, 2 * n_cols, epilogue, dh, a.n_cu) != V_BIG) return false;
+  const int n_cu = a.n_cu > 0 ? a.n_cu : N_CU;
+  const long tm = (a.M + 255) / 256, tn = (n_cols + 127) / 128;  // a 256x256 tile yields 128 output columns
+  const long tiles = tm * tn, full = tiles / n_cu, idle = (full + 1) * n_cu - tiles;
+  const long cols_big = full * n_cu / tm;
+  if (full < 1 || tiles % n_cu == 0 || idle * 4 <= n_cu || cols_big < 1 || cols_big >= tn) return false;
+  *head = a;
+  *tail = a;
+  head->n_count = (int)cols_big * 128;
+  tail->n_begin = a.n_begin + head->n_count;
+  tail->n_count = n_cols - head->n_count;
+  return true;
+}
 
 int gemm_splitk_choice(int M, int N, int K, int epilogue, int n_cu) {
   if (epilogue != EPI_RESID && epilogue != EPI_RESID_NORM && epilogue != EPI_QKV) return 1;
@@ -626,7 +642,6 @@ int gemm_ss_parts(const GemmArgs &a, int epilogue, int dh) {
   if (a.k_splits > 1) return 1;  // the split-K reduction leaves whole row sums
   const int v = choose_variant(a.M, a.N, epilogue, dh, a.n_cu);
   // partial row sums: one per (column tile, wavefront column)
-  if (v == V_QUAD) return ((a.N + 255) / 256) * 2;
   return v == V_SMALL ? ((a.N + 127) / 128) * 2 : ((a.N + 255) / 256) * 4;
 }
 
@@ -653,23 +668,6 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stre
   if (a.n_count && epilogue != EPI_SWIGLU && epilogue != EPI_PLAIN) return hipErrorInvalidValue;
   const int n_cols = a.n_count ? a.n_count : a.N;
   const int v = choose_variant(a.M, (epilogue == EPI_SWIGLU) ? 2 * n_cols : n_cols, epilogue, dh, a.n_cu);
-  if (epilogue == EPI_SWIGLU && v == V_BIG && g_forced_variant == V_AUTO) {
-    // Whole rounds of 256x256 tiles first; if the last round would leave more than a quarter
-    // of the chip idle, its columns go to a second launch with whatever shape suits them.
-    const int n_cu = a.n_cu > 0 ? a.n_cu : N_CU;
-    const long tm = (a.M + 255) / 256, tn = (n_cols + 127) / 128;  // a tile yields 128 output columns
-    const long tiles = tm * tn, full = tiles / n_cu, idle = (full + 1) * n_cu - tiles;
-    const long cols_big = full * n_cu / tm;
-    if (full >= 1 && tiles % n_cu != 0 && idle * 4 > n_cu && cols_big >= 1 && cols_big < tn) {
-      GemmArgs head = a, tail = a;
-      head.n_count = (int)cols_big * 128;
-      tail.n_begin = a.n_begin + head.n_count;
-      tail.n_count = n_cols - head.n_count;
-      hipError_t e = launch_one<256, 256, 2, 4, EPI_SWIGLU, 64>(head, stream);
-      if (e != hipSuccess) return e;
-      return launch_gemm(tail, epilogue, dh, stream);
-    }
-  }
   switch (epilogue) {
     case EPI_PLAIN: return launch_variant<EPI_PLAIN, 2, 4>(a, v, stream);
     case EPI_RESID: return launch_variant<EPI_RESID, 2, 4>(a, v, stream);
@@ -677,13 +675,11 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stre
     case EPI_SWIGLU: return launch_variant<EPI_SWIGLU, 2, 4>(a, v, stream);
     case EPI_QKV:
       if (dh == 128)
-        return v == V_QUAD  ? launch_one<256, 256, 2, 2, EPI_QKV, 128>(a, stream)
-               : v == V_BIG ? launch_one<256, 256, 4, 2, EPI_QKV, 128>(a, stream)
-                            : launch_one<128, 128, 4, 1, EPI_QKV, 128>(a, stream);
+        return v == V_BIG ? launch_one<256, 256, 4, 2, EPI_QKV, 128>(a, stream)
+                          : launch_one<128, 128, 4, 1, EPI_QKV, 128>(a, stream);
       if (dh == 64)
-        return v == V_QUAD  ? launch_one<256, 256, 2, 2, EPI_QKV, 64>(a, stream)
-               : v == V_BIG ? launch_one<256, 256, 2, 4, EPI_QKV, 64>(a, stream)
-                            : launch_one<128, 128, 2, 2, EPI_QKV, 64>(a, stream);
+        return v == V_BIG ? launch_one<256, 256, 2, 4, EPI_QKV, 64>(a, stream)
+                          : launch_one<128, 128, 2, 2, EPI_QKV, 64>(a, stream);
       return hipErrorInvalidValue;
     default:
       return hipErrorInvalidValue;

@@ -56,6 +56,11 @@ struct GemmArgs {
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream);
 // partial-sum slots a RESID_NORM launch over N columns writes
 int gemm_ss_parts(const GemmArgs &a, int epilogue, int dh);
+// Whole rounds first: when a gate/up GEMM on 256x256 tiles would end with a round that leaves
+// more than a quarter of the chip idle, returns true and the two column ranges to launch
+// instead: `head` = the tile columns of the whole rounds, `tail` = the rest (whatever tile
+// shape suits them).
+bool gemm_round_split(const GemmArgs &a, int epilogue, int dh, GemmArgs *head, GemmArgs *tail);
 // Number of k-ranges worth using for this problem (1 = no split): only when the tiles would
 // leave most of the chip idle and every range keeps at least eight k-tiles.
 int gemm_splitk_choice(int M, int N, int K, int epilogue, int n_cu);
