@@ -211,6 +211,36 @@ def test_decode_only_and_prefill_only(lib):
         check_step(lib, W.TINY, batch, tens)
 
 
+def test_degenerate_batches(lib):
+    import torch
+    shape = W.TINY
+    layer = lib.Layer(shape, device=0)
+    # an empty batch is accepted and touches nothing
+    empty = W.assemble_batch(16, [], 0, [], None)
+    tens = W.make_tensors(shape, W.batch_tiny(0), 0)
+    dev = layer.upload(tens, W.batch_tiny(0))
+    y = torch.full_like(dev.x, 7.0)
+    layer.blend_step(dev, empty, y=y)
+    torch.cuda.synchronize()
+    assert bool((y == 7.0).all())
+    # one decode sequence whose context is its own token: attention returns its value vector
+    # (softmax over one score is 1), so this reduces to the dense part of the layer
+    one = W.assemble_batch(16, [(1, 1, -1)], 0, [], None)
+    check_step(lib, shape, one, W.make_tensors(shape, one, 1))
+    # a one-row prefill chunk behind a cached context, contexts that end exactly on a page
+    # boundary, and one that starts a fresh page with this step's row
+    edge = W.assemble_batch(16, [(1, 48, -1), (16, 32, -1), (3, 35, -1), (1, 16, -1), (1, 17, -1), (1, 33, -1)], 3, [],
+                            np.random.default_rng(5))
+    check_step(lib, shape, edge, W.make_tensors(shape, edge, 2, gains="random"))
+
+
+@pytest.mark.parametrize("shape", [W.LayerShape(512, 16, 1, 64, 256), W.LayerShape(256, 4, 4, 64, 344)])
+def test_group_sizes_sixteen_and_one(lib, shape):
+    # 16 query heads per KV head (one member fills a decode work item) and plain multi-head attention
+    batch = W.batch_random(8, n_prefill=2, n_decode=14, max_q=40, max_ctx=260, n_roots=2)
+    check_step(lib, shape, batch, W.make_tensors(shape, batch, 8))
+
+
 def test_shared_and_expanded_kv_agree(lib):
     batch = W.batch_random(21, n_prefill=2, n_decode=24, max_ctx=300, n_roots=3)
     tens = W.make_tensors(W.TINY, batch, 21)
