@@ -107,6 +107,17 @@ typedef struct bs_batch_owned {
  * decode members and at least one whole page, physical pages are numbered node pages
  * first (DFS order), then each sequence's private pages in sequence order. */
 int bs_builder_next_batch(bs_builder *b, int64_t prefill_budget, int64_t decode_budget, bs_batch_owned **out);
+
+/* The descriptor of an explicit step, for a driver that keeps the requests' state itself
+ * (Section 5.3: the runtime batch is re-formed every iteration from the requests in flight;
+ * Appendix A.2): n_pre prefill segments - request, prompt tokens whose KV is already cached,
+ * rows to compute this step (cached + chunk <= prompt length) - in the order given, then n_dec
+ * decode sequences - request, tokens cached before this step (>= prompt length) - emitted in
+ * leaf order.  A request may appear once.  Prefix nodes and page numbering as in
+ * bs_builder_next_batch; `info` of the result is zero. */
+int bs_builder_emit(bs_builder *b, int32_t n_pre, const int32_t *pre_req, const int32_t *pre_cached,
+                    const int32_t *pre_chunk, int32_t n_dec, const int32_t *dec_req, const int32_t *dec_ctx,
+                    bs_batch_owned **out);
 void bs_batch_free(bs_batch_owned *batch);
 
 #ifdef __cplusplus

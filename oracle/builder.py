@@ -486,10 +486,25 @@ class BuilderOracle:
                     j -= 1
                 else:
                     go_r = False
-        pos_in_order = {ri: k for k, ri in enumerate(order)}
-        dec = sorted(dec_l + dec_r, key=lambda ri: pos_in_order[ri])
+        dec = dec_l + dec_r
         b.update(n_prefill=len(pre), n_decode=len(dec))
+        desc = self.emit([(ri, self.reqs[ri].n_cached, chunk) for ri, chunk in pre],
+                         [(ri, self.reqs[ri].n_cached) for ri in dec])
+        return b, desc
 
+    def emit(self, pre: Sequence[Tuple[int, int, int]], dec: Sequence[Tuple[int, int]]):
+        """The batch descriptor of an explicit step: prefill segments (request, tokens already
+        cached, rows this step) in the order given, then decode sequences (request, tokens cached
+        before this step) in leaf order.  Prefix nodes = trie nodes with at least two of the decode
+        sequences below them and at least one whole page of their own; pages are numbered afresh:
+        node pages first (DFS order), then every sequence's private pages."""
+        ps = self.cm.page_size
+        order = self.leaf_order
+        pos_in_order = {ri: k for k, ri in enumerate(order)}
+        ctx_of = {ri: c for ri, c in dec}
+        cached_of = {ri: c for ri, c, _ in pre}
+        pre = [(ri, chunk) for ri, _, chunk in pre]
+        dec = sorted((ri for ri, _ in dec), key=lambda ri: pos_in_order[ri])
         # ---- descriptor ----------------------------------------------------------------
         # prefix nodes: trie nodes (in DFS order) with >= 2 admitted decode members and >= 1 whole page
         dec_pos = {ri: k for k, ri in enumerate(dec)}
@@ -534,7 +549,7 @@ class BuilderOracle:
         row_start, kv_len, page_start, page_ids, seq_leaf, seq_req = [0], [], [0], [], [], []
         for ri, chunk in pre:
             r = self.reqs[ri]
-            kv = r.n_cached + chunk
+            kv = cached_of[ri] + chunk
             npg = -(-kv // ps)
             page_ids.extend(range(next_page, next_page + npg))
             next_page += npg
@@ -542,7 +557,7 @@ class BuilderOracle:
             kv_len.append(kv); page_start.append(len(page_ids)); seq_leaf.append(-1); seq_req.append(ri)
         for ri in dec:
             r = self.reqs[ri]
-            kv = r.n_cached + 1
+            kv = ctx_of[ri] + 1
             # deepest kept node on the request's path
             n = self.nodes[leaf_node_of_req[ri]].parent
             while n >= 0 and n not in node_id:
@@ -568,4 +583,4 @@ class BuilderOracle:
                     n_nodes=len(node_parent), node_parent=i32(node_parent), node_page_start=i32(node_page_start),
                     node_page_ids=i32(node_page_ids), node_seq_first=i32(node_first), node_seq_count=i32(node_count),
                     seq_leaf_node=i32(seq_leaf), seq_request=i32(seq_req), n_pages=next_page)
-        return b, desc
+        return desc

@@ -129,6 +129,8 @@ def raw():
         lib.bs_builder_tree_size.argtypes = [C.c_void_p, _i32p, _i32p]
         lib.bs_builder_tree.argtypes = [C.c_void_p] + [_i32p] * 6 + [_i64p, _i64p, _i32p]
         lib.bs_builder_next_batch.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.POINTER(C.POINTER(BatchOwned))]
+        lib.bs_builder_emit.argtypes = [C.c_void_p, C.c_int32, _i32p, _i32p, _i32p, C.c_int32, _i32p, _i32p,
+                                        C.POINTER(C.POINTER(BatchOwned))]
         lib.bs_batch_free.argtypes = [C.POINTER(BatchOwned)]
         lib.bs_batch_free.restype = None
         _lib = lib
@@ -388,10 +390,7 @@ class Builder:
         return dict(parent=parent[:n], start=start[:n], end=end[:n], req=req[:n], first_leaf=first[:n],
                     leaf_count=count[:n], A=A[:n], B=B[:n], leaf_order=order[:nr.value])
 
-    def next_batch(self, prefill_budget=0, decode_budget=0):
-        """Returns (info dict, descriptor dict of numpy arrays); the library's copy is freed."""
-        out = C.POINTER(BatchOwned)()
-        self._check(self.lib.bs_builder_next_batch(self.h, int(prefill_budget), int(decode_budget), C.byref(out)))
+    def _take(self, out):
         o = out.contents
         b = o.batch
         arr = lambda p, n: np.ctypeslib.as_array(p, shape=(max(1, n),))[:n].copy()
@@ -408,6 +407,22 @@ class Builder:
         info = {k: getattr(o.info, k) for k, _ in ScanInfo._fields_}
         self.lib.bs_batch_free(out)
         return info, d
+
+    def next_batch(self, prefill_budget=0, decode_budget=0):
+        """Returns (info dict, descriptor dict of numpy arrays); the library's copy is freed."""
+        out = C.POINTER(BatchOwned)()
+        self._check(self.lib.bs_builder_next_batch(self.h, int(prefill_budget), int(decode_budget), C.byref(out)))
+        return self._take(out)
+
+    def emit(self, pre, dec):
+        """Descriptor of an explicit step: pre = [(request, cached, chunk)], dec = [(request, ctx)]."""
+        i32 = lambda v: np.ascontiguousarray(np.asarray(v, dtype=np.int32))
+        pr, pc, pk = (i32([x[k] for x in pre]) for k in range(3))
+        dr, dc = (i32([x[k] for x in dec]) for k in range(2))
+        out = C.POINTER(BatchOwned)()
+        self._check(self.lib.bs_builder_emit(self.h, len(pre), _ptr(pr), _ptr(pc), _ptr(pk), len(dec), _ptr(dr), _ptr(dc),
+                                             C.byref(out)))
+        return self._take(out)[1]
 
 
 class _Api:

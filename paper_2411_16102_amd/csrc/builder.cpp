@@ -277,6 +277,98 @@ std::vector<int32_t> longest_non_increasing(const std::vector<int64_t> &A, const
   return out;
 }
 
+struct Pre { int32_t req, cached, chunk; };  // a prefill segment: request, tokens already cached, rows this step
+struct Dec { int32_t req, ctx; };            // a decode sequence: request, tokens cached before this step
+
+// The descriptor of an explicit step: the prefill segments in the order given, then the decode
+// sequences in leaf order.  Prefix nodes = trie nodes with at least two of the decode sequences
+// below them and at least one whole page of their own; pages are numbered afresh, node pages
+// first (DFS order), then every sequence's private pages.
+int emit(bs_builder *b, const std::vector<Pre> &pre, std::vector<Dec> dec, bs_batch_owned **out) {
+  const std::vector<Node> &nd = b->nodes;
+  const int32_t ps = b->cm.page_size;
+  std::vector<int32_t> leaf_pos(b->reqs.size(), 0);
+  for (size_t i = 0; i < b->leaf_order.size(); ++i) leaf_pos[b->leaf_order[i]] = (int32_t)i;
+  std::sort(dec.begin(), dec.end(), [&](const Dec &x, const Dec &y) { return leaf_pos[x.req] < leaf_pos[y.req]; });
+
+  // prefix nodes: internal trie nodes with >= 2 admitted decode members and >= 1 whole new page
+  const int32_t n_pre = (int32_t)pre.size(), n_dec = (int32_t)dec.size();
+  std::vector<int32_t> mem_count(nd.size(), 0), mem_first(nd.size(), std::numeric_limits<int32_t>::max());
+  for (int32_t k = 0; k < n_dec; ++k) {
+    int32_t n = nd[b->leaf_node[dec[k].req]].parent;
+    while (n >= 0) { ++mem_count[n]; mem_first[n] = std::min(mem_first[n], k); n = nd[n].parent; }
+  }
+  std::vector<int32_t> node_id(nd.size(), -1), cover(nd.size(), 0);
+  std::vector<int32_t> o_parent, o_first, o_count, o_pstart{0}, o_pages;
+  int64_t next_page = 0;
+  for (size_t n = 0; n < nd.size(); ++n) {
+    if (nd[n].req >= 0) continue;
+    const int32_t par = nd[n].parent;
+    const int32_t above = par >= 0 ? cover[par] : 0;
+    const int32_t hi = nd[n].end / ps;
+    if (mem_count[n] >= 2 && hi > above) {
+      int32_t anc = par;
+      while (anc >= 0 && node_id[anc] < 0) anc = nd[anc].parent;
+      node_id[n] = (int32_t)o_parent.size();
+      o_parent.push_back(anc >= 0 ? node_id[anc] : -1);
+      o_first.push_back(n_pre + mem_first[n]);
+      o_count.push_back(mem_count[n]);
+      for (int32_t k = above; k < hi; ++k) o_pages.push_back((int32_t)next_page++);
+      o_pstart.push_back((int32_t)o_pages.size());
+      cover[n] = hi;
+    } else {
+      cover[n] = above;
+    }
+  }
+  std::vector<int32_t> row_start{0}, kv_len, page_start{0}, page_ids, seq_leaf, seq_req;
+  for (const Pre &s : pre) {
+    const int32_t kv = s.cached + s.chunk;
+    const int32_t npg = (kv + ps - 1) / ps;
+    for (int32_t k = 0; k < npg; ++k) page_ids.push_back((int32_t)next_page++);
+    row_start.push_back(row_start.back() + s.chunk);
+    kv_len.push_back(kv); page_start.push_back((int32_t)page_ids.size()); seq_leaf.push_back(-1); seq_req.push_back(s.req);
+  }
+  std::vector<int32_t> path;
+  for (int32_t k = 0; k < n_dec; ++k) {
+    const int32_t ri = dec[k].req;
+    const int32_t kv = dec[k].ctx + 1;
+    int32_t n = nd[b->leaf_node[ri]].parent;
+    while (n >= 0 && node_id[n] < 0) n = nd[n].parent;
+    const int32_t leaf = n >= 0 ? node_id[n] : -1;
+    path.clear();
+    for (int32_t q = leaf; q >= 0; q = o_parent[q]) path.push_back(q);
+    int32_t shared = 0;
+    for (size_t q = path.size(); q-- > 0;) {
+      const int32_t id = path[q];
+      page_ids.insert(page_ids.end(), o_pages.begin() + o_pstart[id], o_pages.begin() + o_pstart[id + 1]);
+      shared += o_pstart[id + 1] - o_pstart[id];
+    }
+    const int32_t npg = (kv + ps - 1) / ps;
+    for (int32_t q = shared; q < npg; ++q) page_ids.push_back((int32_t)next_page++);
+    row_start.push_back(row_start.back() + 1);
+    kv_len.push_back(kv); page_start.push_back((int32_t)page_ids.size()); seq_leaf.push_back(leaf); seq_req.push_back(ri);
+  }
+
+  bs_batch_owned *o = new (std::nothrow) bs_batch_owned();
+  if (!o) return fail(b, BS_ENOMEM, "out of memory");
+  std::memset(o, 0, sizeof *o);
+  auto dup = [](const std::vector<int32_t> &v) {
+    int32_t *p = new int32_t[v.size() ? v.size() : 1];
+    if (!v.empty()) std::memcpy(p, v.data(), v.size() * sizeof(int32_t));
+    return p;
+  };
+  o->batch.n_seq = n_pre + n_dec; o->batch.n_prefill = n_pre; o->batch.n_rows = row_start.back();
+  o->batch.row_start = dup(row_start); o->batch.kv_len = dup(kv_len); o->batch.page_start = dup(page_start);
+  o->batch.page_ids = dup(page_ids);
+  o->batch.n_nodes = (int32_t)o_parent.size();
+  o->batch.node_parent = dup(o_parent); o->batch.node_page_start = dup(o_pstart); o->batch.node_page_ids = dup(o_pages);
+  o->batch.node_seq_first = dup(o_first); o->batch.node_seq_count = dup(o_count); o->batch.seq_leaf_node = dup(seq_leaf);
+  o->seq_request = dup(seq_req);
+  o->n_pages = next_page;
+  *out = o;
+  return BS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -428,6 +520,39 @@ int bs_builder_tree(const bs_builder *b, int32_t *parent, int32_t *start, int32_
   return BS_OK;
 }
 
+int bs_builder_emit(bs_builder *b, int32_t n_pre, const int32_t *pre_req, const int32_t *pre_cached,
+                    const int32_t *pre_chunk, int32_t n_dec, const int32_t *dec_req, const int32_t *dec_ctx,
+                    bs_batch_owned **out) {
+  if (!b || !out) return BS_EINVAL;
+  *out = nullptr;
+  if (!b->finalized) return fail(b, BS_EINVAL, "finalize the builder first");
+  if (n_pre < 0 || n_dec < 0 || (n_pre && (!pre_req || !pre_cached || !pre_chunk)) || (n_dec && (!dec_req || !dec_ctx)))
+    return fail(b, BS_EINVAL, "bs_builder_emit: bad counts or NULL arrays");
+  const int32_t nr = (int32_t)b->reqs.size();
+  std::vector<char> seen(nr, 0);
+  std::vector<Pre> pre;
+  std::vector<Dec> dec;
+  for (int32_t i = 0; i < n_pre; ++i) {
+    const int32_t r = pre_req[i];
+    if (r < 0 || r >= nr || seen[r]) return fail(b, BS_EINVAL, "prefill segment %d: request %d out of range or repeated", i, r);
+    seen[r] = 1;
+    const int64_t p = (int64_t)b->reqs[r].tok.size();
+    if (pre_cached[i] < 0 || pre_chunk[i] < 1 || (int64_t)pre_cached[i] + pre_chunk[i] > p)
+      return fail(b, BS_EINVAL, "prefill segment %d: cached %d + chunk %d must lie within the prompt (%lld tokens)", i,
+                  pre_cached[i], pre_chunk[i], (long long)p);
+    pre.push_back({r, pre_cached[i], pre_chunk[i]});
+  }
+  for (int32_t i = 0; i < n_dec; ++i) {
+    const int32_t r = dec_req[i];
+    if (r < 0 || r >= nr || seen[r]) return fail(b, BS_EINVAL, "decode sequence %d: request %d out of range or repeated", i, r);
+    seen[r] = 1;
+    if (dec_ctx[i] < (int64_t)b->reqs[r].tok.size())
+      return fail(b, BS_EINVAL, "decode sequence %d: context %d shorter than the prompt", i, dec_ctx[i]);
+    dec.push_back({r, dec_ctx[i]});
+  }
+  return emit(b, pre, dec, out);
+}
+
 void bs_batch_free(bs_batch_owned *o) {
   if (!o) return;
   delete[] o->batch.row_start; delete[] o->batch.kv_len; delete[] o->batch.page_start; delete[] o->batch.page_ids;
@@ -443,7 +568,6 @@ int bs_builder_next_batch(bs_builder *b, int64_t prefill_budget, int64_t decode_
   if (!b->finalized) return fail(b, BS_EINVAL, "finalize the builder first");
   if (b->reqs.empty()) return fail(b, BS_EINVAL, "no requests");
   const bs_cost_model &cm = b->cm;
-  const int32_t ps = cm.page_size;
   const std::vector<Node> &nd = b->nodes;
 
   // Algorithm 3 on the first branching node's leftmost and rightmost subtree
@@ -483,7 +607,6 @@ int bs_builder_next_batch(bs_builder *b, int64_t prefill_budget, int64_t decode_
     n_r = decode_budget - n_l;
   }
 
-  struct Pre { int32_t req, chunk; };
   std::vector<Pre> pre;
   std::vector<int32_t> dec;  // leaf-order positions of admitted decode requests
   const std::vector<int32_t> &order = b->leaf_order;
@@ -501,7 +624,7 @@ int bs_builder_next_batch(bs_builder *b, int64_t prefill_budget, int64_t decode_
     int64_t &c = left ? c_l : c_r;
     if (c <= 0) return false;
     const int32_t chunk = (int32_t)std::min<int64_t>(p - r.n_cached, c);
-    pre.push_back({ri, chunk});
+    pre.push_back({ri, r.n_cached, chunk});
     c -= chunk;
     return true;
   };
@@ -511,88 +634,13 @@ int bs_builder_next_batch(bs_builder *b, int64_t prefill_budget, int64_t decode_
     if (go_l && i <= j) { if (admit(i, true)) ++i; else go_l = false; }
     if (go_r && i <= j) { if (admit(j, false)) --j; else go_r = false; }
   }
-  std::sort(dec.begin(), dec.end());
   info.n_prefill = (int32_t)pre.size();
   info.n_decode = (int32_t)dec.size();
-
-  // prefix nodes: internal trie nodes with >= 2 admitted decode members and >= 1 whole new page
-  const int32_t n_pre = (int32_t)pre.size(), n_dec = (int32_t)dec.size();
-  std::vector<int32_t> mem_count(nd.size(), 0), mem_first(nd.size(), std::numeric_limits<int32_t>::max());
-  for (int32_t k = 0; k < n_dec; ++k) {
-    int32_t n = nd[b->leaf_node[order[dec[k]]]].parent;
-    while (n >= 0) { ++mem_count[n]; mem_first[n] = std::min(mem_first[n], k); n = nd[n].parent; }
-  }
-  std::vector<int32_t> node_id(nd.size(), -1), cover(nd.size(), 0);
-  std::vector<int32_t> o_parent, o_first, o_count, o_pstart{0}, o_pages;
-  int64_t next_page = 0;
-  for (size_t n = 0; n < nd.size(); ++n) {
-    if (nd[n].req >= 0) continue;
-    const int32_t par = nd[n].parent;
-    const int32_t above = par >= 0 ? cover[par] : 0;
-    const int32_t hi = nd[n].end / ps;
-    if (mem_count[n] >= 2 && hi > above) {
-      int32_t anc = par;
-      while (anc >= 0 && node_id[anc] < 0) anc = nd[anc].parent;
-      node_id[n] = (int32_t)o_parent.size();
-      o_parent.push_back(anc >= 0 ? node_id[anc] : -1);
-      o_first.push_back(n_pre + mem_first[n]);
-      o_count.push_back(mem_count[n]);
-      for (int32_t k = above; k < hi; ++k) o_pages.push_back((int32_t)next_page++);
-      o_pstart.push_back((int32_t)o_pages.size());
-      cover[n] = hi;
-    } else {
-      cover[n] = above;
-    }
-  }
-  std::vector<int32_t> row_start{0}, kv_len, page_start{0}, page_ids, seq_leaf, seq_req;
-  for (const Pre &s : pre) {
-    const Req &r = b->reqs[s.req];
-    const int32_t kv = r.n_cached + s.chunk;
-    const int32_t npg = (kv + ps - 1) / ps;
-    for (int32_t k = 0; k < npg; ++k) page_ids.push_back((int32_t)next_page++);
-    row_start.push_back(row_start.back() + s.chunk);
-    kv_len.push_back(kv); page_start.push_back((int32_t)page_ids.size()); seq_leaf.push_back(-1); seq_req.push_back(s.req);
-  }
-  std::vector<int32_t> path;
-  for (int32_t k = 0; k < n_dec; ++k) {
-    const int32_t ri = order[dec[k]];
-    const Req &r = b->reqs[ri];
-    const int32_t kv = r.n_cached + 1;
-    int32_t n = nd[b->leaf_node[ri]].parent;
-    while (n >= 0 && node_id[n] < 0) n = nd[n].parent;
-    const int32_t leaf = n >= 0 ? node_id[n] : -1;
-    path.clear();
-    for (int32_t q = leaf; q >= 0; q = o_parent[q]) path.push_back(q);
-    int32_t shared = 0;
-    for (size_t q = path.size(); q-- > 0;) {
-      const int32_t id = path[q];
-      page_ids.insert(page_ids.end(), o_pages.begin() + o_pstart[id], o_pages.begin() + o_pstart[id + 1]);
-      shared += o_pstart[id + 1] - o_pstart[id];
-    }
-    const int32_t npg = (kv + ps - 1) / ps;
-    for (int32_t q = shared; q < npg; ++q) page_ids.push_back((int32_t)next_page++);
-    row_start.push_back(row_start.back() + 1);
-    kv_len.push_back(kv); page_start.push_back((int32_t)page_ids.size()); seq_leaf.push_back(leaf); seq_req.push_back(ri);
-  }
-
-  bs_batch_owned *o = new (std::nothrow) bs_batch_owned();
-  if (!o) return fail(b, BS_ENOMEM, "out of memory");
-  std::memset(o, 0, sizeof *o);
-  auto dup = [](const std::vector<int32_t> &v) {
-    int32_t *p = new int32_t[v.size() ? v.size() : 1];
-    if (!v.empty()) std::memcpy(p, v.data(), v.size() * sizeof(int32_t));
-    return p;
-  };
-  o->batch.n_seq = n_pre + n_dec; o->batch.n_prefill = n_pre; o->batch.n_rows = row_start.back();
-  o->batch.row_start = dup(row_start); o->batch.kv_len = dup(kv_len); o->batch.page_start = dup(page_start);
-  o->batch.page_ids = dup(page_ids);
-  o->batch.n_nodes = (int32_t)o_parent.size();
-  o->batch.node_parent = dup(o_parent); o->batch.node_page_start = dup(o_pstart); o->batch.node_page_ids = dup(o_pages);
-  o->batch.node_seq_first = dup(o_first); o->batch.node_seq_count = dup(o_count); o->batch.seq_leaf_node = dup(seq_leaf);
-  o->seq_request = dup(seq_req);
-  o->n_pages = next_page;
-  o->info = info;
-  *out = o;
+  std::vector<Dec> dec_list;
+  for (int32_t pos : dec) dec_list.push_back({order[pos], b->reqs[order[pos]].n_cached});
+  int rc = emit(b, pre, dec_list, out);
+  if (rc) return rc;
+  (*out)->info = info;
   return BS_OK;
 }
 

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import builder as OB
-from paper_2411_16102_amd import binding
+from paper_2411_16102_amd import binding, workloads as W
 
 A100_8B = dict(p_model=8_030_000_000, kv_bytes=1024 * 32 * 4, compute=312e12, bandwidth=2.039e12)
 MI355_8B = dict(p_model=8_030_000_000, kv_bytes=1024 * 32 * 2 * 2, compute=2.5e15, bandwidth=8.0e12)
@@ -146,6 +146,35 @@ def test_split_matches_oracle(seed, t, budget):
     # a second call continues from the relocated tree, identically on both sides
     assert o.split(10**9) == b.split(10**9)
     assert_same_tree(o, b)
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_emit_of_an_explicit_step_matches_oracle(seed):
+    reqs = grouped_pool(seed, two_level=bool(seed % 2))
+    o, b = both(reqs, mem_bytes=int(2e9), hw=MI355_8B)
+    rng = np.random.default_rng(seed)
+    pick = [int(i) for i in rng.permutation(len(reqs))[:30]]
+    pre, dec = [], []
+    for r in pick:
+        p = len(reqs[r].tokens)
+        if rng.random() < 0.3:
+            cached = int(rng.integers(0, p))
+            pre.append((r, cached, int(rng.integers(1, p - cached + 1))))
+        else:
+            dec.append((r, p + int(rng.integers(0, 200))))
+    want, got = o.emit(pre, dec), b.emit(pre, dec)
+    assert set(want) == set(got)
+    for k in want:
+        assert np.array_equal(np.asarray(want[k]), np.asarray(got[k])), k
+    lay = binding.Layer(W.TINY, device=-1)
+    batch = W.Batch(page_size=16, **{k: got[k] for k in got if k != "seq_request"})
+    assert lay.validate(batch) == 0, lay.last_error()
+    with pytest.raises(binding.BlendStepError):
+        b.emit([(pick[0], 0, 10 ** 6)], [])          # chunk beyond the prompt
+    with pytest.raises(binding.BlendStepError):
+        b.emit([], [(pick[0], 0)])                    # decoding before the prompt is cached
+    with pytest.raises(binding.BlendStepError):
+        b.emit([(pick[0], 0, 1)], [(pick[0], 10 ** 4)])   # a request twice
 
 
 def test_split_before_finalize_is_an_error():
