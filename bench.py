@@ -41,6 +41,41 @@ def measured_traffic(profile_name, sources):
     return int(val.group(1))
 
 
+def pool_run(args, lib, W, note):
+    """The multi-step driver on a synthetic pool (8B-shaped layer): tokens served per second of
+    device time under each admission order."""
+    from paper_2411_16102_amd import engine as E
+    shape = W.LLAMA3_8B
+    budget = 2560
+    reqs = E.synthetic_pool(args.seed, n_groups=args.pool_groups, per_group=12, n_fresh=args.pool_fresh)
+    prompt = sum(len(r.tokens) for r in reqs)
+    outp = sum(r.d_true for r in reqs)
+    pages = args.pool_mem_tokens // 16 * 2 + 16384
+    stepper = E.GpuStepper(lib, shape, budget, pages, seed=args.seed)
+    kv_bytes = shape.kv_bytes_per_token
+    for policy in (["blend", "dfs", "random"] if args.pool == "all" else [args.pool]):
+        b = lib.Builder(8_030_000_000, kv_bytes * 32, PEAK_MFMA_BF16, PEAK_HBM, args.pool_mem_tokens * kv_bytes * 32, 16)
+        shared = None
+        eng = E.Engine(b, reqs, args.pool_mem_tokens, policy=policy, token_budget=budget, seed=args.seed,
+                       split_t=4096 if policy == "blend" else 0, split_budget=int(0.01 * prompt))
+        stepper.events = []
+        t0 = time.perf_counter()
+        st = eng.run(stepper, progress=lambda s_: note("%s: step %d, %d finished" % (policy, s_["steps"], s_["finished"])))
+        ms = stepper.total_ms()
+        wall = time.perf_counter() - t0
+        print(json.dumps({
+            "metric": "pool tokens/s per layer (prompt + output tokens over the device time of all steps)",
+            "value": (prompt + outp) / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "policy": policy,
+            "device_ms": ms, "wall_s": wall, "steps": st["steps"], "requests": len(reqs), "prompt_tokens": prompt,
+            "output_tokens": outp, "prefill_rows": st["prefill_rows"], "prompt_tokens_skipped": st["prompt_tokens_skipped"],
+            "decode_rows": st["decode_rows"], "mean_rows_per_step": st["rows"] / max(1, st["steps"]),
+            "peak_kv_tokens": st["peak_tokens"], "kv_capacity_tokens": args.pool_mem_tokens,
+            "split": eng.split_info, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "pool(seed=%d, groups=%d, fresh=%d)" % (args.seed, args.pool_groups, args.pool_fresh), "token_budget": budget,
+                       "d_model": shape.d_model, "d_ffn": shape.d_ffn}}), flush=True)
+        del shared
+
+
 def cpu_baseline(shape, batch, tens, target_flops=1.2e12):
     """The oracle, as it stands, on a bounded sample of the same batch: whole
     prefill segments and evenly spaced decode sequences in the batch's own
@@ -94,6 +129,12 @@ def main():
     ap.add_argument("--layers", type=int, default=1,
                     help="a step = this many layers back to back through bs_blend_layers (same weights and pool "
                          "for every layer: timing only); value stays per layer")
+    ap.add_argument("--pool", default="",
+                    help="instead of one workload: serve a synthetic request pool to completion with the multi-step "
+                         "driver, admission order blend | dfs | random | all (one JSON line each)")
+    ap.add_argument("--pool-mem-tokens", type=int, default=200_000, help="KV capacity of the pool run, in tokens")
+    ap.add_argument("--pool-groups", type=int, default=24, help="prefix groups of 12 requests (short, medium, long outputs in turn)")
+    ap.add_argument("--pool-fresh", type=int, default=1500, help="prompt-heavy requests without shared prefix")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (for scaling HBM traffic counters)")
     args = ap.parse_args()
@@ -111,6 +152,8 @@ def main():
         print("[bench] " + msg, file=sys.stderr, flush=True)
 
     lib = pkg.load()
+    if args.pool:
+        return pool_run(args, lib, W, note)
     note("generating inputs for " + args.workload)
     shape, make_batch = W.CONFIGS[args.workload]
     batch = make_batch(seed=args.seed)
