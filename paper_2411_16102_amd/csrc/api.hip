@@ -362,12 +362,12 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
       }
     }
   }
-  // prefill work: (sequence, block of 32 query rows), longest contexts first
+  // prefill work: (sequence, block of 64 query rows), longest contexts first
   c->pf_work.clear();
   std::vector<std::pair<int, std::pair<int, int>>> order;
   for (int s = 0; s < b->n_prefill; ++s) {
     const int q = b->row_start[s + 1] - b->row_start[s];
-    for (int k = 0; k * 32 < q; ++k) order.push_back({-(b->kv_len[s] - q + std::min(q, k * 32 + 32)), {s, k}});
+    for (int k = 0; k * 64 < q; ++k) order.push_back({-(b->kv_len[s] - q + std::min(q, k * 64 + 64)), {s, k}});
   }
   std::stable_sort(order.begin(), order.end(), [](const auto &x, const auto &y) { return x.first < y.first; });
   p.n_pf_work = (int)order.size();

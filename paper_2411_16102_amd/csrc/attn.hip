@@ -290,51 +290,60 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const MergeArgs a) {
 }
 
 // ------------------------------------------------------------------------------
-// prefill attention: one wavefront per (32 query rows, query head); the
+// prefill attention: one wavefront per (64 query rows, query head); the
 // wavefronts of a workgroup are the heads of one KV group and walk the same pages
 // ------------------------------------------------------------------------------
+// Two blocks of 32 query rows share every key and value fragment the wavefront loads
+// (the operands come straight from global memory, so the load path, not the matrix pipe,
+// bounds this kernel: twice the rows per load is twice the arithmetic per byte).
 template <int DH>
 __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, int heads_per_wg) {
   constexpr int KC = DH / 16;  // k-steps of the 32x32x16 score MFMA
   constexpr int DB = DH / 32;  // 32-row blocks of the output
+  constexpr int NQ = 2;        // blocks of 32 query rows per wavefront
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int hkv = a.s.n_kv_heads, hq = a.s.n_q_heads, grp = hq / hkv;
   const int wg_per_work = hq / heads_per_wg;
   const int w = blockIdx.x / wg_per_work;
-  const int seq = a.work[2 * w], qblk = a.work[2 * w + 1];
+  const int seq = a.work[2 * w], qblk = a.work[2 * w + 1];  // block of 64 query rows
   const int head = (blockIdx.x % wg_per_work) * heads_per_wg + wave;
   const int kvh = head / grp;
   const int r0 = a.row_start[seq], q_len = a.row_start[seq + 1] - r0;
   const int kv_len = a.kv_len[seq];
-  const int n_q = min(32, q_len - qblk * 32);
-  const int first_pos = kv_len - q_len + qblk * 32;
   const int lr = lane & 31, g2 = lane >> 5;
-  const int my_pos = min(first_pos + lr, kv_len - 1);
   const size_t tile = (size_t)16 * DH;
   const int32_t *pages = a.page_ids + a.page_start[seq];
   const int n_pg = (kv_len + 15) >> 4;
 
-  bf16x8_t qf[KC];
-  {
-    const bool ok = lr < n_q;
-    const uint16_t *p = a.q + (size_t)(r0 + qblk * 32 + (ok ? lr : 0)) * (hq * DH) + head * DH + 8 * g2;
+  int n_q[NQ], my_pos[NQ], last_tb[NQ];
+  bf16x8_t qf[NQ][KC];
+  f32x16_t o[NQ][DB];
+  float m[NQ], l[NQ];
+#pragma unroll
+  for (int qb = 0; qb < NQ; ++qb) {
+    const int row0 = qblk * 64 + qb * 32;
+    n_q[qb] = min(32, q_len - row0);                       // <= 0: the block does not exist
+    const int first_pos = kv_len - q_len + row0;
+    my_pos[qb] = min(first_pos + lr, kv_len - 1);
+    last_tb[qb] = n_q[qb] > 0 ? (first_pos + n_q[qb] - 1) / 32 : -1;  // last block of 32 tokens it attends to
+    const bool ok = lr < n_q[qb];
+    const uint16_t *p = a.q + (size_t)(r0 + (ok ? row0 + lr : 0)) * (hq * DH) + head * DH + 8 * g2;
 #pragma unroll
     for (int c = 0; c < KC; ++c) {
       u32x4_t v = {0u, 0u, 0u, 0u};
       if (ok) v = ld16(p + 16 * c);
-      qf[c] = as_bf16x8(v);
+      qf[qb][c] = as_bf16x8(v);
     }
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
+    m[qb] = NEG_BIG;
+    l[qb] = 0.f;
   }
-  f32x16_t o[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-  float m = NEG_BIG, l = 0.f;
 
-  const int last_tok = first_pos + n_q - 1;
-  const int n_tb = last_tok / 32 + 1;
+  const int n_tb = max(last_tb[0], last_tb[1]) + 1;
   // Software pipeline: the keys of block tb+1 and the values of block tb are requested
   // before the score MFMAs of block tb are issued, so both loads have a whole block of
   // arithmetic to arrive.  A step past the end re-reads the last block (never used).
@@ -354,72 +363,73 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
   auto block = [&](int tb, const u32x4_t (&kf)[KC]) {
     size_t p0, p1;
     page_pair(tb, p0, p1);
-    u32x2_t va[DB][4];  // values of the block: [32-row block of dh][8-token group]
+    u32x4_t va[DB][2];  // values of the block, masked where ragged: [32-row block of dh][16-token half]
+    {
+      const bool ragged = tb * 32 + 32 > kv_len;
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      const uint16_t *v0 = a.kv_pool + ((p0 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
-      const uint16_t *v1 = a.kv_pool + ((p1 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
-      va[db][0] = ld8(v0);
-      va[db][1] = ld8(v0 + 8);
-      va[db][2] = ld8(v1);
-      va[db][3] = ld8(v1 + 8);
-    }
-    f32x16_t s;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-    for (int c = 0; c < KC; ++c)
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[c]), qf[c], s, 0, 0, 0);
-    // element r: token tb*32 + 8*(r/4) + 4*g2 + r%4 against the query at my_pos
-    float mx = NEG_BIG;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int t = tb * 32 + 8 * (r >> 2) + 4 * g2 + (r & 3);
-      s[r] = (t <= my_pos) ? s[r] * a.s.scale_log2e : NEG_BIG;
-      mx = fmaxf(mx, s[r]);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    // lazy reference exponent, as in the decode kernel: rescale only when somebody's maximum
-    // has grown by more than 2^TAU
-    if (__builtin_amdgcn_ballot_w64(mx > m + TAU) != 0) {
-      const float m_new = fmaxf(m, mx);
-      const float alpha = fast_exp2(m - m_new);
-      m = m_new;
-      l *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db) o[db] *= alpha;
-    }
-    float ps = 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      s[r] = fast_exp2(s[r] - m);
-      ps += s[r];
-    }
-    l += ps;
-    u32x4_t pw0, pw1;
-    pw0.x = pack_bf16x2(s[0], s[1]);
-    pw0.y = pack_bf16x2(s[2], s[3]);
-    pw0.z = pack_bf16x2(s[4], s[5]);
-    pw0.w = pack_bf16x2(s[6], s[7]);
-    pw1.x = pack_bf16x2(s[8], s[9]);
-    pw1.y = pack_bf16x2(s[10], s[11]);
-    pw1.z = pack_bf16x2(s[12], s[13]);
-    pw1.w = pack_bf16x2(s[14], s[15]);
-    const bool ragged = tb * 32 + 32 > kv_len;
-#pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      u32x2_t a0 = va[db][0], a1 = va[db][1], b0 = va[db][2], b1 = va[db][3];
-      if (ragged) {
-        a0 = mask_tokens(a0, tb * 32 + 4 * g2, kv_len);
-        a1 = mask_tokens(a1, tb * 32 + 8 + 4 * g2, kv_len);
-        b0 = mask_tokens(b0, tb * 32 + 16 + 4 * g2, kv_len);
-        b1 = mask_tokens(b1, tb * 32 + 24 + 4 * g2, kv_len);
+      for (int db = 0; db < DB; ++db) {
+        const uint16_t *v0 = a.kv_pool + ((p0 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
+        const uint16_t *v1 = a.kv_pool + ((p1 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
+        u32x2_t a0 = ld8(v0), a1 = ld8(v0 + 8), b0 = ld8(v1), b1 = ld8(v1 + 8);
+        if (ragged) {
+          a0 = mask_tokens(a0, tb * 32 + 4 * g2, kv_len);
+          a1 = mask_tokens(a1, tb * 32 + 8 + 4 * g2, kv_len);
+          b0 = mask_tokens(b0, tb * 32 + 16 + 4 * g2, kv_len);
+          b1 = mask_tokens(b1, tb * 32 + 24 + 4 * g2, kv_len);
+        }
+        va[db][0] = u32x4_t{a0.x, a0.y, a1.x, a1.y};
+        va[db][1] = u32x4_t{b0.x, b0.y, b1.x, b1.y};
       }
-      u32x4_t xa, xb;
-      xa.x = a0.x; xa.y = a0.y; xa.z = a1.x; xa.w = a1.y;
-      xb.x = b0.x; xb.y = b0.y; xb.z = b1.x; xb.w = b1.y;
-      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(xa), as_bf16x8(pw0), o[db], 0, 0, 0);
-      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(xb), as_bf16x8(pw1), o[db], 0, 0, 0);
+    }
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+      if (tb > last_tb[qb]) continue;  // wave-uniform: these tokens lie after every query of the block
+      f32x16_t s;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+      for (int c = 0; c < KC; ++c)
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[c]), qf[qb][c], s, 0, 0, 0);
+      // element r: token tb*32 + 8*(r/4) + 4*g2 + r%4 against the query at my_pos
+      float mx = NEG_BIG;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int t = tb * 32 + 8 * (r >> 2) + 4 * g2 + (r & 3);
+        s[r] = (t <= my_pos[qb]) ? s[r] * a.s.scale_log2e : NEG_BIG;
+        mx = fmaxf(mx, s[r]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      // lazy reference exponent, as in the decode kernel: rescale only when somebody's maximum
+      // has grown by more than 2^TAU
+      if (__builtin_amdgcn_ballot_w64(mx > m[qb] + TAU) != 0) {
+        const float m_new = fmaxf(m[qb], mx);
+        const float alpha = fast_exp2(m[qb] - m_new);
+        m[qb] = m_new;
+        l[qb] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) o[qb][db] *= alpha;
+      }
+      float ps = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        s[r] = fast_exp2(s[r] - m[qb]);
+        ps += s[r];
+      }
+      l[qb] += ps;
+      u32x4_t pw0, pw1;
+      pw0.x = pack_bf16x2(s[0], s[1]);
+      pw0.y = pack_bf16x2(s[2], s[3]);
+      pw0.z = pack_bf16x2(s[4], s[5]);
+      pw0.w = pack_bf16x2(s[6], s[7]);
+      pw1.x = pack_bf16x2(s[8], s[9]);
+      pw1.y = pack_bf16x2(s[10], s[11]);
+      pw1.z = pack_bf16x2(s[12], s[13]);
+      pw1.w = pack_bf16x2(s[14], s[15]);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[db][0]), as_bf16x8(pw0), o[qb][db], 0, 0, 0);
+        o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[db][1]), as_bf16x8(pw1), o[qb][db], 0, 0, 0);
+      }
     }
   };
   u32x4_t ka[KC], kb[KC];
@@ -432,19 +442,23 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
       block(tb + 1, kb);
     }
   }
-  l += __shfl_xor(l, 32, 64);
-  if (lr < n_q) {
-    const float inv = 1.f / l;
-    uint16_t *dst = a.out + (size_t)(r0 + qblk * 32 + lr) * (hq * DH) + head * DH;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+  for (int qb = 0; qb < NQ; ++qb) {
+    float ls = l[qb];
+    ls += __shfl_xor(ls, 32, 64);
+    if (lr < n_q[qb]) {
+      const float inv = 1.f / ls;
+      uint16_t *dst = a.out + (size_t)(r0 + qblk * 64 + qb * 32 + lr) * (hq * DH) + head * DH;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        u32x2_t v;
-        v.x = pack_bf16x2(o[db][4 * q + 0] * inv, o[db][4 * q + 1] * inv);
-        v.y = pack_bf16x2(o[db][4 * q + 2] * inv, o[db][4 * q + 3] * inv);
-        *reinterpret_cast<u32x2_t *>(dst + 32 * db + 8 * q + 4 * g2) = v;
-      }
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          u32x2_t v;
+          v.x = pack_bf16x2(o[qb][db][4 * q + 0] * inv, o[qb][db][4 * q + 1] * inv);
+          v.y = pack_bf16x2(o[qb][db][4 * q + 2] * inv, o[qb][db][4 * q + 3] * inv);
+          *reinterpret_cast<u32x2_t *>(dst + 32 * db + 8 * q + 4 * g2) = v;
+        }
+    }
   }
 }
 

@@ -50,7 +50,7 @@ hipError_t launch_decode_merge(const MergeArgs &a, hipStream_t stream);
 
 struct PrefillArgs {
   AttnShape s;
-  const int32_t *work;  // [n_work][2] = (sequence, block of 32 query rows)
+  const int32_t *work;  // [n_work][2] = (sequence, block of 64 query rows)
   int n_work;
   const int32_t *row_start, *kv_len, *page_start, *page_ids;
   const uint16_t *q;
