@@ -19,6 +19,8 @@
 // dimension; every (node chunk | private tail chunk) leaves a partial softmax
 // state (m, l, acc) per query row and head, and a second kernel merges a
 // sequence's states along its root-to-leaf path.
+#include <type_traits>
+
 #include "attn.hpp"
 #include "common.hpp"
 
@@ -289,13 +291,39 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const MergeArgs a) {
   for (int e = 0; e < E; ++e) dst[e] = f32_to_bf16(acc[e] * inv);
 }
 
+// acc *= alpha for an MFMA accumulator that lives in the accumulation registers.  Written out
+// by hand so that the only vector-ALU use of the output accumulators inside the block loop
+// is this rarely taken path: left to the compiler, the register copies it needs are hoisted
+// to the top of every iteration.  The trailing wait states separate the last register write
+// from a following MFMA that reads it.
+__device__ __forceinline__ void scale_acc(f32x16_t &acc, float alpha) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float e = acc[r], t;
+    asm(  // not volatile: the compiler must see that it touches no memory
+        "v_accvgpr_read_b32 %1, %0\n\t"
+        "v_mul_f32 %1, %1, %2\n\t"
+        "v_accvgpr_write_b32 %0, %1\n\t"
+        "s_nop 3"
+        : "+a"(e), "=&v"(t)
+        : "v"(alpha));
+    acc[r] = e;
+  }
+}
+
 // ------------------------------------------------------------------------------
 // prefill attention: one wavefront per (64 query rows, query head); the
 // wavefronts of a workgroup are the heads of one KV group and walk the same pages
 // ------------------------------------------------------------------------------
-// Two blocks of 32 query rows share every key and value fragment the wavefront loads
-// (the operands come straight from global memory, so the load path, not the matrix pipe,
-// bounds this kernel: twice the rows per load is twice the arithmetic per byte).
+// Two blocks of 32 query rows share every key and value fragment the wavefront loads: the
+// operands come straight from global memory (a lane's key fragment is 16 bytes of a
+// 256-byte row, so a load instruction touches 32 cache lines), and twice the rows per load
+// is half the L1 accesses per MFMA.  The accumulators of 64 rows x dh 128 leave room for
+// one wavefront per SIMD only, so vector-ALU and matrix work of a block overlap only as far
+// as the instruction order below lets them.  A variant that stages keys and values in LDS
+// for eight wavefronts of 32 rows (one workgroup-wide load per block, one barrier per block)
+// was measured slower: its wavefronts move in lockstep and the LDS, matrix and
+// vector-ALU phases of a block add up instead of overlapping.
 template <int DH>
 __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, int heads_per_wg) {
   constexpr int KC = DH / 16;  // k-steps of the 32x32x16 score MFMA
@@ -315,8 +343,9 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
   const size_t tile = (size_t)16 * DH;
   const int32_t *pages = a.page_ids + a.page_start[seq];
   const int n_pg = (kv_len + 15) >> 4;
+  const uint32_t v_off = lr * 16 + 4 * g2;  // this lane's element within a value tile [dh][16 tokens]
 
-  int n_q[NQ], my_pos[NQ], last_tb[NQ];
+  int n_q[NQ], my_pos[NQ], last_tb[NQ], first_pos[NQ];
   bf16x8_t qf[NQ][KC];
   f32x16_t o[NQ][DB];
   float m[NQ], l[NQ];
@@ -324,9 +353,9 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
   for (int qb = 0; qb < NQ; ++qb) {
     const int row0 = qblk * 64 + qb * 32;
     n_q[qb] = min(32, q_len - row0);                       // <= 0: the block does not exist
-    const int first_pos = kv_len - q_len + row0;
-    my_pos[qb] = min(first_pos + lr, kv_len - 1);
-    last_tb[qb] = n_q[qb] > 0 ? (first_pos + n_q[qb] - 1) / 32 : -1;  // last block of 32 tokens it attends to
+    first_pos[qb] = kv_len - q_len + row0;
+    my_pos[qb] = min(first_pos[qb] + lr, kv_len - 1);
+    last_tb[qb] = n_q[qb] > 0 ? (first_pos[qb] + n_q[qb] - 1) / 32 : -1;  // last block of 32 tokens it attends to
     const bool ok = lr < n_q[qb];
     const uint16_t *p = a.q + (size_t)(r0 + (ok ? row0 + lr : 0)) * (hq * DH) + head * DH + 8 * g2;
 #pragma unroll
@@ -344,60 +373,79 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
   }
 
   const int n_tb = max(last_tb[0], last_tb[1]) + 1;
-  // Software pipeline: the keys of block tb+1 and the values of block tb are requested
-  // before the score MFMAs of block tb are issued, so both loads have a whole block of
-  // arithmetic to arrive.  A step past the end re-reads the last block (never used).
-  auto page_pair = [&](int tb, size_t &p0, size_t &p1) {
+  // Software pipeline, one block of 32 tokens deep: while block tb is computed, the values of
+  // block tb+1 travel into the second value buffer, its keys into the key registers (as soon
+  // as the score MFMAs of block tb have read them) and the page ids of block tb+2 into scalar
+  // registers.  Steps past the end re-read the last block (never used).
+  struct PagePair { int p0, p1; };
+  auto page_pair = [&](int tb) __attribute__((always_inline)) {
     const int t = tb < n_tb ? tb : n_tb - 1;
-    p0 = pages[2 * t];
-    p1 = (2 * t + 1 < n_pg) ? pages[2 * t + 1] : p0;
+    PagePair pp;
+    pp.p0 = pages[2 * t];
+    pp.p1 = (2 * t + 1 < n_pg) ? pages[2 * t + 1] : pp.p0;
+    return pp;
   };
-  auto load_k = [&](int tb, u32x4_t (&kf)[KC]) {
-    size_t p0, p1;
-    page_pair(tb, p0, p1);
-    const size_t pk = (lr < 16) ? p0 : p1;
+  auto load_k = [&](PagePair pp, u32x4_t (&kf)[KC]) __attribute__((always_inline)) {
+    const size_t pk = (lr < 16) ? pp.p0 : pp.p1;
     const uint16_t *kp = a.kv_pool + ((pk * 2 + 0) * hkv + kvh) * tile + (lr & 15) * DH + 8 * g2;
 #pragma unroll
     for (int c = 0; c < KC; ++c) kf[c] = ld16(kp + 16 * c);
   };
-  auto block = [&](int tb, const u32x4_t (&kf)[KC]) {
-    size_t p0, p1;
-    page_pair(tb, p0, p1);
-    u32x4_t va[DB][2];  // values of the block, masked where ragged: [32-row block of dh][16-token half]
-    {
-      const bool ragged = tb * 32 + 32 > kv_len;
+  // values of a block as loaded: [32-row block of dh][16-token half of the block][8 tokens]
+  auto load_v = [&](PagePair pp, u32x2_t (&r)[DB][4]) __attribute__((always_inline)) {
+    const uint16_t *v0 = a.kv_pool + (((size_t)pp.p0 * 2 + 1) * hkv + kvh) * tile;  // wave-uniform bases,
+    const uint16_t *v1 = a.kv_pool + (((size_t)pp.p1 * 2 + 1) * hkv + kvh) * tile;  // lane offset v_off
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const uint16_t *v0 = a.kv_pool + ((p0 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
-        const uint16_t *v1 = a.kv_pool + ((p1 * 2 + 1) * hkv + kvh) * tile + (32 * db + lr) * 16 + 4 * g2;
-        u32x2_t a0 = ld8(v0), a1 = ld8(v0 + 8), b0 = ld8(v1), b1 = ld8(v1 + 8);
-        if (ragged) {
-          a0 = mask_tokens(a0, tb * 32 + 4 * g2, kv_len);
-          a1 = mask_tokens(a1, tb * 32 + 8 + 4 * g2, kv_len);
-          b0 = mask_tokens(b0, tb * 32 + 16 + 4 * g2, kv_len);
-          b1 = mask_tokens(b1, tb * 32 + 24 + 4 * g2, kv_len);
-        }
-        va[db][0] = u32x4_t{a0.x, a0.y, a1.x, a1.y};
-        va[db][1] = u32x4_t{b0.x, b0.y, b1.x, b1.y};
-      }
+    for (int db = 0; db < DB; ++db) {
+      r[db][0] = ld8(v0 + v_off + 512 * db);
+      r[db][1] = ld8(v0 + v_off + 512 * db + 8);
+      r[db][2] = ld8(v1 + v_off + 512 * db);
+      r[db][3] = ld8(v1 + v_off + 512 * db + 8);
     }
+  };
+  // block tb: keys in kf and values in vr have been requested; `next` holds the pages of block tb+1
+  auto block = [&](int tb, u32x4_t (&kf)[KC], u32x2_t (&vr)[DB][4], u32x2_t (&vn)[DB][4], PagePair &next, auto two) __attribute__((always_inline)) {
+    const PagePair after = page_pair(tb + 2);
+    load_v(next, vn);
+    if (tb * 32 + 32 > kv_len) {  // wave-uniform: the block runs past the context
 #pragma unroll
-    for (int qb = 0; qb < NQ; ++qb) {
-      if (tb > last_tb[qb]) continue;  // wave-uniform: these tokens lie after every query of the block
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int h = 0; h < 4; ++h) vr[db][h] = mask_tokens(vr[db][h], tb * 32 + 8 * h + 4 * g2, kv_len);
+    }
+    u32x4_t va[DB][2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      va[db][0] = u32x4_t{vr[db][0].x, vr[db][0].y, vr[db][1].x, vr[db][1].y};
+      va[db][1] = u32x4_t{vr[db][2].x, vr[db][2].y, vr[db][3].x, vr[db][3].y};
+    }
+    // Order of issue: both score products, then softmax of the first query block (its VALU
+    // work runs while the matrix pipe is still busy with the second product), its PV product,
+    // softmax of the second block under that product, and the second PV product.
+    auto scores = [&](int qb) {
       f32x16_t s;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
       for (int c = 0; c < KC; ++c)
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[c]), qf[qb][c], s, 0, 0, 0);
-      // element r: token tb*32 + 8*(r/4) + 4*g2 + r%4 against the query at my_pos
-      float mx = NEG_BIG;
+      return s;
+    };
+    // element r of s: token tb*32 + 8*(r/4) + 4*g2 + r%4 against the query at my_pos
+    // softmax of one query block in two parts.  `prepare` (mask, running maximum, the rare
+    // rescale) branches; `weights` (exponentials, row sums, bf16 packing) does not, so that
+    // the scheduler may slide it under the MFMAs of the other query block.
+    auto prepare = [&](f32x16_t &s, int qb) __attribute__((always_inline)) {
+      if (tb * 32 + 31 > first_pos[qb]) {  // wave-uniform: the block holds tokens some query must not see
+        const int lim = my_pos[qb] - tb * 32 - 4 * g2;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int t = tb * 32 + 8 * (r >> 2) + 4 * g2 + (r & 3);
-        s[r] = (t <= my_pos[qb]) ? s[r] * a.s.scale_log2e : NEG_BIG;
-        mx = fmaxf(mx, s[r]);
+        for (int r = 0; r < 16; ++r)
+          if (8 * (r >> 2) + (r & 3) > lim) s[r] = NEG_BIG;
       }
+      float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+      for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
+      mx *= a.s.scale_log2e;  // the scale is positive: the maximum commutes with it
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       // lazy reference exponent, as in the decode kernel: rescale only when somebody's maximum
       // has grown by more than 2^TAU
@@ -407,16 +455,18 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
         m[qb] = m_new;
         l[qb] *= alpha;
 #pragma unroll
-        for (int db = 0; db < DB; ++db) o[qb][db] *= alpha;
+        for (int db = 0; db < DB; ++db) scale_acc(o[qb][db], alpha);
       }
+    };
+    auto weights = [&](f32x16_t &s, int qb, u32x4_t &pw0, u32x4_t &pw1) __attribute__((always_inline)) {
+      const float neg_m = -m[qb];
       float ps = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        s[r] = fast_exp2(s[r] - m[qb]);
+        s[r] = fast_exp2(__builtin_fmaf(s[r], a.s.scale_log2e, neg_m));
         ps += s[r];
       }
       l[qb] += ps;
-      u32x4_t pw0, pw1;
       pw0.x = pack_bf16x2(s[0], s[1]);
       pw0.y = pack_bf16x2(s[2], s[3]);
       pw0.z = pack_bf16x2(s[4], s[5]);
@@ -425,23 +475,62 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
       pw1.y = pack_bf16x2(s[10], s[11]);
       pw1.z = pack_bf16x2(s[12], s[13]);
       pw1.w = pack_bf16x2(s[14], s[15]);
+    };
+    auto pv = [&](int qb, const u32x4_t &pw0, const u32x4_t &pw1) __attribute__((always_inline)) {
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[db][0]), as_bf16x8(pw0), o[qb][db], 0, 0, 0);
         o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[db][1]), as_bf16x8(pw1), o[qb][db], 0, 0, 0);
       }
+    };
+    u32x4_t pa0, pa1, pb0, pb1;
+    if constexpr (decltype(two)::value) {  // the second query block exists
+      // (past the first block's last position its scores are all masked and add nothing)
+      f32x16_t s0 = scores(0);
+      f32x16_t s1 = scores(1);
+      load_k(next, kf);
+      prepare(s0, 0);
+      prepare(s1, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      weights(s0, 0, pa0, pa1);
+      __builtin_amdgcn_sched_barrier(0);
+      // the first PV product, one MFMA at a time, with the second block's weights in between
+      pv(0, pa0, pa1);
+      weights(s1, 1, pb0, pb1);
+#pragma unroll
+      for (int i = 0; i < 2 * DB; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x002, 56 / (2 * DB), 0);  // its share of the VALU work
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      pv(1, pb0, pb1);
+    } else {
+      f32x16_t s0 = scores(0);
+      load_k(next, kf);
+      prepare(s0, 0);
+      weights(s0, 0, pa0, pa1);
+      pv(0, pa0, pa1);
+    }
+    next = after;
+  };
+  u32x4_t kf[KC];
+  u32x2_t v_a[DB][4], v_b[DB][4];
+  {
+    const PagePair first = page_pair(0);
+    load_k(first, kf);
+    load_v(first, v_a);
+  }
+  PagePair next = page_pair(1);
+  auto run = [&](auto two) __attribute__((always_inline)) {
+    for (int tb = 0; tb < n_tb; tb += 2) {
+      block(tb, kf, v_a, v_b, next, two);
+      if (tb + 1 < n_tb) block(tb + 1, kf, v_b, v_a, next, two);
     }
   };
-  u32x4_t ka[KC], kb[KC];
-  load_k(0, ka);
-  for (int tb = 0; tb < n_tb; tb += 2) {
-    load_k(tb + 1, kb);
-    block(tb, ka);
-    if (tb + 1 < n_tb) {
-      load_k(tb + 2, ka);
-      block(tb + 1, kb);
-    }
-  }
+  if (n_q[1] > 0)  // wave-uniform: the second block of query rows exists
+    run(std::true_type{});
+  else
+    run(std::false_type{});
 #pragma unroll
   for (int qb = 0; qb < NQ; ++qb) {
     float ls = l[qb];
