@@ -41,6 +41,31 @@ const char *bs_builder_last_error(const bs_builder *b);
  * Returns the request's index (>= 0) or a negative bs_status. */
 int bs_builder_add(bs_builder *b, const int32_t *tokens, int32_t n_tokens, int32_t d_est, int32_t n_cached);
 
+/* Memory model behind B, before bs_builder_finalize.
+ *   BS_MEM_EXPANDED (default): Section 4.1's Mem(r) summed over requests; a cached prefix
+ *     is charged to every request that holds it (Section 3.3: a prefix-cache hit saves
+ *     no bandwidth).
+ *   BS_MEM_SHARED: an extension for a decode kernel that reads the pages of a shared
+ *     segment once per step (Appendix A.2): loaded tokens of the subtree when all its
+ *     requests decode together, each segment charged once per step while any request
+ *     below it still decodes,
+ *       S(leaf) = 2 own d + d^2, S(N) = 2 len(N) max_d(N) + sum S(child),
+ *       B(R) = S(R) + 2 start(R) max_d(R);
+ *     equal to the default wherever nothing is shared.  bs_builder_split is defined for
+ *     the default only (it reasons with sums over leaves) and fails otherwise. */
+enum { BS_MEM_EXPANDED = 0, BS_MEM_SHARED = 1 };
+int bs_builder_set_mem_model(bs_builder *b, int mem_model);
+
+/* kv_bytes of bs_cost_model ("H_kv * L * 2 * 2" of Section 4.1) for the attention
+ * variants of Section 7: bytes of cached state per token over all layers.  MHA: keys and
+ * values of n_heads heads; MQA: of one head; GQA: of n_kv_heads heads (must divide
+ * n_heads); MLA: one latent of latent_dim plus a shared rotary key of rope_dim per
+ * layer.  Arguments a variant does not use are ignored.  Returns a negative bs_status
+ * on invalid arguments.  Host only. */
+enum { BS_ATTN_MHA = 0, BS_ATTN_MQA = 1, BS_ATTN_GQA = 2, BS_ATTN_MLA = 3 };
+int64_t bs_kv_bytes_per_token(int variant, int32_t n_layers, int32_t n_heads, int32_t head_dim, int32_t n_kv_heads,
+                              int32_t latent_dim, int32_t rope_dim, int32_t elem_bytes);
+
 /* Build the compressed trie over all prompts (every request a leaf, every internal
  * node a maximal shared segment), annotate every node with
  *   A = distinct prompt tokens of its subtree with the root path counted once + sum d_i

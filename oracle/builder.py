@@ -66,6 +66,21 @@ exact integer / rational arithmetic where a decision depends on a comparison.
           recomputed and Algorithm 1 runs again.
      Every leaf is split at most once, so there are at most N_leaf rounds.
 
+  7. Memory model with prefix pages read once (an extension: Section 3.3 charges the
+     cached prefix of every request at full bytes because a prefix-cache hit saves no
+     bandwidth; with the intra-batch prefix sharing of Appendix A.2 the pages of a shared
+     segment are read once per step for all requests below it).  `mem_model="shared"`
+     replaces B(R) by the loaded-token count of the subtree when all its requests decode
+     together, each segment charged once per step while any request below it still
+     decodes:
+        S(leaf) = 2 own d + d^2,           D(leaf) = d,
+        S(N)    = 2 len(N) D(N) + sum_c S(c),   D(N) = max_c D(c),
+        B(R)    = S(R) + 2 start(R) D(R)        (the path above R, shared by all of R),
+     which equals the paper's B wherever nothing is shared.  A is unchanged.  Node
+     splitting (step 6) reasons with sums over leaves and is defined for the paper's
+     model only.  The other attention variants of Section 7 (MHA, MQA, GQA, MLA) enter
+     through kappa alone: `kv_bytes_per_token`.
+
 Pins (tests/test_oracle_builder.py): the memory-partition example printed with
 Figure 6; the batch-density = request-density identity of Section 4.2; linearity of
 the memory model in loaded tokens (the ratios of Table 1); brute-force shared-prefix
@@ -88,6 +103,30 @@ from typing import List, Optional, Sequence, Tuple
 import numpy as np
 
 
+def kv_bytes_per_token(variant: str, n_layers: int, n_heads: int, head_dim: int, n_kv_heads: int = 0,
+                       latent_dim: int = 0, rope_dim: int = 0, elem_bytes: int = 2) -> int:
+    """kappa of Section 4.1 ("H_kv * L * 2 * 2": keys and values of every KV head, every
+    layer, 2 bytes each) for the attention variants named in Section 7.  MHA keeps one KV
+    head per query head, MQA one in all, GQA n_kv_heads; MLA caches one compressed latent
+    of latent_dim plus a shared rotary key of rope_dim per token and layer instead of
+    per-head keys and values."""
+    if variant == "mha":
+        per_layer = 2 * n_heads * head_dim
+    elif variant == "mqa":
+        per_layer = 2 * head_dim
+    elif variant == "gqa":
+        if n_kv_heads <= 0 or n_heads % n_kv_heads:
+            raise ValueError("gqa needs n_kv_heads dividing n_heads")
+        per_layer = 2 * n_kv_heads * head_dim
+    elif variant == "mla":
+        if latent_dim <= 0:
+            raise ValueError("mla needs latent_dim")
+        per_layer = latent_dim + rope_dim
+    else:
+        raise ValueError("unknown attention variant " + variant)
+    return per_layer * n_layers * elem_bytes
+
+
 @dataclass
 class CostModel:
     p_model: int          # model parameters
@@ -96,6 +135,7 @@ class CostModel:
     bandwidth: float      # bytes/s
     mem_bytes: int        # M: KV-cache capacity in bytes
     page_size: int = 16
+    mem_model: str = "expanded"   # "expanded": Section 4.1's Mem(r) summed; "shared": step 7 above
 
 
 @dataclass
@@ -118,6 +158,8 @@ class TNode:
     sum_p: int = 0
     sum_d: int = 0
     min_req: int = 0
+    S: int = 0                      # "shared" memory model: loaded tokens (x2) at or below the node's segment
+    max_d: int = 0                  # longest output below the node
     lo: Tuple[int, int] = (0, 1)    # (A, B) of the least / most compute-intensive leaf below
     hi: Tuple[int, int] = (0, 1)
 
@@ -217,6 +259,8 @@ class BuilderOracle:
     def split(self, t: int, budget: int = -1):
         """Relocate outlier leaves whose shared prefix is at most t tokens, spending at most
         `budget` recomputed tokens in total (< 0: no limit)."""
+        if self.cm.mem_model != "expanded":
+            raise ValueError("node splitting is defined for the paper's memory model only")
         spent = rounds = n_split = 0
         while True:
             keys = self.leaf_keys()
@@ -319,11 +363,12 @@ class BuilderOracle:
             nd.n_req, nd.sum_p, nd.sum_d, nd.min_req = 1, p, d, nd.req
             own = nd.end - nd.start
             nd.B = 2 * p * d + d * d
+            nd.S, nd.max_d = 2 * own * d + d * d, d
             below = own + d                       # distinct tokens strictly below the node's start
             nd.lo = nd.hi = (nd.start + below, nd.B)
         else:
             below = nd.end - nd.start
-            nd.n_req = nd.sum_p = nd.sum_d = nd.B = 0
+            nd.n_req = nd.sum_p = nd.sum_d = nd.B = nd.S = nd.max_d = 0
             nd.min_req = 1 << 62
             for k, c in enumerate(nd.children):
                 self._annotate(c)
@@ -334,8 +379,13 @@ class BuilderOracle:
                 nd.sum_p += ch.sum_p
                 nd.sum_d += ch.sum_d
                 nd.B += ch.B
+                nd.S += ch.S
+                nd.max_d = max(nd.max_d, ch.max_d)
                 nd.min_req = min(nd.min_req, ch.min_req)
                 below += ch.A - ch.start          # the child's A counts its root path once: remove it
+            nd.S += 2 * (nd.end - nd.start) * nd.max_d
+            if self.cm.mem_model == "shared":
+                nd.B = nd.S + 2 * nd.start * nd.max_d
         nd.A = nd.start + below                   # the path root -> node counted once
         return nd
 

@@ -125,6 +125,9 @@ def raw():
         lib.bs_builder_last_error.restype = C.c_char_p
         lib.bs_builder_add.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_int32, C.c_int32]
         lib.bs_builder_finalize.argtypes = [C.c_void_p]
+        lib.bs_builder_set_mem_model.argtypes = [C.c_void_p, C.c_int]
+        lib.bs_kv_bytes_per_token.argtypes = [C.c_int] + [C.c_int32] * 7
+        lib.bs_kv_bytes_per_token.restype = C.c_int64
         lib.bs_builder_split.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.POINTER(SplitInfo)]
         lib.bs_builder_tree_size.argtypes = [C.c_void_p, _i32p, _i32p]
         lib.bs_builder_tree.argtypes = [C.c_void_p] + [_i32p] * 6 + [_i64p, _i64p, _i32p]
@@ -369,6 +372,14 @@ class Builder:
     def finalize(self):
         self._check(self.lib.bs_builder_finalize(self.h))
 
+    MEM_MODELS = {"expanded": 0, "shared": 1}
+
+    def set_mem_model(self, name):
+        """Memory model behind B ("expanded" or "shared"); before finalize()."""
+        if name not in self.MEM_MODELS:
+            raise ValueError("unknown memory model " + str(name))
+        self._check(self.lib.bs_builder_set_mem_model(self.h, self.MEM_MODELS[name]))
+
     def split(self, t, budget_tokens=-1):
         """Conditional node splitting; returns what bs_split_info reports."""
         info = SplitInfo()
@@ -439,3 +450,17 @@ class _Api:
 def load():
     raw()
     return _Api
+
+
+ATTN_VARIANTS = {"mha": 0, "mqa": 1, "gqa": 2, "mla": 3}
+
+
+def kv_bytes_per_token(variant, n_layers, n_heads=0, head_dim=0, n_kv_heads=0, latent_dim=0, rope_dim=0, elem_bytes=2):
+    """bs_kv_bytes_per_token: the cost model's kv_bytes for an attention variant."""
+    if variant not in ATTN_VARIANTS:
+        raise ValueError("unknown attention variant " + str(variant))
+    v = raw().bs_kv_bytes_per_token(ATTN_VARIANTS[variant], n_layers, n_heads, head_dim, n_kv_heads, latent_dim,
+                                    rope_dim, elem_bytes)
+    if v < 0:
+        raise BlendStepError(int(v), "bs_kv_bytes_per_token: invalid arguments")
+    return int(v)

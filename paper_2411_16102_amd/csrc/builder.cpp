@@ -52,6 +52,7 @@ struct bs_builder {
   std::vector<int32_t> leaf_order;
   std::vector<int32_t> leaf_node;   // request -> node
   std::vector<char> detached;       // request was re-inserted under the root by node splitting
+  int mem_model = BS_MEM_EXPANDED;
   bool finalized = false;
 };
 
@@ -143,6 +144,7 @@ struct Grower {
 struct Tmp {  // unsorted finished tree
   int32_t parent, start, end, req;
   int64_t A = 0, B = 0, n_req = 0, sum_p = 0, sum_d = 0;
+  int64_t S = 0, max_d = 0;  // prefix-pages-read-once memory model: loaded tokens (x2) at or below the segment; longest output below
   int64_t lo_a = 0, lo_b = 1, hi_a = 0, hi_b = 1;
   int32_t min_req = 0;
   std::vector<int32_t> kids;
@@ -195,6 +197,7 @@ void rebuild(bs_builder *b) {
       const int64_t p = (int64_t)r.tok.size(), d = r.d_est;
       n.n_req = 1; n.sum_p = p; n.sum_d = d; n.min_req = n.req;
       n.B = 2 * p * d + d * d;
+      n.S = 2 * (int64_t)(n.end - n.start) * d + d * d; n.max_d = d;
       below = (n.end - n.start) + d;
       n.lo_a = n.hi_a = n.start + below; n.lo_b = n.hi_b = n.B;
     } else {
@@ -207,9 +210,13 @@ void rebuild(bs_builder *b) {
         if (first || cmp_density(ch.hi_a, ch.hi_b, n.hi_a, n.hi_b) > 0) { n.hi_a = ch.hi_a; n.hi_b = ch.hi_b; }
         first = false;
         n.n_req += ch.n_req; n.sum_p += ch.sum_p; n.sum_d += ch.sum_d; n.B += ch.B;
+        n.S += ch.S; n.max_d = std::max(n.max_d, ch.max_d);
         n.min_req = std::min(n.min_req, ch.min_req);
         below += ch.A - ch.start;
       }
+      // a shared segment is charged once per step while any request below it decodes
+      n.S += 2 * (int64_t)(n.end - n.start) * n.max_d;
+      if (b->mem_model == BS_MEM_SHARED) n.B = n.S + 2 * (int64_t)n.start * n.max_d;
     }
     n.A = n.start + below;
   }
@@ -403,6 +410,41 @@ int bs_builder_add(bs_builder *b, const int32_t *tokens, int32_t n_tokens, int32
   return (int)b->reqs.size() - 1;
 }
 
+int bs_builder_set_mem_model(bs_builder *b, int mem_model) {
+  if (!b) return BS_EINVAL;
+  if (b->finalized) return fail(b, BS_EINVAL, "bs_builder_set_mem_model after bs_builder_finalize");
+  if (mem_model != BS_MEM_EXPANDED && mem_model != BS_MEM_SHARED) return fail(b, BS_EINVAL, "unknown memory model %d", mem_model);
+  b->mem_model = mem_model;
+  return BS_OK;
+}
+
+int64_t bs_kv_bytes_per_token(int variant, int32_t n_layers, int32_t n_heads, int32_t head_dim, int32_t n_kv_heads,
+                              int32_t latent_dim, int32_t rope_dim, int32_t elem_bytes) {
+  if (n_layers <= 0 || elem_bytes <= 0) return BS_EINVAL;
+  int64_t per_layer;
+  switch (variant) {
+    case BS_ATTN_MHA:
+      if (n_heads <= 0 || head_dim <= 0) return BS_EINVAL;
+      per_layer = 2 * (int64_t)n_heads * head_dim;
+      break;
+    case BS_ATTN_MQA:
+      if (head_dim <= 0) return BS_EINVAL;
+      per_layer = 2 * (int64_t)head_dim;
+      break;
+    case BS_ATTN_GQA:
+      if (n_heads <= 0 || head_dim <= 0 || n_kv_heads <= 0 || n_heads % n_kv_heads) return BS_EINVAL;
+      per_layer = 2 * (int64_t)n_kv_heads * head_dim;
+      break;
+    case BS_ATTN_MLA:
+      if (latent_dim <= 0 || rope_dim < 0) return BS_EINVAL;
+      per_layer = (int64_t)latent_dim + rope_dim;
+      break;
+    default:
+      return BS_EINVAL;
+  }
+  return per_layer * n_layers * elem_bytes;
+}
+
 int bs_builder_finalize(bs_builder *b) {
   if (!b) return BS_EINVAL;
   if (b->finalized) return BS_OK;
@@ -415,6 +457,8 @@ int bs_builder_split(bs_builder *b, int64_t t, int64_t budget_tokens, bs_split_i
   if (!b) return BS_EINVAL;
   if (!b->finalized) return fail(b, BS_EINVAL, "bs_builder_split before bs_builder_finalize");
   if (t < 0) return fail(b, BS_EINVAL, "threshold t must be >= 0");
+  if (b->mem_model != BS_MEM_EXPANDED)
+    return fail(b, BS_EINVAL, "node splitting is defined for the additive memory model (BS_MEM_EXPANDED) only");
   int64_t spent = 0;
   int32_t rounds = 0, n_split = 0;
   std::vector<int64_t> A, B;

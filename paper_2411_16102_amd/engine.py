@@ -53,8 +53,12 @@ class _Live:
 
 class Engine:
     def __init__(self, builder, requests: Sequence[PoolRequest], mem_tokens: int, policy: str = "blend",
-                 token_budget: int = 2560, split_t: int = 0, split_budget: int = -1, seed: int = 0):
+                 token_budget: int = 2560, split_t: int = 0, split_budget: int = -1, seed: int = 0,
+                 mem_model: str = "expanded"):
         assert policy in ("blend", "dfs", "random")
+        if mem_model != "expanded":
+            builder.set_mem_model(mem_model)   # densities with shared prefix pages read once per step
+            split_t = 0                        # node splitting is defined for the additive model
         self.b = builder
         self.reqs = list(requests)
         self.policy = policy

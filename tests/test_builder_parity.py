@@ -194,3 +194,52 @@ def test_errors():
     b.finalize()
     with pytest.raises(binding.BlendStepError):
         b.add([3], 1, 0)
+
+
+# ---------------------------------------------------------------------------
+# memory model with prefix pages read once; kappa of the attention variants
+# ---------------------------------------------------------------------------
+def both_shared(reqs, mem_bytes, hw=MI355_8B):
+    cm = OB.CostModel(mem_bytes=mem_bytes, page_size=16, mem_model="shared", **hw)
+    o = OB.BuilderOracle(cm, reqs)
+    b = binding.Builder(hw["p_model"], hw["kv_bytes"], hw["compute"], hw["bandwidth"], mem_bytes, 16)
+    b.set_mem_model("shared")
+    for r in reqs:
+        b.add(r.tokens, r.d_est, r.n_cached)
+    b.finalize()
+    return o, b
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_shared_memory_model_small_pools(seed):
+    o, b = both_shared(small_pool(seed), mem_bytes=5_000_000, hw=A100_8B)
+    assert_same_tree(o, b)
+    assert_same_batch(o, b)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_shared_memory_model_grouped_pools(seed):
+    reqs = grouped_pool(seed, two_level=bool(seed % 2))
+    o, b = both_shared(reqs, mem_bytes=int(2e9))
+    assert_same_tree(o, b)
+    assert_same_batch(o, b, prefill_budget=1024)
+    e, _ = both(reqs, mem_bytes=int(2e9), hw=MI355_8B)
+    assert (o.tree_arrays()["B"] <= e.tree_arrays()["B"]).all() or o.leaf_order != e.leaf_order
+    with pytest.raises(binding.BlendStepError):
+        b.split(100)                                   # defined for the additive model only
+    with pytest.raises(binding.BlendStepError):
+        b.set_mem_model("expanded")                    # after finalize
+
+
+def test_kv_bytes_of_the_attention_variants_match_the_oracle():
+    cases = [dict(variant="mha", n_layers=32, n_heads=32, head_dim=128),
+             dict(variant="mqa", n_layers=40, n_heads=48, head_dim=128),
+             dict(variant="gqa", n_layers=80, n_heads=64, head_dim=128, n_kv_heads=8),
+             dict(variant="gqa", n_layers=28, n_heads=28, head_dim=128, n_kv_heads=4, elem_bytes=1),
+             dict(variant="mla", n_layers=60, n_heads=128, head_dim=128, latent_dim=512, rope_dim=64)]
+    for kw in cases:
+        assert binding.kv_bytes_per_token(**kw) == OB.kv_bytes_per_token(**kw)
+    with pytest.raises(binding.BlendStepError):
+        binding.kv_bytes_per_token("gqa", 32, 32, 128, n_kv_heads=5)
+    with pytest.raises(ValueError):
+        binding.kv_bytes_per_token("xyz", 1)

@@ -88,3 +88,17 @@ def test_blend_fills_steps_that_the_dfs_order_leaves_to_decoding_alone():
         out[policy] = (cost[0], st["steps"])
     print(out)
     assert out["blend"][1] < 0.75 * out["dfs"][1] and out["blend"][0] < out["dfs"][0]
+
+
+def test_pool_is_served_under_the_shared_memory_model():
+    reqs = E.synthetic_pool(3, n_groups=6, per_group=5, n_fresh=10)
+    eng = make_engine(reqs, "blend", split_t=10 ** 9, mem_model="shared")
+    assert eng.split_info is None                     # node splitting is switched off with this model
+    st = eng.run(lambda d: None)
+    assert eng.done and st["finished"] == len(reqs)
+    assert st["tokens_out"] == sum(r.d_true for r in reqs)
+    assert st["prefill_rows"] + st["prompt_tokens_skipped"] == sum(len(r.tokens) for r in reqs)
+    # groups look less memory-bound than under the paper's model, fresh prompts look the same
+    ref = make_engine(reqs, "blend")
+    t_s, t_e = eng.b.tree(), ref.b.tree()
+    assert int(t_s["B"][0]) < int(t_e["B"][0]) and int(t_s["A"][0]) == int(t_e["A"][0])

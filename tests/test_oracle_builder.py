@@ -411,3 +411,72 @@ def test_split_separates_the_low_density_request_of_the_overview_figure():
     o2 = B.BuilderOracle(cm(), reqs)
     i2 = o2.split(t=len(P) + len(Q) - 1)
     assert 2 not in o2.detached and not i2["monotone"]
+
+
+# ---------------------------------------------------------------------------
+# memory model with prefix pages read once, and kappa of the attention variants
+# ---------------------------------------------------------------------------
+def loaded_tokens_when_decoding_together(reqs, members):
+    """Section 4.1's count of loaded tokens, sum over decode steps i of (p + i) per request,
+    taken literally step by step for `members` decoding together, but with every distinct
+    prompt position (a position in the trie = a distinct prompt prefix) loaded once per step."""
+    total = 0
+    for i in range(1, max([reqs[r].d_est for r in members] + [0]) + 1):
+        active = [r for r in members if reqs[r].d_est >= i]
+        prefixes = {tuple(reqs[r].tokens[:k]) for r in active for k in range(1, len(reqs[r].tokens) + 1)}
+        total += len(prefixes) + i * len(active)
+    return total
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_shared_memory_model_against_step_by_step_count(seed):
+    reqs = random_pool(seed, n=9)
+    o = B.BuilderOracle(cm(mem_model="shared"), reqs)
+    e = B.BuilderOracle(cm(), reqs)
+    for n, nd in enumerate(o.nodes):
+        members = subtree_requests(o, n)
+        # the closed form drops the same d/2 per request as the paper's (p d + d^2 / 2)
+        want = 2 * loaded_tokens_when_decoding_together(reqs, members) - sum(reqs[r].d_est for r in members)
+        assert nd.B == want, (n, nd.B, want)
+    # A does not depend on the memory model; B never exceeds the paper's
+    key = lambda t: sorted((nd.start, nd.end, nd.req, nd.A) for nd in t.nodes)
+    assert key(o) == key(e)
+    assert o.nodes[0].B <= e.nodes[0].B
+
+
+def test_shared_memory_model_equals_the_papers_without_sharing():
+    reqs = [B.Request(tokens=[i] + [7] * (3 + i), d_est=2 * i + 1) for i in range(6)]   # distinct first tokens
+    o = B.BuilderOracle(cm(mem_model="shared"), reqs)
+    e = B.BuilderOracle(cm(), reqs)
+    assert o.tree_arrays()["B"].tolist() == e.tree_arrays()["B"].tolist()
+    assert o.leaf_order == e.leaf_order
+
+
+def test_shared_memory_model_closed_form_for_one_group():
+    # n requests behind one prefix of P tokens, each with o own tokens and the same d:
+    # the prefix is read d times in all instead of n d times
+    n, P, own, d = 5, 40, 3, 11
+    reqs = [B.Request(tokens=[1] * P + [10 + i] * own, d_est=d) for i in range(n)]
+    o = B.BuilderOracle(cm(mem_model="shared"), reqs)
+    e = B.BuilderOracle(cm(), reqs)
+    assert e.nodes[0].B == n * (2 * (P + own) * d + d * d)
+    assert o.nodes[0].B == 2 * P * d + n * (2 * own * d + d * d)
+    with pytest.raises(ValueError):
+        o.split(100)
+
+
+def test_kv_bytes_of_the_attention_variants():
+    # Llama-3-8B, GQA with 8 KV heads of 128, 32 layers, 2-byte elements: H_kv * L * 4 with H_kv = 1024
+    assert B.kv_bytes_per_token("gqa", 32, 32, 128, n_kv_heads=8) == 1024 * 32 * 4 == LLAMA8B["kv_bytes"]
+    mha = B.kv_bytes_per_token("mha", 32, 32, 128)
+    assert mha == 4096 * 32 * 4                                   # H_kv = H for multi-head attention
+    assert B.kv_bytes_per_token("gqa", 32, 32, 128, n_kv_heads=32) == mha
+    assert B.kv_bytes_per_token("mqa", 32, 32, 128) == mha // 32 == B.kv_bytes_per_token("gqa", 32, 32, 128, n_kv_heads=1)
+    # a latent of 512 plus a rotary key of 64 per token and layer, 60 layers
+    assert B.kv_bytes_per_token("mla", 60, 128, 128, latent_dim=512, rope_dim=64) == 576 * 60 * 2
+    assert B.kv_bytes_per_token("gqa", 32, 32, 128, n_kv_heads=8, elem_bytes=1) == 1024 * 32 * 2
+    for bad in (dict(variant="gqa", n_layers=32, n_heads=32, head_dim=128, n_kv_heads=5),
+                dict(variant="mla", n_layers=60, n_heads=128, head_dim=128),
+                dict(variant="xyz", n_layers=1, n_heads=1, head_dim=1)):
+        with pytest.raises(ValueError):
+            B.kv_bytes_per_token(**bad)
