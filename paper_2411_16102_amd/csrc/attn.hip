@@ -252,43 +252,63 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NQB > 1 ? 1
 }
 
 // ------------------------------------------------------------------------------
-// merge: one wavefront per (decode sequence, query head)
+// merge: dh/4 lanes per (decode sequence, query head), four output elements per lane
 //   M = max_p m_p;  w_p = 2^(m_p - M);  out = sum_p w_p acc_p / sum_p w_p l_p
 // ------------------------------------------------------------------------------
+// A wavefront covers 256/dh heads of one sequence, so its loads of the partial outputs are
+// 16 bytes per lane, and the partial states are added four at a time with their loads
+// issued together: the kernel is a chain of a few memory round trips, not bandwidth.
 template <int DH>
 __global__ __launch_bounds__(256) void decode_merge_kernel(const MergeArgs a) {
+  constexpr int LPH = DH / 4;    // lanes per head
+  constexpr int HPW = 64 / LPH;  // heads per wavefront
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int hq = a.s.n_q_heads;
+  const int units_per_seq = (hq + HPW - 1) / HPW;
   const int unit = blockIdx.x * 4 + wave;
-  if (unit >= a.n_decode * hq) return;
-  const int seq = a.n_prefill + unit / hq;
-  const int head = unit % hq;
+  if (unit >= a.n_decode * units_per_seq) return;
+  const int seq = a.n_prefill + unit / units_per_seq;
+  const int sub = lane / LPH, li = lane % LPH;
+  const int head_raw = (unit % units_per_seq) * HPW + sub;
+  const bool ok = head_raw < hq;
+  const int head = ok ? head_raw : hq - 1;  // lanes past the last head repeat it and store nothing
   const int s0 = a.part_start[seq], n = a.part_start[seq + 1] - s0;
   float mx = NEG_BIG;
-  for (int p = lane; p < n; p += 64) mx = fmaxf(mx, a.part_m[(size_t)(s0 + p) * hq + head]);
-  mx = wave_max(mx);
+  for (int p = li; p < n; p += LPH) mx = fmaxf(mx, a.part_m[(size_t)(s0 + p) * hq + head]);
+#pragma unroll
+  for (int o = LPH / 2; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
   float ls = 0.f;
-  for (int p = lane; p < n; p += 64) {
+  for (int p = li; p < n; p += LPH) {
     const size_t b = (size_t)(s0 + p) * hq + head;
     ls += fast_exp2(a.part_m[b] - mx) * a.part_l[b];
   }
-  ls = wave_sum(ls);
-  constexpr int E = DH / 64;  // elements per lane
-  float acc[E];
 #pragma unroll
-  for (int e = 0; e < E; ++e) acc[e] = 0.f;
-  for (int p = 0; p < n; ++p) {
-    const size_t b = (size_t)(s0 + p) * hq + head;
-    const float w = fast_exp2(a.part_m[b] - mx);
-    const float *src = a.part_acc + b * DH + lane * E;
+  for (int o = LPH / 2; o >= 1; o >>= 1) ls += __shfl_xor(ls, o, 64);
+  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+  int p = 0;
+  for (; p + 4 <= n; p += 4) {
+    float w[4];
+    f32x4_t v[4];
 #pragma unroll
-    for (int e = 0; e < E; ++e) acc[e] += w * src[e];
+    for (int u = 0; u < 4; ++u) {
+      const size_t b = (size_t)(s0 + p + u) * hq + head;
+      w[u] = a.part_m[b];
+      v[u] = *reinterpret_cast<const f32x4_t *>(a.part_acc + b * DH + li * 4);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc += fast_exp2(w[u] - mx) * v[u];
   }
+  for (; p < n; ++p) {
+    const size_t b = (size_t)(s0 + p) * hq + head;
+    acc += fast_exp2(a.part_m[b] - mx) * *reinterpret_cast<const f32x4_t *>(a.part_acc + b * DH + li * 4);
+  }
+  if (!ok) return;
   const float inv = 1.f / ls;
-  uint16_t *dst = a.out + (size_t)a.row_start[seq] * (hq * DH) + head * DH + lane * E;
-#pragma unroll
-  for (int e = 0; e < E; ++e) dst[e] = f32_to_bf16(acc[e] * inv);
+  u32x2_t o2;
+  o2.x = pack_bf16x2(acc[0] * inv, acc[1] * inv);
+  o2.y = pack_bf16x2(acc[2] * inv, acc[3] * inv);
+  *reinterpret_cast<u32x2_t *>(a.out + (size_t)a.row_start[seq] * (hq * DH) + head * DH + li * 4) = o2;
 }
 
 // acc *= alpha for an MFMA accumulator that lives in the accumulation registers.  Written out
@@ -572,14 +592,14 @@ hipError_t launch_decode_attn(const DecodeArgs &a, int item_base, int n_items, i
 }
 
 hipError_t launch_decode_merge(const MergeArgs &a, hipStream_t stream) {
-  const int units = a.n_decode * a.s.n_q_heads;
-  if (units <= 0) return hipSuccess;
+  if (a.n_decode <= 0) return hipSuccess;
+  if (a.s.head_dim != 128 && a.s.head_dim != 64) return hipErrorInvalidValue;
+  const int hpw = 256 / a.s.head_dim;  // heads per wavefront
+  const int units = a.n_decode * ((a.s.n_q_heads + hpw - 1) / hpw);
   if (a.s.head_dim == 128)
     hipLaunchKernelGGL((decode_merge_kernel<128>), dim3((units + 3) / 4), dim3(256), 0, stream, a);
-  else if (a.s.head_dim == 64)
-    hipLaunchKernelGGL((decode_merge_kernel<64>), dim3((units + 3) / 4), dim3(256), 0, stream, a);
   else
-    return hipErrorInvalidValue;
+    hipLaunchKernelGGL((decode_merge_kernel<64>), dim3((units + 3) / 4), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 

@@ -36,14 +36,22 @@ __global__ __launch_bounds__(256) void norm_prep_kernel(const uint16_t *x, const
 }
 
 // rstd[m] = 1 / sqrt(sum_p part[p][m] / d + eps): closes the row sums of squares that
-// the output projection's epilogue leaves per column tile
-__global__ void rstd_finalize_kernel(const float *part, int n_part, int stride, float *rstd, int rows, float d,
-                                     float eps) {
-  const int m = blockIdx.x * blockDim.x + threadIdx.x;
-  if (m >= rows) return;
+// the output projection's epilogue leaves per column tile.  A workgroup covers 64 rows;
+// its four wavefronts each add every fourth partial (coalesced along the rows, the loads
+// of a thread independent of each other) and meet in LDS.
+__global__ __launch_bounds__(256) void rstd_finalize_kernel(const float *part, int n_part, int stride, float *rstd,
+                                                            int rows, float d, float eps) {
+  __shared__ float sh[4][64];
+  const int r = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int m = blockIdx.x * 64 + r;
   float s = 0.f;
-  for (int p = 0; p < n_part; ++p) s += part[(size_t)p * stride + m];
-  rstd[m] = rsqrtf(s / d + eps);
+  if (m < rows) {
+#pragma unroll 8
+    for (int p = q; p < n_part; p += 4) s += part[(size_t)p * stride + m];
+  }
+  sh[q][r] = s;
+  __syncthreads();
+  if (q == 0 && m < rows) rstd[m] = rsqrtf((sh[0][r] + sh[1][r] + sh[2][r] + sh[3][r]) / d + eps);
 }
 
 // cos/sin of pos * theta^(-2i/dh), evaluated in double and stored as float
@@ -93,7 +101,7 @@ hipError_t launch_norm_prep(const uint16_t *x, const uint16_t *g, uint16_t *xg, 
 hipError_t launch_rstd_finalize(const float *part, int n_part, int stride, float *rstd, int rows, int d, float eps,
                                 hipStream_t stream) {
   if (rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(rstd_finalize_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, part, n_part, stride, rstd,
+  hipLaunchKernelGGL(rstd_finalize_kernel, dim3((rows + 63) / 64), dim3(256), 0, stream, part, n_part, stride, rstd,
                      rows, (float)d, eps);
   return hipGetLastError();
 }
