@@ -234,6 +234,17 @@ def test_degenerate_batches(lib):
     check_step(lib, shape, edge, W.make_tensors(shape, edge, 2, gains="random"))
 
 
+def test_contexts_up_to_the_last_position(lib):
+    # the longest contexts the default RoPE table (16384 positions) admits: a prefill chunk whose
+    # last row sits at the last position, decode sequences there and one page short of it, two of
+    # them behind a shared prefix of 1000 pages (split over many chunks of the decode kernel)
+    shape = W.TINY
+    top = 16384
+    batch = W.assemble_batch(16, [(70, top, -1), (1, top, -1), (1, top, 0), (1, top - 16, 0), (1, 5000, -1)], 1,
+                             [(-1, 1000)], np.random.default_rng(9))
+    check_step(lib, shape, batch, W.make_tensors(shape, batch, 4, gains="random"))
+
+
 @pytest.mark.parametrize("shape", [W.LayerShape(512, 16, 1, 64, 256), W.LayerShape(256, 4, 4, 64, 344)])
 def test_group_sizes_sixteen_and_one(lib, shape):
     # 16 query heads per KV head (one member fills a decode work item) and plain multi-head attention
