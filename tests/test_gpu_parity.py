@@ -234,6 +234,15 @@ def test_degenerate_batches(lib):
     check_step(lib, shape, edge, W.make_tensors(shape, edge, 2, gains="random"))
 
 
+def test_ragged_prefill_segments(lib):
+    # segments of 1, 31, 32, 33, 64, 65 and 97 rows (a wavefront of prefill attention owns 64) behind
+    # cached contexts that end on and off page and block boundaries
+    shape = W.LayerShape(512, 8, 2, 128, 256)
+    segs = [(1, 48, -1), (31, 31, -1), (32, 96, -1), (33, 33, -1), (64, 200, -1), (65, 129, -1), (97, 1000, -1)]
+    batch = W.assemble_batch(16, segs + [(1, 77, -1)], len(segs), [], np.random.default_rng(11))
+    check_step(lib, shape, batch, W.make_tensors(shape, batch, 6, gains="random"), mae_tol=2 * MAE)
+
+
 def test_contexts_up_to_the_last_position(lib):
     # the longest contexts the default RoPE table (16384 positions) admits: a prefill chunk whose
     # last row sits at the last position, decode sequences there and one page short of it, two of
