@@ -181,14 +181,17 @@ def main():
     note("timing")
     y = torch.empty_like(dev.x)
 
+    def run_once(flags):
+        if args.layers > 1:
+            layer.blend_layers([dev] * args.layers, batch, flags=flags, y=y, desc=desc)
+        else:
+            layer.blend_step(dev, batch, flags=flags, y=y, desc=desc)
+
     def run(n, flags):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(n):
-            if args.layers > 1:
-                layer.blend_layers([dev] * args.layers, batch, flags=flags, y=y, desc=desc)
-            else:
-                layer.blend_step(dev, batch, flags=flags, y=y, desc=desc)
+            run_once(flags)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / max(1, n)
 
@@ -201,6 +204,20 @@ def main():
         flags = 1 if t_overlap < t_serial else 0
     run(args.warmup, flags)
     sec = run(args.steps, flags) / args.layers
+
+    # spread of single calls: the same loop once more with a pair of events around every call
+    stream = torch.cuda.current_stream()
+    pairs = []
+    for _ in range(args.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        run_once(flags)
+        e1.record(stream)
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    per_call = np.sort(np.array([a.elapsed_time(b) for a, b in pairs])) / args.layers
+    spread = {"p10": float(np.percentile(per_call, 10)), "p50": float(np.percentile(per_call, 50)),
+              "p90": float(np.percentile(per_call, 90))}
 
     # per-kernel durations: the same loop again with HIP events around every kernel class
     layer.profile(True)
@@ -239,6 +256,7 @@ def main():
     out = {
         "metric": "blended-step tokens/s per layer", "value": T / sec, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
+        "ms_per_call_by_events": spread,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "rows": T, "prefill_rows": int(batch.row_start[batch.n_prefill]),
                    "decode_seqs": batch.n_seq - batch.n_prefill, "prefix_nodes": batch.n_nodes,
