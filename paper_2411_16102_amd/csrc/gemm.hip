@@ -1,10 +1,13 @@
 // bf16 "NT" GEMM  C[M,N] = A[M,K] * B[N,K]^T  for gfx950, fp32 accumulation on
-// v_mfma_f32_32x32x16_bf16, tiles staged through LDS, fused epilogues.
+// v_mfma_f32_16x16x32_bf16, tiles staged through LDS, fused epilogues.  (The chip lowers its
+// clock under matrix load; at that limit the 16x16x32 shape, which moves fewer accumulator
+// registers per flop, sustains 1.87 PFLOP/s on random operands where 32x32x16 sustains
+// 1.7, and this kernel gained 10 to 24 % from the change.)
 //
 // Operand roles are swapped with respect to the usual picture: the weight rows
 // feed the MFMA "A" operand and the activation rows the "B" operand, so an
-// accumulator block holds C^T: a lane owns ONE activation row (m = lane % 32) and
-// runs of four consecutive output features (n).  Every fused epilogue is then
+// accumulator block holds C^T: a lane owns ONE activation row (m = lane % 16) and
+// a run of four consecutive output features (n = 4 * (lane / 16) ..).  Every fused epilogue is then
 // lane-local: the RMSNorm factor of a row is one scalar per lane, a RoPE pair
 // (i, i + dh/2) and a SwiGLU (gate, up) pair sit in two accumulator blocks of the
 // same lane, and results leave as 8-byte bf16x4 stores.
@@ -18,8 +21,8 @@
 // tile kt+1 has landed or is landing and the activation panel of tile kt+2 is in
 // flight.  Rows are 128 B whose eight 16-byte chunks are XOR-swizzled with
 // ((row >> 1) & 7): two consecutive rows fill the 256-byte bank row, so the swizzle
-// must change every two rows for the ds_read_b128 of a fragment (32 rows, one chunk
-// column) to be conflict-free.  Waits on the LDS-DMA loads are placed by hand
+// must change every two rows for the ds_read_b128 of a fragment (16 rows by four chunk
+// columns) to be conflict-free.  Waits on the LDS-DMA loads are placed by hand
 // (s_waitcnt vmcnt + s_barrier); the compiler does not track them.
 #include <algorithm>
 #include "gemm.hpp"
@@ -76,15 +79,15 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
   constexpr int NW = WAVES_M * WAVES_N;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
-  constexpr int MI = WTM / 32, NI = WTN / 32;
+  constexpr int MI = WTM / 16, NI = WTN / 16;  // 16x16 accumulator blocks of a wavefront's tile
   constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   constexpr int ROWB = BK * 2;                       // bytes of one tile row
   constexpr int UNIT = (BM > BN ? BM : BN) * ROWB;   // one ring unit holds either panel
   constexpr int GA = BM / 8, GB = BN / 8;            // 8-row groups = one 1 KB wavefront load each
   constexpr int LA = (GA + NW - 1) / NW, LB = (GB + NW - 1) / NW;  // loads per thread per panel
   static_assert(BK == 64, "swizzle and fragment addressing assume 128-byte tile rows");
-  static_assert(BM % 32 == 0 && BN % 32 == 0, "tiles are made of 32x32 MFMA blocks");
-  static_assert(EPI != EPI_SWIGLU || NI % 2 == 0, "gate and up blocks pair up inside a wave");
+  static_assert(WTM % 16 == 0 && WTN % 16 == 0, "tiles are made of 16x16 MFMA blocks");
+  static_assert(EPI != EPI_SWIGLU || WTN % 64 == 0, "32 gate rows and their 32 up rows pair up inside a wave");
   static_assert(EPI != EPI_QKV || (WTN % DH == 0 && DH % 64 == 0), "a wave covers whole heads");
   static_assert(2 * LA + 2 * LB < 64, "outstanding loads must fit the vmcnt field");
 
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm0 = (wave / WAVES_N) * WTM, wn0 = (wave % WAVES_N) * WTN;
-  const int lr = lane & 31, lg = lane >> 5;
+  const int lr = lane & 15, lg = lane >> 4;  // row of a 16-row block; k-chunk of a fragment, feature group of an accumulator
 
   // ---- global -> LDS, without passing through registers ---------------------------
   // One wavefront load moves 8 tile rows (1 KB): lane i lands at LDS byte 16 i of the
@@ -164,15 +167,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
     __builtin_amdgcn_global_load_lds(p, (__attribute__((address_space(3))) void *)(smem + slot * UNIT + dst_b[i]), 16, 0, 0);
   };
 
-  f32x16_t acc[NI][MI];
+  f32x4_t acc[NI][MI];
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[ni][mi][r] = 0.f;
+    for (int mi = 0; mi < MI; ++mi) acc[ni][mi] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  // fragment addresses: tile row of the lane, chunk 2*ks + lg swizzled by ((row >> 1) & 7)
+  // fragment addresses: tile row of the lane, chunk 4*ks + lg swizzled by ((row >> 1) & 7)
   const int sw = (lr >> 1) & 7;
   const int xfrag = (wm0 + lr) * ROWB;
   const int wfrag = (wn0 + lr) * ROWB;
@@ -181,15 +182,15 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   // this workgroup's k-tiles [kt0, kt1): all of them, or one of k_splits nearly equal ranges
   const int kt0 = (EPI == EPI_PARTIAL) ? (int)((long)nk_all * split / a.k_splits) : 0;
   const int kt1 = (EPI == EPI_PARTIAL) ? (int)((long)nk_all * (split + 1) / a.k_splits) : nk_all;
-  constexpr int NF = MI + NI;   // fragment reads per 16-wide k-step
-  constexpr int NMF = MI * NI;  // MFMAs per 16-wide k-step
-  // read number o of k-step ks (16 wide, four per tile) of the panels in ring slots sa, sb
+  constexpr int NF = MI + NI;   // fragment reads per 32-wide k-step
+  constexpr int NMF = MI * NI;  // MFMAs per 32-wide k-step
+  // read number o of k-step ks (32 wide, two per tile) of the panels in ring slots sa, sb
   auto frag = [&](int sa, int sb, int ks, int o, bf16x8_t (&xf)[MI], bf16x8_t (&wf)[NI]) {
-    const int ch = ((ks * 2 + lg) ^ sw) << 4;
+    const int ch = ((ks * 4 + lg) ^ sw) << 4;
     if (o < MI)
-      xf[o] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(smem + sa * UNIT + xfrag + o * 32 * ROWB + ch));
+      xf[o] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(smem + sa * UNIT + xfrag + o * 16 * ROWB + ch));
     else
-      wf[o - MI] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(smem + sb * UNIT + wfrag + (o - MI) * 32 * ROWB + ch));
+      wf[o - MI] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(smem + sb * UNIT + wfrag + (o - MI) * 16 * ROWB + ch));
   };
   // One k-step: its NMF MFMAs in program order, with the `n_ops` side operations (LDS
   // reads of the next k-step, DMA requests) dealt out behind the first MFMAs, `per` at a
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
 #pragma unroll
     for (int j = 0; j < NMF; ++j) {
       const int ni = j / MI, mi = j % MI;
-      acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
+      acc[ni][mi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int q = 0; q < per; ++q)
@@ -212,16 +213,16 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   // panel u lives in ring slot u % 5.  Once the last fragments of tile kt are in
   // registers, at the one barrier of the iteration, W(kt+2) and X(kt+3) are requested
   // into the two slots that tile kt frees.  LDS -> registers: the fragments of the next
-  // 16-wide k-step are requested while the MFMAs of the current one are issued, across
+  // 32-wide k-step are requested while the MFMAs of the current one are issued, across
   // tile boundaries too, so the matrix pipe never waits for a whole LDS read phase.
   // The compiler counts an LDS-DMA load as a pending LDS operation of unknown order, so
   // every wait it places before an MFMA is lgkmcnt(0); waiting explicitly at the start of
   // a k-step, for reads issued during the first MFMAs of the previous one, keeps those
   // waits from covering reads that were only just issued.
   constexpr int LGKM0 = waitcnt_imm(63, true);
-  constexpr int PER_F = (NF + NMF - 1) / NMF > 2 ? (NF + NMF - 1) / NMF : 2;
+  constexpr int PER_F = (NF + NMF - 1) / NMF;  // side operations per MFMA: one is enough where a step has 32 MFMAs
   constexpr int N_P = NF + LB + LA;
-  constexpr int PER_P = (N_P + NMF - 1) / NMF > 2 ? (N_P + NMF - 1) / NMF : 2;
+  constexpr int PER_P = (N_P + NMF - 1) / NMF;
   bf16x8_t xa[MI], wa[NI], xb[MI], wb[NI];
 #pragma unroll
   for (int i = 0; i < LA; ++i) dma_a(kt0, 0, i, Yes{});
@@ -241,10 +242,6 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   auto tile = [&](int kt, auto checked) {
     __builtin_amdgcn_s_waitcnt(LGKM0);
     step(xa, wa, NF, PER_F, [&](int o) { frag(sa, sb, 1, o, xb, wb); });
-    __builtin_amdgcn_s_waitcnt(LGKM0);
-    step(xb, wb, NF, PER_F, [&](int o) { frag(sa, sb, 2, o, xa, wa); });
-    __builtin_amdgcn_s_waitcnt(LGKM0);
-    step(xa, wa, NF, PER_F, [&](int o) { frag(sa, sb, 3, o, xb, wb); });
     // Every fragment of tile kt is in registers once the LDS reads have returned, and
     // tile kt+1 has landed once this wavefront's loads other than the youngest panel,
     // X(kt+2), are done; after the barrier both hold for every wavefront, so the two
@@ -271,53 +268,53 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
 
   // ---- epilogues ---------------------------------------------------------------
-  // accumulator element r of block (ni, mi): m = m0 + wm0 + mi*32 + lr,
-  // n = n_tile + wn0 + ni*32 + 8*(r/4) + 4*lg + r%4
-  float rstd[MI];
-  if (EPI == EPI_QKV || EPI == EPI_SWIGLU) {
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-      const int m = m0 + wm0 + mi * 32 + lr;
-      rstd[mi] = (m < a.M) ? a.rstd[m] : 0.f;
+  // accumulator element e of block (ni, mi): m = m0 + wm0 + mi*16 + lr,
+  // n = n_tile + wn0 + ni*16 + 4*lg + e
+  // A tile that lies wholly inside the matrix takes a copy of the epilogue without bounds
+  // checks: straight-line code whose loads all go out together; with the checks every
+  // block is a basic block of its own and the epilogue becomes a chain of memory round trips.
+  auto epilogue = [&](auto checked) {
+    constexpr bool CK = decltype(checked)::value;
+    float rstd[MI];
+    if (EPI == EPI_QKV || EPI == EPI_SWIGLU) {
+  #pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        const int m = m0 + wm0 + mi * 16 + lr;
+        rstd[mi] = (!CK || m < a.M) ? a.rstd[m] : 0.f;
+      }
     }
-  }
 
-  if (EPI == EPI_PARTIAL) {
-    float *ws = a.splitk_ws + (size_t)split * a.M * a.N;
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-      const int m = m0 + wm0 + mi * 32 + lr;
-      if (m >= a.M) continue;
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + wn0 + ni * 32 + 8 * q + 4 * lg;
-          if (n >= a.N) continue;
-          *reinterpret_cast<f32x4_t *>(ws + (size_t)m * a.N + n) =
-              f32x4_t{acc[ni][mi][4 * q], acc[ni][mi][4 * q + 1], acc[ni][mi][4 * q + 2], acc[ni][mi][4 * q + 3]};
+    if (EPI == EPI_PARTIAL) {
+      float *ws = a.splitk_ws + (size_t)split * a.M * a.N;
+  #pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        const int m = m0 + wm0 + mi * 16 + lr;
+        if (CK && m >= a.M) continue;
+  #pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+          const int n = n0 + wn0 + ni * 16 + 4 * lg;
+          if (CK && n >= a.N) continue;
+          *reinterpret_cast<f32x4_t *>(ws + (size_t)m * a.N + n) = acc[ni][mi];
         }
+      }
     }
-  }
 
-  if (EPI == EPI_PLAIN || EPI == EPI_RESID) {
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-      const int m = m0 + wm0 + mi * 32 + lr;
-      if (m >= a.M) continue;
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + wn0 + ni * 32 + 8 * q + 4 * lg;
-          if (n >= n_lim) continue;
+    if (EPI == EPI_PLAIN || EPI == EPI_RESID) {
+  #pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        const int m = m0 + wm0 + mi * 16 + lr;
+        if (CK && m >= a.M) continue;
+  #pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+          const int n = n0 + wn0 + ni * 16 + 4 * lg;
+          if (CK && n >= n_lim) continue;
           float v[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[ni][mi][4 * q + e];
+  #pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = acc[ni][mi][e];
           if (EPI == EPI_RESID) {
             if (a.resid32) {
               const f32x4_t rr = *reinterpret_cast<const f32x4_t *>(a.resid32 + (size_t)m * a.ldr + n);
-#pragma unroll
+  #pragma unroll
               for (int e = 0; e < 4; ++e) v[e] += rr[e];
             } else {
               const u32x2_t rr = *reinterpret_cast<const u32x2_t *>(a.resid + (size_t)m * a.ldr + n);
@@ -329,130 +326,133 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
           }
           store_bf16x4(a.C + (size_t)m * a.ldc + n, v[0], v[1], v[2], v[3]);
         }
+      }
     }
-  }
 
-  if (EPI == EPI_RESID_NORM) {
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-      const int m = m0 + wm0 + mi * 32 + lr;
-      float ss = 0.f;
-      if (m < a.M) {
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int n = n0 + wn0 + ni * 32 + 8 * q + 4 * lg;
-            if (n >= a.N) continue;
+    if (EPI == EPI_RESID_NORM) {
+  #pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        const int m = m0 + wm0 + mi * 16 + lr;
+        float ss = 0.f;
+        if (!CK || m < a.M) {
+  #pragma unroll
+          for (int ni = 0; ni < NI; ++ni) {
+            const int n = n0 + wn0 + ni * 16 + 4 * lg;
+            if (CK && n >= a.N) continue;
             const u32x2_t rr = *reinterpret_cast<const u32x2_t *>(a.resid + (size_t)m * a.ldr + n);
             const u32x2_t gg = *reinterpret_cast<const u32x2_t *>(a.gain + n);
             float v[4], g[4];
-            v[0] = acc[ni][mi][4 * q + 0] + __uint_as_float(rr.x << 16);
-            v[1] = acc[ni][mi][4 * q + 1] + __uint_as_float(rr.x & 0xFFFF0000u);
-            v[2] = acc[ni][mi][4 * q + 2] + __uint_as_float(rr.y << 16);
-            v[3] = acc[ni][mi][4 * q + 3] + __uint_as_float(rr.y & 0xFFFF0000u);
+            v[0] = acc[ni][mi][0] + __uint_as_float(rr.x << 16);
+            v[1] = acc[ni][mi][1] + __uint_as_float(rr.x & 0xFFFF0000u);
+            v[2] = acc[ni][mi][2] + __uint_as_float(rr.y << 16);
+            v[3] = acc[ni][mi][3] + __uint_as_float(rr.y & 0xFFFF0000u);
             g[0] = __uint_as_float(gg.x << 16);
             g[1] = __uint_as_float(gg.x & 0xFFFF0000u);
             g[2] = __uint_as_float(gg.y << 16);
             g[3] = __uint_as_float(gg.y & 0xFFFF0000u);
-#pragma unroll
+  #pragma unroll
             for (int e = 0; e < 4; ++e) ss += v[e] * v[e];
             // x1 stays in fp32 for the second residual add; the next GEMM reads bf16(x1 * gain)
             *reinterpret_cast<f32x4_t *>(a.C32 + (size_t)m * a.ldc + n) = f32x4_t{v[0], v[1], v[2], v[3]};
             store_bf16x4(a.C_gain + (size_t)m * a.ldc + n, v[0] * g[0], v[1] * g[1], v[2] * g[2], v[3] * g[3]);
           }
-      }
-      ss += __shfl_xor(ss, 32, 64);
-      if (lg == 0 && m < a.M)
-        a.ss_out[(size_t)(tc.tn * WAVES_N + (wave % WAVES_N)) * a.ss_stride + m] = ss;
-    }
-  }
-
-  if (EPI == EPI_SWIGLU) {
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-      const int m = m0 + wm0 + mi * 32 + lr;
-      if (m >= a.M) continue;
-      const float s = rstd[mi];
-#pragma unroll
-      for (int p = 0; p < NI / 2; ++p)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + (wn0 >> 1) + p * 32 + 8 * q + 4 * lg;
-          if (n >= n_lim) continue;
-          float v[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float g = acc[2 * p][mi][4 * q + e] * s;
-            const float u = acc[2 * p + 1][mi][4 * q + e] * s;
-            v[e] = g / (1.f + __expf(-g)) * u;
-          }
-          store_bf16x4(a.C + (size_t)m * a.ldc + n, v[0], v[1], v[2], v[3]);
         }
+        // the four lanes that share the row (lg = 0..3) add up: one partial sum per wavefront column
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (lg == 0 && (!CK || m < a.M))
+          a.ss_out[(size_t)(tc.tn * WAVES_N + (wave % WAVES_N)) * a.ss_stride + m] = ss;
+      }
     }
-  }
 
-  if (EPI == EPI_QKV) {
-    constexpr int HB = DH / 32, PB = HB / 2, HALF = DH / 2;
-    const size_t tile_elems = (size_t)16 * DH;  // one K or V tile of a (page, head)
-#pragma unroll
-    for (int hh = 0; hh < WTN / DH; ++hh) {
-      const int nh = n0 + wn0 + hh * DH;
-      if (nh >= a.N) continue;
-      const int head = nh / DH;
-      const bool is_q = head < a.n_q_heads;
-      const bool is_k = !is_q && head < a.n_q_heads + a.n_kv_heads;
-#pragma unroll
+    if (EPI == EPI_SWIGLU) {
+      // the weight tile interleaves 32 gate rows with the matching 32 up rows: blocks 4p, 4p+1 are
+      // gate features 32p .. 32p+31 of the wavefront, blocks 4p+2, 4p+3 their up features
+  #pragma unroll
       for (int mi = 0; mi < MI; ++mi) {
-        const int m = m0 + wm0 + mi * 32 + lr;
-        if (m >= a.M) continue;
+        const int m = m0 + wm0 + mi * 16 + lr;
+        if (CK && m >= a.M) continue;
         const float s = rstd[mi];
-        if (is_q || is_k) {
-          const int pos = a.row_pos[m];
-          uint16_t *dst;
-          if (is_q) {
-            dst = a.q_out + (size_t)m * (a.n_q_heads * DH) + head * DH;
-          } else {
-            const size_t page = a.row_page[m];
-            dst = a.kv_pool + ((page * 2 + 0) * a.n_kv_heads + (head - a.n_q_heads)) * tile_elems +
-                  (size_t)a.row_slot[m] * DH;
+  #pragma unroll
+        for (int p = 0; p < NI / 4; ++p)
+  #pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const int n = n0 + (wn0 >> 1) + p * 32 + h * 16 + 4 * lg;
+            if (CK && n >= n_lim) continue;
+            float v[4];
+  #pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float g = acc[4 * p + h][mi][e] * s;
+              const float u = acc[4 * p + 2 + h][mi][e] * s;
+              v[e] = g / (1.f + __expf(-g)) * u;
+            }
+            store_bf16x4(a.C + (size_t)m * a.ldc + n, v[0], v[1], v[2], v[3]);
           }
-#pragma unroll
-          for (int j = 0; j < PB; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int i = j * 32 + 8 * q + 4 * lg;
+      }
+    }
+
+    if (EPI == EPI_QKV) {
+      constexpr int HB = DH / 16, PB = HB / 2, HALF = DH / 2;
+      const size_t tile_elems = (size_t)16 * DH;  // one K or V tile of a (page, head)
+  #pragma unroll
+      for (int hh = 0; hh < WTN / DH; ++hh) {
+        const int nh = n0 + wn0 + hh * DH;
+        if (CK && nh >= a.N) continue;
+        const int head = nh / DH;
+        const bool is_q = head < a.n_q_heads;
+        const bool is_k = !is_q && head < a.n_q_heads + a.n_kv_heads;
+  #pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+          const int m = m0 + wm0 + mi * 16 + lr;
+          if (CK && m >= a.M) continue;
+          const float s = rstd[mi];
+          if (is_q || is_k) {
+            const int pos = a.row_pos[m];
+            uint16_t *dst;
+            if (is_q) {
+              dst = a.q_out + (size_t)m * (a.n_q_heads * DH) + head * DH;
+            } else {
+              const size_t page = a.row_page[m];
+              dst = a.kv_pool + ((page * 2 + 0) * a.n_kv_heads + (head - a.n_q_heads)) * tile_elems +
+                    (size_t)a.row_slot[m] * DH;
+            }
+  #pragma unroll
+            for (int j = 0; j < PB; ++j) {
+              const int i = j * 16 + 4 * lg;
               const f32x4_t c4 = *reinterpret_cast<const f32x4_t *>(a.rope_cos + (size_t)pos * HALF + i);
               const f32x4_t s4 = *reinterpret_cast<const f32x4_t *>(a.rope_sin + (size_t)pos * HALF + i);
               float lo[4], hi[4];
-#pragma unroll
+  #pragma unroll
               for (int e = 0; e < 4; ++e) {
-                const float l = acc[hh * HB + j][mi][4 * q + e] * s;
-                const float h = acc[hh * HB + PB + j][mi][4 * q + e] * s;
+                const float l = acc[hh * HB + j][mi][e] * s;
+                const float h = acc[hh * HB + PB + j][mi][e] * s;
                 lo[e] = l * c4[e] - h * s4[e];
                 hi[e] = h * c4[e] + l * s4[e];
               }
               store_bf16x4(dst + i, lo[0], lo[1], lo[2], lo[3]);
               store_bf16x4(dst + HALF + i, hi[0], hi[1], hi[2], hi[3]);
             }
-        } else {
-          const size_t page = a.row_page[m];
-          const int slot = a.row_slot[m];
-          uint16_t *dst = a.kv_pool +
-                          ((page * 2 + 1) * a.n_kv_heads + (head - a.n_q_heads - a.n_kv_heads)) * tile_elems + slot;
-#pragma unroll
-          for (int b = 0; b < HB; ++b)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
+          } else {
+            const size_t page = a.row_page[m];
+            const int slot = a.row_slot[m];
+            uint16_t *dst = a.kv_pool +
+                            ((page * 2 + 1) * a.n_kv_heads + (head - a.n_q_heads - a.n_kv_heads)) * tile_elems + slot;
+  #pragma unroll
+            for (int b = 0; b < HB; ++b)
+  #pragma unroll
               for (int e = 0; e < 4; ++e) {
-                const int ei = b * 32 + 8 * q + 4 * lg + e;
-                dst[ei * 16] = f32_to_bf16(acc[hh * HB + b][mi][4 * q + e] * s);
+                const int ei = b * 16 + 4 * lg + e;
+                dst[ei * 16] = f32_to_bf16(acc[hh * HB + b][mi][e] * s);
               }
+          }
         }
       }
     }
-  }
+  };
+  if (m0 + BM <= a.M && n0 + OUT_BN <= n_lim && (EPI != EPI_QKV || n0 + BN <= a.N))
+    epilogue(No{});
+  else
+    epilogue(Yes{});
 }
 
 constexpr int MAX_SPLITS = 8;
@@ -569,7 +569,7 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// Tile shapes.  BIG: 256x256, 8 wavefronts.  TALL: 160x256, 4 wavefronts of 160x64: 2560 (and
+// Tile shapes.  BIG: 256x256, 8 wavefronts.  TALL: 160x256, 8 wavefronts of 80x64: 2560 (and
 // 5120) rows by 4096 (8192) columns then make exactly one (four) full rounds of 256
 // workgroups where 256x256 tiles leave 38 % (17 %) of the CUs idle.  SMALL: 128x128.
 enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3 };
@@ -602,7 +602,7 @@ int choose_variant(int m, int n_b_rows, int epilogue, int dh, int n_cu) {
 template <int EPI, int DH_BIG_M, int DH_BIG_N>
 hipError_t launch_variant(const GemmArgs &a, int v, hipStream_t stream) {
   if (v == V_BIG) return launch_one<256, 256, DH_BIG_M, DH_BIG_N, EPI, (DH_BIG_M == 4 ? 128 : 64)>(a, stream);
-  if (v == V_TALL) return launch_one<160, 256, 1, 4, EPI, 64>(a, stream);
+  if (v == V_TALL) return launch_one<160, 256, 2, 4, EPI, 64>(a, stream);
   return launch_one<128, 128, 2, 2, EPI, 64>(a, stream);
 }
 
