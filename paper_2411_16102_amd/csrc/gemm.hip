@@ -579,21 +579,26 @@ int g_forced_variant = V_AUTO;
 
 long n_tiles(int m, int n, int bm, int bn) { return (long)((m + bm - 1) / bm) * ((n + bn - 1) / bn); }
 
-// estimated time = rounds of workgroups x tile area / per-tile efficiency of the shape
-// (efficiencies measured on MI355X relative to the 256x256 tile: both smaller shapes reach 0.8)
+// Estimated time of a launch in units of one full round of 256x256 tiles: full rounds of
+// workgroups (the 128x128 tile runs two per CU) cost T each; a last, partly filled round costs
+// T (a + (1 - a) fill): workgroups that share the chip with fewer others run faster, but not in
+// proportion.  T and a were fitted on MI355X to the four GEMM shapes of the 8B layer at 384 to
+// 2560 rows (the 160x256 tile: 0.072 ms per full round at K = 4096 where the 256x256 tile takes
+// 0.100 and 512 tiles of 128x128 take 0.075).
 int choose_variant(int m, int n_b_rows, int epilogue, int dh, int n_cu) {
   if (n_cu <= 0) n_cu = N_CU;
   if (g_forced_variant != V_AUTO && !(g_forced_variant == V_TALL && epilogue == EPI_QKV)) return g_forced_variant;
   (void)dh;
-  struct Cand { int v, bm, bn; double q; };
-  const Cand cands[3] = {{V_BIG, 256, 256, 1.0}, {V_TALL, 160, 256, 0.8}, {V_SMALL, 128, 128, 0.8}};
+  struct Cand { int v, bm, bn, per_cu; double T, a; };
+  const Cand cands[3] = {{V_BIG, 256, 256, 1, 1.00, 0.72}, {V_TALL, 160, 256, 1, 0.76, 0.65}, {V_SMALL, 128, 128, 2, 0.75, 0.60}};
   int best = V_SMALL;
   double best_t = 1e300;
   for (const Cand &c : cands) {
     if (c.v == V_TALL && epilogue == EPI_QKV) continue;  // a wavefront must cover whole heads
     const long tiles = n_tiles(m, n_b_rows, c.bm, c.bn);
-    const long rounds = (tiles + n_cu - 1) / n_cu;
-    const double t = (double)rounds * c.bm * c.bn / c.q;
+    const long slots = (long)n_cu * c.per_cu;
+    const long full = tiles / slots, rem = tiles % slots;
+    const double t = (double)full * c.T + (rem ? c.T * (c.a + (1.0 - c.a) * (double)rem / (double)slots) : 0.0);
     if (t < best_t) { best_t = t; best = c.v; }
   }
   return best;
@@ -624,6 +629,8 @@ bool gemm_round_split(const GemmArgs &a, int epilogue, int dh, GemmArgs *head, G
   head->n_count = (int)cols_big * 128;
   tail->n_begin = a.n_begin + head->n_count;
   tail->n_count = n_cols - head->n_count;
+  head->tile_variant = V_BIG;
+  tail->tile_variant = V_SMALL;  // two workgroups per CU fill the chip best with what is left of a round
   return true;
 }
 
@@ -667,7 +674,8 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stre
     return hipErrorInvalidValue;
   if (a.n_count && epilogue != EPI_SWIGLU && epilogue != EPI_PLAIN) return hipErrorInvalidValue;
   const int n_cols = a.n_count ? a.n_count : a.N;
-  const int v = choose_variant(a.M, (epilogue == EPI_SWIGLU) ? 2 * n_cols : n_cols, epilogue, dh, a.n_cu);
+  const int v = a.tile_variant ? a.tile_variant
+                               : choose_variant(a.M, (epilogue == EPI_SWIGLU) ? 2 * n_cols : n_cols, epilogue, dh, a.n_cu);
   switch (epilogue) {
     case EPI_PLAIN: return launch_variant<EPI_PLAIN, 2, 4>(a, v, stream);
     case EPI_RESID: return launch_variant<EPI_RESID, 2, 4>(a, v, stream);

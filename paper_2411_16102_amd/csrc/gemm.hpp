@@ -23,6 +23,7 @@ struct GemmArgs {
   int M, N, K, lda, ldb;
   int n_cu;           // CUs the launch may use (0 = the whole chip); only steers the tile choice
   int n_begin, n_count;  // output columns [n_begin, n_begin + n_count) only (n_count = 0: all N); SWIGLU and PLAIN
+  int tile_variant;      // 0: chosen by the cost model; else that tile shape (set by gemm_round_split for its tail)
   uint16_t *C;        // output [M, ldc] bf16 (PLAIN, RESID*, SWIGLU)
   int ldc;
   const uint16_t *resid;  // [M, ldr] bf16
