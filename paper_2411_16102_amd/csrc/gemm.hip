@@ -209,10 +209,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   };
   auto next_slot = [](int s, int by) { s += by; return s >= NU ? s - NU : s; };
   static_assert(NU == 5, "the pipeline below is written for a ring of five panels");
-  // Software pipeline.  Panels are numbered in issue order, X(0) W(0) X(1) W(1) ..., and
+  // Software pipeline.  Panels are numbered in issue order, W(0) X(0) W(1) X(1) ..., and
   // panel u lives in ring slot u % 5.  Once the last fragments of tile kt are in
-  // registers, at the one barrier of the iteration, W(kt+2) and X(kt+3) are requested
-  // into the two slots that tile kt frees.  LDS -> registers: the fragments of the next
+  // registers, at the one barrier of the iteration, X(kt+2) and W(kt+3) are requested
+  // into the two slots that tile kt frees: the weight panel, which in a layer streams from
+  // HBM, gets the two k-tiles of look-ahead, and the activation panel, which the previous
+  // kernel has just left in the caches, gets one.  LDS -> registers: the fragments of the next
   // 32-wide k-step are requested while the MFMAs of the current one are issued, across
   // tile boundaries too, so the matrix pipe never waits for a whole LDS read phase.
   // The compiler counts an LDS-DMA load as a pending LDS operation of unknown order, so
@@ -225,18 +227,18 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   constexpr int PER_P = (N_P + NMF - 1) / NMF;
   bf16x8_t xa[MI], wa[NI], xb[MI], wb[NI];
 #pragma unroll
-  for (int i = 0; i < LA; ++i) dma_a(kt0, 0, i, Yes{});
+  for (int i = 0; i < LB; ++i) dma_b(kt0, 0, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LB; ++i) dma_b(kt0, 1, i, Yes{});
+  for (int i = 0; i < LA; ++i) dma_a(kt0, 1, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LA; ++i) dma_a(kt0 + 1, 2, i, Yes{});
+  for (int i = 0; i < LB; ++i) dma_b(kt0 + 1, 2, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LB; ++i) dma_b(kt0 + 1, 3, i, Yes{});
+  for (int i = 0; i < LA; ++i) dma_a(kt0 + 1, 3, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LA; ++i) dma_a(kt0 + 2, 4, i, Yes{});
-  __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LA + LB, true));  // tile 0 has landed
+  for (int i = 0; i < LB; ++i) dma_b(kt0 + 2, 4, i, Yes{});
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LB + LA, true));  // tile 0 has landed
   __builtin_amdgcn_s_barrier();
-  int sa = 0, sb = 1;  // slots of the tile being multiplied
+  int sb = 0, sa = 1;  // slots of the tile being multiplied: weights, activations
 #pragma unroll
   for (int o = 0; o < NF; ++o) frag(sa, sb, 0, o, xa, wa);
   auto tile = [&](int kt, auto checked) {
@@ -244,24 +246,24 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
     step(xa, wa, NF, PER_F, [&](int o) { frag(sa, sb, 1, o, xb, wb); });
     // Every fragment of tile kt is in registers once the LDS reads have returned, and
     // tile kt+1 has landed once this wavefront's loads other than the youngest panel,
-    // X(kt+2), are done; after the barrier both hold for every wavefront, so the two
+    // W(kt+2), are done; after the barrier both hold for every wavefront, so the two
     // slots of tile kt can be refilled and tile kt+1 can be read.
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(LA, true));
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(LB, true));
     __builtin_amdgcn_s_barrier();
     const int na = next_slot(sa, 2), nb = next_slot(sb, 2);
     step(xb, wb, N_P, PER_P, [&](int o) {
       if (o < NF)
         frag(na, nb, 0, o, xa, wa);
-      else if (o < NF + LB)
-        dma_b(kt + 2, sa, o - NF, checked);
+      else if (o < NF + LA)
+        dma_a(kt + 2, sb, o - NF, checked);
       else
-        dma_a(kt + 3, sb, o - NF - LB, checked);
+        dma_b(kt + 3, sa, o - NF - LA, checked);
     });
     sa = na;
     sb = nb;
   };
   int kt = kt0;
-  const int n_plain = a.K / BK - 3;  // tiles kt for which W(kt+2) and X(kt+3) lie wholly inside K
+  const int n_plain = a.K / BK - 3;  // tiles kt for which X(kt+2) and W(kt+3) lie wholly inside K
   for (; kt < n_plain && kt < kt1; ++kt) tile(kt, No{});
   for (; kt < kt1; ++kt) tile(kt, Yes{});
   // drain the look-ahead loads (zeros or clamped rows) before the LDS is released
