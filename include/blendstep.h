@@ -170,8 +170,10 @@ int bs_profile_enable(bs_ctx *ctx, int on);
 int bs_profile_read(bs_ctx *ctx, int which, double *total_ms, int64_t *launches);
 int bs_profile_reset(bs_ctx *ctx);
 
-/* Tuning knob: pages per chunk of decode-attention work (even, 2..64; default 32).
- * Smaller chunks give more parallelism and more partial states to merge. */
+/* Tuning knob: pages per chunk of decode-attention work (even, 2..64).  Smaller chunks give more
+ * parallelism and more partial states to merge.  Default: 64 for private tails and for prefix nodes
+ * whose work items carry at most 16 query rows, 32 for nodes with more (every chunk of such a node
+ * costs one partial state per member row); a call sets both. */
 int bs_set_chunk_pages(bs_ctx *ctx, int32_t pages);
 
 /* Tuning knob: CUs reserved for decode attention in the BS_FLAG_OVERLAP schedule (0, 64, 128 or

@@ -66,7 +66,9 @@ struct bs_ctx {
   int cus_a = 256, cus_b = 256;
   hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr;
   // tunables
-  int chunk_pages = 32;
+  int chunk_pages = 64;       // pages per chunk of decode-attention work: private tails and nodes with few member rows
+  int chunk_pages_wide = 32;  // nodes whose items carry more than 16 query rows: four wavefronts share an item, and every
+                              // chunk costs one partial state per member row
   // profiling
   bool prof = false;
   struct Span { hipEvent_t a, b; };
@@ -292,17 +294,19 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
     const int par = b->node_parent[n];
     const int np = b->node_page_start[n + 1] - b->node_page_start[n];
     const int above = par >= 0 ? c->path_chunks[par] : 0;
-    const int nch = (np + ch - 1) / ch;
-    c->path_chunks[n] = above + nch;
     const int cnt = b->node_seq_count[n];
+    const int n_groups = cnt > 0 ? (cnt + max_members - 1) / max_members : 1;
+    // the chunk size of a node is one for all its member groups: their partial states share slot numbers
+    const int chn = ((cnt + n_groups - 1) / n_groups) * grp > 16 ? c->chunk_pages_wide : ch;
+    const int nch = (np + chn - 1) / chn;
+    c->path_chunks[n] = above + nch;
     if (cnt <= 0 || np <= 0) continue;
-    const int n_groups = (cnt + max_members - 1) / max_members;
     for (int g = 0; g < n_groups; ++g) {
       const int lo = (int)((long)cnt * g / n_groups), hi = (int)((long)cnt * (g + 1) / n_groups);
       for (int k = 0; k < nch; ++k) {
         DecodeItem it{};
-        it.page_off = b->node_page_start[n] + k * ch;
-        it.n_tokens = std::min(ch, np - k * ch) * ps;
+        it.page_off = b->node_page_start[n] + k * chn;
+        it.n_tokens = std::min(chn, np - k * chn) * ps;
         it.seq_first = b->node_seq_first[n] + lo;
         it.n_members = hi - lo;
         it.slot_off = above + k;
@@ -466,8 +470,7 @@ int run_decode_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, 
   a.q = q; a.kv_pool = pool;
   a.part_acc = c->part_acc; a.part_m = c->part_m; a.part_l = c->part_l;
   SPAN(c, BS_K_ATTN_DECODE, st, {
-    HIP_TRY(c, launch_decode_attn(a, 0, p.n_wide, 4, st));
-    HIP_TRY(c, launch_decode_attn(a, p.n_wide, p.n_narrow, 1, st));
+    HIP_TRY(c, launch_decode_attn(a, p.n_wide, p.n_narrow, st));
   });
   MergeArgs m;
   m.s = a.s; m.n_prefill = p.n_prefill; m.n_decode = p.n_decode;
@@ -888,6 +891,7 @@ int bs_set_chunk_pages(bs_ctx *c, int32_t pages) {
   if (!c) return BS_EINVAL;
   if (pages < 2 || pages > 64 || (pages & 1)) return fail(c, BS_EINVAL, "chunk_pages %d (even, 2..64)", pages);
   c->chunk_pages = pages;
+  c->chunk_pages_wide = pages;
   return BS_OK;
 }
 

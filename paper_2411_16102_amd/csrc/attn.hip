@@ -50,16 +50,10 @@ __device__ __forceinline__ u32x2_t mask_tokens(u32x2_t v, int t0, int limit) {
 constexpr float TAU = 8.0f;
 
 template <int DH, int NQB>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NQB > 1 ? 1 : 2, NQB > 1 ? 1 : 2))) void decode_attn_kernel(const DecodeArgs a, int item_base, int n_units) {
+__device__ __forceinline__ void decode_unit(const DecodeArgs &a, int item, int kvh, int wave, int lane, uint16_t *q_sh) {
   constexpr int KC = DH / 32;  // 32-wide chunks of the head dimension (QK^T contraction)
   constexpr int DB = DH / 16;  // 16-row blocks of the head dimension (PV output rows)
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  const int unit = blockIdx.x * 4 + wave;
-  if (unit >= n_units) return;
   const int hkv = a.s.n_kv_heads, hq = a.s.n_q_heads, grp = hq / hkv;
-  const int item = item_base + unit / hkv;
-  const int kvh = unit % hkv;
   const DecodeItem it = a.items[item];
   const int n_rows = it.n_members * grp;
   const int n_tok = it.n_tokens;
@@ -74,7 +68,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NQB > 1 ? 1
   // wrote itself: no barrier is needed) and are fetched again for every pair of pages.
   constexpr bool Q_LDS = NQB > 1 && DH > 64;
   constexpr int QLD = DH + 8;  // padded row: 16-byte reads of 16 consecutive rows spread over all banks
-  __shared__ __align__(16) uint16_t q_sh[Q_LDS ? 4 * NQB * 16 * QLD : 8];
   bf16x8_t qf[Q_LDS ? 1 : NQB][Q_LDS ? 1 : KC];
   uint32_t q_off = (uint32_t)((wave * NQB * 16 + jq) * QLD + 8 * g4);
   bool row_ok[NQB];
@@ -248,6 +241,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NQB > 1 ? 1
         a.part_l[base] = ls;
       }
     }
+  }
+}
+
+// Items of more than 16 query rows come first in the item list and in the grid, so the few
+// long-running wavefronts that serve them start at once and the many single-block items fill
+// the rest of the chip beside them: one launch, one wavefront per SIMD for both kinds (the
+// single-block items stream as fast with one wavefront per SIMD as with two).
+template <int DH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_attn_kernel(const DecodeArgs a, int n_wide_units, int n_units) {
+  constexpr int WQB = 4;  // blocks of 16 query rows of a wide item
+  __shared__ __align__(16) uint16_t q_sh[DH > 64 ? 4 * WQB * 16 * (DH + 8) : 8];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int unit = blockIdx.x * 4 + wave;
+  if (unit >= n_units) return;
+  const int hkv = a.s.n_kv_heads;
+  if (unit < n_wide_units) {
+    decode_unit<DH, WQB>(a, unit / hkv, unit % hkv, wave, lane, q_sh);
+  } else {
+    const int u = unit - n_wide_units;
+    decode_unit<DH, 1>(a, n_wide_units / hkv + u / hkv, u % hkv, wave, lane, q_sh);
   }
 }
 
@@ -573,19 +587,15 @@ __global__ __launch_bounds__(256) void prefill_attn_kernel(const PrefillArgs a, 
 
 }  // namespace
 
-hipError_t launch_decode_attn(const DecodeArgs &a, int item_base, int n_items, int nqb, hipStream_t stream) {
-  const int n_units = n_items * a.s.n_kv_heads;
+hipError_t launch_decode_attn(const DecodeArgs &a, int n_wide, int n_narrow, hipStream_t stream) {
+  const int n_wide_units = n_wide * a.s.n_kv_heads;
+  const int n_units = n_wide_units + n_narrow * a.s.n_kv_heads;
   if (n_units <= 0) return hipSuccess;
   const dim3 grid((n_units + 3) / 4), block(256);
-  const int dh = a.s.head_dim;
-  if (dh == 128 && nqb == 1)
-    hipLaunchKernelGGL((decode_attn_kernel<128, 1>), grid, block, 0, stream, a, item_base, n_units);
-  else if (dh == 128 && nqb == 4)
-    hipLaunchKernelGGL((decode_attn_kernel<128, 4>), grid, block, 0, stream, a, item_base, n_units);
-  else if (dh == 64 && nqb == 1)
-    hipLaunchKernelGGL((decode_attn_kernel<64, 1>), grid, block, 0, stream, a, item_base, n_units);
-  else if (dh == 64 && nqb == 4)
-    hipLaunchKernelGGL((decode_attn_kernel<64, 4>), grid, block, 0, stream, a, item_base, n_units);
+  if (a.s.head_dim == 128)
+    hipLaunchKernelGGL((decode_attn_kernel<128>), grid, block, 0, stream, a, n_wide_units, n_units);
+  else if (a.s.head_dim == 64)
+    hipLaunchKernelGGL((decode_attn_kernel<64>), grid, block, 0, stream, a, n_wide_units, n_units);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

@@ -36,8 +36,8 @@ struct DecodeArgs {
   float *part_m, *part_l;     // [slots][Hq]
 };
 
-// items [item_base, item_base + n_items) each hold at most 16 * nqb query rows (nqb = 1 or 4)
-hipError_t launch_decode_attn(const DecodeArgs &a, int item_base, int n_items, int nqb, hipStream_t stream);
+// one launch over items [0, n_wide) of up to 64 query rows each, then [n_wide, n_wide + n_narrow) of up to 16
+hipError_t launch_decode_attn(const DecodeArgs &a, int n_wide, int n_narrow, hipStream_t stream);
 
 struct MergeArgs {
   AttnShape s;
