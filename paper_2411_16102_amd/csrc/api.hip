@@ -394,6 +394,11 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
   if (p.n_narrow) std::memcpy(&blob[p.off_items + 8L * p.n_wide], c->items.data(), sizeof(DecodeItem) * p.n_narrow);
   if (p.total_node_pages) std::memcpy(&blob[p.off_pages], b->node_page_ids, sizeof(int32_t) * p.total_node_pages);
   if (n_tab) std::memcpy(&blob[p.off_pages + p.total_node_pages], b->page_ids, sizeof(int32_t) * n_tab);
+  for (long i = 0; i < n_items; ++i) {  // every item has at least one token, hence one page
+    DecodeItem *it = reinterpret_cast<DecodeItem *>(&blob[p.off_items + 8 * i]);
+    it->page0 = blob[p.off_pages + it->page_off];
+    it->page1 = blob[p.off_pages + it->page_off + (it->n_tokens > ps ? 1 : 0)];
+  }
   return BS_OK;
 }
 
@@ -466,7 +471,7 @@ int run_decode_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, 
   a.s = attn_shape(c);
   a.items = reinterpret_cast<const DecodeItem *>(c->d_blob + p.off_items);
   a.item_pages = c->d_blob + p.off_pages;
-  a.row_start = c->d_blob + p.off_row_start; a.part_start = c->d_blob + p.off_part_start;
+  a.row_base = p.n_prefill_rows - p.n_prefill; a.part_start = c->d_blob + p.off_part_start;
   a.q = q; a.kv_pool = pool;
   a.part_acc = c->part_acc; a.part_m = c->part_m; a.part_l = c->part_l;
   SPAN(c, BS_K_ATTN_DECODE, st, {
@@ -474,7 +479,7 @@ int run_decode_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, 
   });
   MergeArgs m;
   m.s = a.s; m.n_prefill = p.n_prefill; m.n_decode = p.n_decode;
-  m.row_start = a.row_start; m.part_start = a.part_start;
+  m.row_start = c->d_blob + p.off_row_start; m.part_start = a.part_start;
   m.part_acc = c->part_acc; m.part_m = c->part_m; m.part_l = c->part_l; m.out = out;
   SPAN(c, BS_K_ATTN_MERGE, st, HIP_TRY(c, launch_decode_merge(m, st)));
   return BS_OK;

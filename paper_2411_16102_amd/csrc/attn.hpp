@@ -16,7 +16,8 @@ struct DecodeItem {
   int32_t seq_first;  // first member sequence
   int32_t n_members;  // member sequences (n_members * group <= 16 * nqb query rows of the launch)
   int32_t slot_off;   // partial-state slot of this chunk inside every member's slot range
-  int32_t pad[3];
+  int32_t page0, page1;  // pool pages of the chunk's first two pages (page1 = page0 in a chunk of one page)
+  int32_t pad;
 };
 
 struct AttnShape {
@@ -28,7 +29,7 @@ struct DecodeArgs {
   AttnShape s;
   const DecodeItem *items;
   const int32_t *item_pages;
-  const int32_t *row_start;   // [n_seq + 1]
+  int row_base;               // row of decode sequence s = s + row_base (one row each, after the prefill rows)
   const int32_t *part_start;  // [n_seq + 1] partial-state slots of each sequence
   const uint16_t *q;          // [T, Hq*dh]
   const uint16_t *kv_pool;
