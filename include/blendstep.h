@@ -163,7 +163,10 @@ int bs_resolve_rows(bs_ctx *ctx, const bs_batch *batch, int32_t *page_out, int32
 /* Per-kernel timing.  With profiling on, bs_blend_step brackets each kernel
  * class with HIP events on the stream it runs on; bs_profile_read waits for the
  * recorded events and returns the accumulated milliseconds and launch count of
- * class `which` since the last reset.  Off by default (events cost time). */
+ * class `which` since the last reset.  Off by default (events cost time).
+ * In the serial schedule a step with prefill and decode rows runs both kinds of
+ * attention as one launch, booked under BS_K_ATTN_DECODE (BS_K_ATTN_PREFILL
+ * then has no launches). */
 enum { BS_K_PREP = 0, BS_K_GEMM_QKV, BS_K_ATTN_PREFILL, BS_K_ATTN_DECODE, BS_K_ATTN_MERGE,
        BS_K_GEMM_O, BS_K_GEMM_GATE_UP, BS_K_GEMM_DOWN, BS_K_COUNT };
 int bs_profile_enable(bs_ctx *ctx, int on);

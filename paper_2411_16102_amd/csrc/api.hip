@@ -453,20 +453,17 @@ AttnShape attn_shape(const bs_ctx *c) {
   return s;
 }
 
-int run_prefill_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, const uint16_t *pool, hipStream_t st) {
-  if (p.n_pf_work == 0) return BS_OK;
+PrefillArgs prefill_args(const bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, const uint16_t *pool) {
   PrefillArgs a;
   a.s = attn_shape(c);
   a.work = c->d_blob + p.off_pf_work; a.n_work = p.n_pf_work;
   a.row_start = c->d_blob + p.off_row_start; a.kv_len = c->d_blob + p.off_kv_len;
   a.page_start = c->d_blob + p.off_page_start; a.page_ids = c->d_blob + p.off_pages + p.total_node_pages;
   a.q = q; a.kv_pool = pool; a.out = out;
-  SPAN(c, BS_K_ATTN_PREFILL, st, HIP_TRY(c, launch_prefill_attn(a, st)));
-  return BS_OK;
+  return a;
 }
 
-int run_decode_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, const uint16_t *pool, hipStream_t st) {
-  if (p.n_decode == 0) return BS_OK;
+DecodeArgs decode_args(const bs_ctx *c, const Plan &p, const uint16_t *q, const uint16_t *pool) {
   DecodeArgs a;
   a.s = attn_shape(c);
   a.items = reinterpret_cast<const DecodeItem *>(c->d_blob + p.off_items);
@@ -474,15 +471,43 @@ int run_decode_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, 
   a.row_base = p.n_prefill_rows - p.n_prefill; a.part_start = c->d_blob + p.off_part_start;
   a.q = q; a.kv_pool = pool;
   a.part_acc = c->part_acc; a.part_m = c->part_m; a.part_l = c->part_l;
-  SPAN(c, BS_K_ATTN_DECODE, st, {
-    HIP_TRY(c, launch_decode_attn(a, p.n_wide, p.n_narrow, st));
-  });
+  return a;
+}
+
+int run_prefill_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, const uint16_t *pool, hipStream_t st) {
+  if (p.n_pf_work == 0) return BS_OK;
+  const PrefillArgs a = prefill_args(c, p, q, out, pool);
+  SPAN(c, BS_K_ATTN_PREFILL, st, HIP_TRY(c, launch_prefill_attn(a, st)));
+  return BS_OK;
+}
+
+int run_decode_merge(bs_ctx *c, const Plan &p, uint16_t *out, hipStream_t st) {
   MergeArgs m;
-  m.s = a.s; m.n_prefill = p.n_prefill; m.n_decode = p.n_decode;
-  m.row_start = c->d_blob + p.off_row_start; m.part_start = a.part_start;
+  m.s = attn_shape(c); m.n_prefill = p.n_prefill; m.n_decode = p.n_decode;
+  m.row_start = c->d_blob + p.off_row_start; m.part_start = c->d_blob + p.off_part_start;
   m.part_acc = c->part_acc; m.part_m = c->part_m; m.part_l = c->part_l; m.out = out;
   SPAN(c, BS_K_ATTN_MERGE, st, HIP_TRY(c, launch_decode_merge(m, st)));
   return BS_OK;
+}
+
+int run_decode_attn(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, const uint16_t *pool, hipStream_t st) {
+  if (p.n_decode == 0) return BS_OK;
+  const DecodeArgs a = decode_args(c, p, q, pool);
+  SPAN(c, BS_K_ATTN_DECODE, st, HIP_TRY(c, launch_decode_attn(a, p.n_wide, p.n_narrow, st)));
+  return run_decode_merge(c, p, out, st);
+}
+
+// Attention of a whole step on one stream: prefill and decode rows in one launch where the step
+// has both (its time is booked under the decode class), else the launch of the kind it has.
+int run_attention(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, const uint16_t *pool, hipStream_t st) {
+  if (p.n_pf_work == 0 || p.n_decode == 0 || !blended_attn_possible(attn_shape(c))) {
+    int rc = run_prefill_attn(c, p, q, out, pool, st);
+    return rc ? rc : run_decode_attn(c, p, q, out, pool, st);
+  }
+  const PrefillArgs pf = prefill_args(c, p, q, out, pool);
+  const DecodeArgs d = decode_args(c, p, q, pool);
+  SPAN(c, BS_K_ATTN_DECODE, st, HIP_TRY(c, launch_blended_attn(d, p.n_wide, p.n_narrow, pf, st)));
+  return run_decode_merge(c, p, out, st);
 }
 
 // output projection (+ first residual, second norm) and gate/up (+ SwiGLU) for rows [r0, r1)
@@ -721,8 +746,7 @@ int run_layer(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, 
 
   const bool overlap = (flags & BS_FLAG_OVERLAP) && p.n_decode > 0 && p.n_prefill_rows > 0;
   if (!overlap) {
-    if ((rc = run_prefill_attn(c, p, c->qbuf, c->attn, pool, st))) return rc;
-    if ((rc = run_decode_attn(c, p, c->qbuf, c->attn, pool, st))) return rc;
+    if ((rc = run_attention(c, p, c->qbuf, c->attn, pool, st))) return rc;
     if ((rc = run_o_gate_up(c, w, x, 0, T, st, 0))) return rc;
     if ((rc = run_down(c, w, y, 0, T, st, 0))) return rc;
   } else {
@@ -817,8 +841,7 @@ int bs_attention(bs_ctx *c, const bs_batch *b, const void *q, void *out, const v
   if ((rc = build_plan(c, b, p, false))) return rc;
   if ((rc = ensure_slots(c, p.n_slots))) return rc;
   if ((rc = upload_plan(c, p, st))) return rc;
-  if ((rc = run_prefill_attn(c, p, (const uint16_t *)q, (uint16_t *)out, (const uint16_t *)pool, st))) return rc;
-  if ((rc = run_decode_attn(c, p, (const uint16_t *)q, (uint16_t *)out, (const uint16_t *)pool, st))) return rc;
+  if ((rc = run_attention(c, p, (const uint16_t *)q, (uint16_t *)out, (const uint16_t *)pool, st))) return rc;
   return BS_OK;
 }
 

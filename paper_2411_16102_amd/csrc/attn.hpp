@@ -60,4 +60,9 @@ struct PrefillArgs {
 };
 hipError_t launch_prefill_attn(const PrefillArgs &a, hipStream_t stream);
 
+// both kinds in one launch (prefill workgroups dealt evenly among the decode ones); needs a step with
+// prefill work and decode items, and a group size that is a multiple of four
+bool blended_attn_possible(const AttnShape &s);
+hipError_t launch_blended_attn(const DecodeArgs &d, int n_wide, int n_narrow, const PrefillArgs &pf, hipStream_t stream);
+
 }  // namespace bs

@@ -149,6 +149,28 @@ def test_attention_node_member_counts(lib, shape, members):
     assert maxrel <= MAXREL and mae <= 2 * MAE
 
 
+@pytest.mark.parametrize("root_pages,n_members", [(20, 40), (14, 41)])
+def test_attention_wide_items_alternate_with_narrow_ones(lib, root_pages, n_members):
+    # one long shared root cut into chunks of two pages, short private tails: the workgroups of
+    # 64-row items are more than a third of the launch, so the grid takes its mixed order (some
+    # wide workgroups ahead, then one wide and two narrow in turn, then what is left)
+    import torch
+    shape = W.LayerShape(512, 8, 2, 128, 256)
+    rng = np.random.default_rng(root_pages * 100 + n_members)
+    nodes = [(-1, root_pages)]
+    seqs = [(7, 40, -1)] + [(1, 16 * root_pages + 1 + int(rng.integers(0, 30)), 0) for _ in range(n_members)]
+    batch = W.assemble_batch(16, seqs, 1, nodes, rng)
+    tens = W.make_tensors(shape, batch, 11)
+    q = W.round_to_bf16(rng.standard_normal((batch.n_rows, shape.n_q_heads * shape.head_dim), dtype=np.float32))
+    layer = lib.Layer(shape, device=0)
+    layer.set_chunk_pages(2)
+    pool = layer.pack_pool(tens.k_pool, tens.v_pool)
+    out = to_np(layer.attention(batch, torch.from_numpy(q).cuda().to(torch.bfloat16), pool, batch.n_pages))
+    ref = attention_reference(shape, batch, q.astype(np.float64), tens.k_pool, tens.v_pool)
+    maxrel, mae = errs(out, ref)
+    assert maxrel <= MAXREL and mae <= 2 * MAE
+
+
 def test_attention_ignores_stale_slots(lib):
     # slots past kv_len in the last page hold NaN bit patterns: they must never reach the output
     import torch
