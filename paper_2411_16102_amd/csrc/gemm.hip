@@ -75,16 +75,21 @@ constexpr int waitcnt_imm(int vm, bool lgkm0) {
   return (vm & 0xF) | ((vm >> 4) << 14) | 0x70 | (lgkm0 ? 0 : 0xF00);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH, int DEEP = 0>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
   constexpr int NW = WAVES_M * WAVES_N;
+  // DEEP: the pipeline for one round of tiles over few rows, where every CU streams a weight
+  // panel of its own from HBM; the first half of the wavefronts requests the activation
+  // panels, the second half the weight panels (see the pipeline below)
+  constexpr int XW = DEEP ? NW / 2 : NW, WW = DEEP ? NW / 2 : NW;  // wavefronts that share the loads of a panel
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int MI = WTM / 16, NI = WTN / 16;  // 16x16 accumulator blocks of a wavefront's tile
   constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   constexpr int ROWB = BK * 2;                       // bytes of one tile row
   constexpr int UNIT = (BM > BN ? BM : BN) * ROWB;   // one ring unit holds either panel
   constexpr int GA = BM / 8, GB = BN / 8;            // 8-row groups = one 1 KB wavefront load each
-  constexpr int LA = (GA + NW - 1) / NW, LB = (GB + NW - 1) / NW;  // loads per thread per panel
+  constexpr int LA = (GA + XW - 1) / XW, LB = (GB + WW - 1) / WW;  // loads per thread per panel
+  static_assert(!DEEP || NW % 2 == 0, "two halves of the workgroup share the loads");
   static_assert(BK == 64, "swizzle and fragment addressing assume 128-byte tile rows");
   static_assert(WTM % 16 == 0 && WTN % 16 == 0, "tiles are made of 16x16 MFMA blocks");
   static_assert(EPI != EPI_SWIGLU || WTN % 64 == 0, "32 gate rows and their 32 up rows pair up inside a wave");
@@ -123,7 +128,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   for (int i = 0; i < LA; ++i) {
     // when the groups do not divide over the wavefronts the surplus loads repeat the last
     // group (same bytes to the same place), so every wavefront issues LA loads per panel
-    const int grp = (wave + i * NW) < GA ? (wave + i * NW) : GA - 1;
+    const int grp = (wave % XW + i * XW) < GA ? (wave % XW + i * XW) : GA - 1;
     const int row = grp * 8 + g_row;
     const int chunk = g_slot ^ ((row >> 1) & 7);
     ka[i] = chunk * 8;
@@ -134,7 +139,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   }
 #pragma unroll
   for (int i = 0; i < LB; ++i) {
-    const int grp = (wave + i * NW) < GB ? (wave + i * NW) : GB - 1;
+    const int grp = (wave % WW + i * WW) < GB ? (wave % WW + i * WW) : GB - 1;
     const int wr = grp * 8 + g_row;
     const int chunk = g_slot ^ ((wr >> 1) & 7);
     kb[i] = chunk * 8;
@@ -152,19 +157,19 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
     off_b[i] = (uint32_t)(((size_t)gn * a.ldb + chunk * 8) * 2);
   }
   // load number i of panel X(kt) / W(kt) into ring slot `slot`; `checked` handles chunks past K
-  auto dma_a = [&](int kt, int slot, int i, auto checked) {
+  auto dma_a = [&](int kt, int lds_off, int i, auto checked) {
     const unsigned char *base = reinterpret_cast<const unsigned char *>(a.A) + (size_t)kt * ROWB;
     const void *p = base + off_a[i];
     if constexpr (decltype(checked)::value)
       if (kt * BK + ka[i] >= a.K) p = g_gemm_zero_chunk;
-    __builtin_amdgcn_global_load_lds(p, (__attribute__((address_space(3))) void *)(smem + slot * UNIT + dst_a[i]), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(p, (__attribute__((address_space(3))) void *)(smem + lds_off + dst_a[i]), 16, 0, 0);
   };
-  auto dma_b = [&](int kt, int slot, int i, auto checked) {
+  auto dma_b = [&](int kt, int lds_off, int i, auto checked) {
     const unsigned char *base = reinterpret_cast<const unsigned char *>(a.B) + (size_t)kt * ROWB;
     const void *p = base + off_b[i];
     if constexpr (decltype(checked)::value)
       if (kt * BK + kb[i] >= a.K) p = g_gemm_zero_chunk;
-    __builtin_amdgcn_global_load_lds(p, (__attribute__((address_space(3))) void *)(smem + slot * UNIT + dst_b[i]), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(p, (__attribute__((address_space(3))) void *)(smem + lds_off + dst_b[i]), 16, 0, 0);
   };
 
   f32x4_t acc[NI][MI];
@@ -185,12 +190,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   constexpr int NF = MI + NI;   // fragment reads per 32-wide k-step
   constexpr int NMF = MI * NI;  // MFMAs per 32-wide k-step
   // read number o of k-step ks (32 wide, two per tile) of the panels in ring slots sa, sb
-  auto frag = [&](int sa, int sb, int ks, int o, bf16x8_t (&xf)[MI], bf16x8_t (&wf)[NI]) {
+  // (xo, wo: LDS byte offsets of the two panels)
+  auto frag = [&](int xo, int wo, int ks, int o, bf16x8_t (&xf)[MI], bf16x8_t (&wf)[NI]) {
     const int ch = ((ks * 4 + lg) ^ sw) << 4;
     if (o < MI)
-      xf[o] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(smem + sa * UNIT + xfrag + o * 16 * ROWB + ch));
+      xf[o] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(smem + xo + xfrag + o * 16 * ROWB + ch));
     else
-      wf[o - MI] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(smem + sb * UNIT + wfrag + (o - MI) * 16 * ROWB + ch));
+      wf[o - MI] = as_bf16x8(*reinterpret_cast<const u32x4_t *>(smem + wo + wfrag + (o - MI) * 16 * ROWB + ch));
   };
   // One k-step: its NMF MFMAs in program order, with the `n_ops` side operations (LDS
   // reads of the next k-step, DMA requests) dealt out behind the first MFMAs, `per` at a
@@ -225,47 +231,118 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   constexpr int PER_F = (NF + NMF - 1) / NMF;  // side operations per MFMA: one is enough where a step has 32 MFMAs
   constexpr int N_P = NF + LB + LA;
   constexpr int PER_P = (N_P + NMF - 1) / NMF;
+  (void)N_P; (void)PER_P;
   bf16x8_t xa[MI], wa[NI], xb[MI], wb[NI];
+  if constexpr (!DEEP) {
 #pragma unroll
-  for (int i = 0; i < LB; ++i) dma_b(kt0, 0, i, Yes{});
+    for (int i = 0; i < LB; ++i) dma_b(kt0, 0 * UNIT, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LA; ++i) dma_a(kt0, 1, i, Yes{});
+    for (int i = 0; i < LA; ++i) dma_a(kt0, 1 * UNIT, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LB; ++i) dma_b(kt0 + 1, 2, i, Yes{});
+    for (int i = 0; i < LB; ++i) dma_b(kt0 + 1, 2 * UNIT, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LA; ++i) dma_a(kt0 + 1, 3, i, Yes{});
+    for (int i = 0; i < LA; ++i) dma_a(kt0 + 1, 3 * UNIT, i, Yes{});
 #pragma unroll
-  for (int i = 0; i < LB; ++i) dma_b(kt0 + 2, 4, i, Yes{});
-  __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LB + LA, true));  // tile 0 has landed
-  __builtin_amdgcn_s_barrier();
-  int sb = 0, sa = 1;  // slots of the tile being multiplied: weights, activations
-#pragma unroll
-  for (int o = 0; o < NF; ++o) frag(sa, sb, 0, o, xa, wa);
-  auto tile = [&](int kt, auto checked) {
-    __builtin_amdgcn_s_waitcnt(LGKM0);
-    step(xa, wa, NF, PER_F, [&](int o) { frag(sa, sb, 1, o, xb, wb); });
-    // Every fragment of tile kt is in registers once the LDS reads have returned, and
-    // tile kt+1 has landed once this wavefront's loads other than the youngest panel,
-    // W(kt+2), are done; after the barrier both hold for every wavefront, so the two
-    // slots of tile kt can be refilled and tile kt+1 can be read.
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(LB, true));
+    for (int i = 0; i < LB; ++i) dma_b(kt0 + 2, 4 * UNIT, i, Yes{});
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * LB + LA, true));  // tile 0 has landed
     __builtin_amdgcn_s_barrier();
-    const int na = next_slot(sa, 2), nb = next_slot(sb, 2);
-    step(xb, wb, N_P, PER_P, [&](int o) {
-      if (o < NF)
-        frag(na, nb, 0, o, xa, wa);
-      else if (o < NF + LA)
-        dma_a(kt + 2, sb, o - NF, checked);
+    int sb = 0, sa = 1;  // slots of the tile being multiplied: weights, activations
+#pragma unroll
+    for (int o = 0; o < NF; ++o) frag(sa * UNIT, sb * UNIT, 0, o, xa, wa);
+    auto tile = [&](int kt, auto checked) {
+      __builtin_amdgcn_s_waitcnt(LGKM0);
+      step(xa, wa, NF, PER_F, [&](int o) { frag(sa * UNIT, sb * UNIT, 1, o, xb, wb); });
+      // Every fragment of tile kt is in registers once the LDS reads have returned, and
+      // tile kt+1 has landed once this wavefront's loads other than the youngest panel,
+      // W(kt+2), are done; after the barrier both hold for every wavefront, so the two
+      // slots of tile kt can be refilled and tile kt+1 can be read.
+      __builtin_amdgcn_s_waitcnt(waitcnt_imm(LB, true));
+      __builtin_amdgcn_s_barrier();
+      const int na = next_slot(sa, 2), nb = next_slot(sb, 2);
+      step(xb, wb, N_P, PER_P, [&](int o) {
+        if (o < NF)
+          frag(na * UNIT, nb * UNIT, 0, o, xa, wa);
+        else if (o < NF + LA)
+          dma_a(kt + 2, sb * UNIT, o - NF, checked);
+        else
+          dma_b(kt + 3, sa * UNIT, o - NF - LA, checked);
+      });
+      sa = na;
+      sb = nb;
+    };
+    int kt = kt0;
+    const int n_plain = a.K / BK - 3;  // tiles kt for which X(kt+2) and W(kt+3) lie wholly inside K
+    for (; kt < n_plain && kt < kt1; ++kt) tile(kt, No{});
+    for (; kt < kt1; ++kt) tile(kt, Yes{});
+  } else {
+    // One round of tiles over few rows: every CU streams a weight panel of its own from HBM,
+    // and what bounds the kernel is how many bytes of it are in flight.  LDS holds two slots
+    // for the activation panel (shared by all tiles, served by the L2: one k-tile of
+    // look-ahead) and all the rest, NWS slots, for the weight panel: NWS - 1 k-tiles of
+    // look-ahead.  The memory counter of a wavefront retires its loads in order, so a wait for
+    // an activation panel would also wait for every weight panel requested before it; the two
+    // kinds of request therefore come from different wavefronts: the first half of the
+    // workgroup loads activations and waits for all of its loads, the second half loads
+    // weights and waits until only the NWS - 2 youngest panels are outstanding.
+    constexpr int UX = BM * ROWB, UW = BN * ROWB, W_BASE = 2 * UX;
+    constexpr int NWS = (160 * 1024 - W_BASE) / UW;
+    static_assert(NWS >= 3 && (NWS - 1) * LB < 64, "weight slots and the vmcnt field");
+    const bool loads_x = wave < XW;  // uniform
+    if (loads_x) {
+#pragma unroll
+      for (int i = 0; i < LA; ++i) dma_a(kt0, 0, i, Yes{});
+#pragma unroll
+      for (int i = 0; i < LA; ++i) dma_a(kt0 + 1, UX, i, Yes{});
+      __builtin_amdgcn_s_waitcnt(waitcnt_imm(LA, true));
+    } else {
+#pragma unroll
+      for (int sl = 0; sl < NWS; ++sl)
+#pragma unroll
+        for (int i = 0; i < LB; ++i) dma_b(kt0 + sl, W_BASE + sl * UW, i, Yes{});
+      __builtin_amdgcn_s_waitcnt(waitcnt_imm((NWS - 1) * LB, true));
+    }
+    __builtin_amdgcn_s_barrier();  // tile 0 has landed
+    int xo = 0, ws = 0;            // activation slot offset and weight slot number of the tile being multiplied
+#pragma unroll
+    for (int o = 0; o < NF; ++o) frag(xo, W_BASE + ws * UW, 0, o, xa, wa);
+    constexpr int N_X = NF + LA, N_W = NF + LB;
+    constexpr int PER_X = (N_X + NMF - 1) / NMF, PER_W = (N_W + NMF - 1) / NMF;
+    auto tile = [&](int kt, auto checked) {
+      const int wo = W_BASE + ws * UW;
+      __builtin_amdgcn_s_waitcnt(LGKM0);
+      step(xa, wa, NF, PER_F, [&](int o) { frag(xo, wo, 1, o, xb, wb); });
+      // after the barrier: every wavefront holds all fragments of tile kt, X(kt+1) has landed
+      // (the activation half waited for all its loads) and so has W(kt+1) (the weight half
+      // waited until only W(kt+2) .. W(kt+NWS-1) were outstanding)
+      if (loads_x)
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
       else
-        dma_b(kt + 3, sa, o - NF - LA, checked);
-    });
-    sa = na;
-    sb = nb;
-  };
-  int kt = kt0;
-  const int n_plain = a.K / BK - 3;  // tiles kt for which X(kt+2) and W(kt+3) lie wholly inside K
-  for (; kt < n_plain && kt < kt1; ++kt) tile(kt, No{});
-  for (; kt < kt1; ++kt) tile(kt, Yes{});
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm((NWS - 2) * LB, true));
+      __builtin_amdgcn_s_barrier();
+      const int nxo = xo ^ UX, nws = ws + 1 == NWS ? 0 : ws + 1;
+      const int nwo = W_BASE + nws * UW;
+      if (loads_x)
+        step(xb, wb, N_X, PER_X, [&](int o) {
+          if (o < NF)
+            frag(nxo, nwo, 0, o, xa, wa);
+          else
+            dma_a(kt + 2, xo, o - NF, checked);
+        });
+      else
+        step(xb, wb, N_W, PER_W, [&](int o) {
+          if (o < NF)
+            frag(nxo, nwo, 0, o, xa, wa);
+          else
+            dma_b(kt + NWS, wo, o - NF, checked);
+        });
+      xo = nxo;
+      ws = nws;
+    };
+    int kt = kt0;
+    const int n_plain = a.K / BK - NWS;  // tiles kt for which X(kt+2) and W(kt+NWS) lie wholly inside K
+    for (; kt < n_plain && kt < kt1; ++kt) tile(kt, No{});
+    for (; kt < kt1; ++kt) tile(kt, Yes{});
+  }
   // drain the look-ahead loads (zeros or clamped rows) before the LDS is released
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
 
@@ -552,11 +629,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_qkv_kernel(const GemmArgs a
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH, int DEEP = 0>
 hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
   constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  constexpr int LDS = NU * (BM > BN ? BM : BN) * BK * 2;
-  auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI, DH>;
+  constexpr int LDS = DEEP ? 160 * 1024 : NU * (BM > BN ? BM : BN) * BK * 2;
+  auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI, DH, DEEP>;
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -574,7 +651,8 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
 // Tile shapes.  BIG: 256x256, 8 wavefronts.  TALL: 160x256, 8 wavefronts of 80x64: 2560 (and
 // 5120) rows by 4096 (8192) columns then make exactly one (four) full rounds of 256
 // workgroups where 256x256 tiles leave 38 % (17 %) of the CUs idle.  SMALL: 128x128.
-enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3 };
+// S128 / S256: 128x256 and 256x128 tiles on the deep weight ring, for at most 128 / 256 rows.
+enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3, V_S128 = 4, V_S256 = 5 };
 constexpr int N_CU = 256;
 
 int g_forced_variant = V_AUTO;
@@ -587,10 +665,20 @@ long n_tiles(int m, int n, int bm, int bn) { return (long)((m + bm - 1) / bm) * 
 // proportion.  T and a were fitted on MI355X to the four GEMM shapes of the 8B layer at 384 to
 // 2560 rows (the 160x256 tile: 0.072 ms per full round at K = 4096 where the 256x256 tile takes
 // 0.100 and 512 tiles of 128x128 take 0.075).
+// few rows: one tile row on the deep weight ring (0 where the rows do not fit one tile, or a shape is forced)
+int short_variant(int m) {
+  if (g_forced_variant != V_AUTO || m > 256) return 0;
+  return m <= 128 ? V_S128 : V_S256;
+}
+
 int choose_variant(int m, int n_b_rows, int epilogue, int dh, int n_cu) {
   if (n_cu <= 0) n_cu = N_CU;
   if (g_forced_variant != V_AUTO && !(g_forced_variant == V_TALL && epilogue == EPI_QKV)) return g_forced_variant;
   (void)dh;
+  if (const int sv = short_variant(m); sv && (epilogue == EPI_SWIGLU || epilogue == EPI_PLAIN)) {
+    // worth it once the single row of tiles fills at least half the chip
+    if (2 * n_tiles(m, n_b_rows, sv == V_S128 ? 128 : 256, sv == V_S128 ? 256 : 128) >= n_cu) return sv;
+  }
   struct Cand { int v, bm, bn, per_cu; double T, a; };
   const Cand cands[3] = {{V_BIG, 256, 256, 1, 1.00, 0.72}, {V_TALL, 160, 256, 1, 0.76, 0.65}, {V_SMALL, 128, 128, 2, 0.75, 0.60}};
   int best = V_SMALL;
@@ -610,6 +698,10 @@ template <int EPI, int DH_BIG_M, int DH_BIG_N>
 hipError_t launch_variant(const GemmArgs &a, int v, hipStream_t stream) {
   if (v == V_BIG) return launch_one<256, 256, DH_BIG_M, DH_BIG_N, EPI, (DH_BIG_M == 4 ? 128 : 64)>(a, stream);
   if (v == V_TALL) return launch_one<160, 256, 2, 4, EPI, 64>(a, stream);
+  if constexpr (EPI == EPI_SWIGLU || EPI == EPI_PLAIN) {
+    if (v == V_S128) return launch_one<128, 256, 2, 4, EPI, 64, 1>(a, stream);
+    if (v == V_S256) return launch_one<256, 128, 4, 2, EPI, 64, 1>(a, stream);
+  }
   return launch_one<128, 128, 2, 2, EPI, 64>(a, stream);
 }
 
@@ -639,10 +731,15 @@ bool gemm_round_split(const GemmArgs &a, int epilogue, int dh, GemmArgs *head, G
 int gemm_splitk_choice(int M, int N, int K, int epilogue, int n_cu) {
   if (epilogue != EPI_RESID && epilogue != EPI_RESID_NORM && epilogue != EPI_QKV) return 1;
   if (n_cu <= 0) n_cu = N_CU;
+  const long by_k = ((K + BK - 1) / BK) / 8;    // at least eight k-tiles per range
+  if (const int sv = short_variant(M)) {        // one workgroup per CU, each with a k-range of a one-row tile
+    const long tiles = n_tiles(M, N, sv == V_S128 ? 128 : 256, sv == V_S128 ? 256 : 128);
+    const long s = std::min((long)MAX_SPLITS, std::min((long)n_cu / tiles, by_k));
+    return s >= 2 ? (int)s : 1;
+  }
   if (choose_variant(M, N, epilogue, 64, n_cu) != V_SMALL) return 1;  // only where the smallest tile is already in use
   const long tiles = n_tiles(M, N, 128, 128);
   const long room = 2L * n_cu / tiles;          // two 128x128 workgroups fit one CU
-  const long by_k = ((K + BK - 1) / BK) / 8;    // at least eight k-tiles per range
   const long s = std::min((long)MAX_SPLITS, std::min(room, by_k));
   return s >= 2 ? (int)s : 1;
 }
@@ -658,7 +755,10 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stre
   if (a.k_splits > 1) {
     if ((epilogue != EPI_RESID && epilogue != EPI_RESID_NORM && epilogue != EPI_QKV) || !a.splitk_ws || a.N % 4)
       return hipErrorInvalidValue;
-    hipError_t e = launch_one<128, 128, 2, 2, EPI_PARTIAL, 64>(a, stream);
+    const int sv = short_variant(a.M);
+    hipError_t e = sv == V_S128   ? launch_one<128, 256, 2, 4, EPI_PARTIAL, 64, 1>(a, stream)
+                   : sv == V_S256 ? launch_one<256, 128, 4, 2, EPI_PARTIAL, 64, 1>(a, stream)
+                                  : launch_one<128, 128, 2, 2, EPI_PARTIAL, 64>(a, stream);
     if (e != hipSuccess) return e;
     if (epilogue == EPI_QKV) {
       const int items = ((a.n_q_heads + a.n_kv_heads) * (dh / 2) + a.n_kv_heads * dh) / 4;

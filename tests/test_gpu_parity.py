@@ -68,7 +68,9 @@ def check_step(lib, shape, batch, tens, flags=0, mae_tol=MAE):
 # ---------------------------------------------------------------------------
 # stand-alone operators
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("m,n,k", [(136, 512, 256), (300, 264, 688), (1, 8, 8), (1030, 1544, 520), (2048, 1024, 512)])
+@pytest.mark.parametrize("m,n,k", [(136, 512, 256), (300, 264, 688), (1, 8, 8), (1030, 1544, 520), (2048, 1024, 512),
+                                   # at most 256 / 128 rows and a row of tiles that fills the chip: the deep weight ring
+                                   (200, 16512, 520), (256, 16384, 192), (100, 33000, 328), (128, 32768, 1024)])
 def test_gemm_nt(lib, m, n, k):
     import torch
     rng = np.random.default_rng(m + n + k)
@@ -224,6 +226,17 @@ def test_many_rows_use_large_tiles(lib):
     batch = W.assemble_batch(16, [(700, 700, -1), (391, 500, -1)] + [(1, 200 + 7 * i, -1) for i in range(50)], 2,
                              [], np.random.default_rng(5))
     tens = W.make_tensors(shape, batch, 5)
+    check_step(lib, shape, batch, tens, mae_tol=3 * MAE)
+
+
+@pytest.mark.parametrize("n_decode,q_rows", [(60, 40), (120, 80), (97, 0)])
+def test_few_rows_take_the_deep_weight_ring(lib, n_decode, q_rows):
+    # at most 128 / 256 rows: the QKV, output and down projections run as k-ranges of a single
+    # row of tiles on the pipeline with its own look-ahead for the weight panel
+    shape = W.LayerShape(1024, 8, 2, 128, 2048)
+    seqs = ([(q_rows, q_rows + 30, -1)] if q_rows else []) + [(1, 50 + 11 * i, -1) for i in range(n_decode)]
+    batch = W.assemble_batch(16, seqs, 1 if q_rows else 0, [], np.random.default_rng(n_decode))
+    tens = W.make_tensors(shape, batch, 7, gains="random")
     check_step(lib, shape, batch, tens, mae_tol=3 * MAE)
 
 
