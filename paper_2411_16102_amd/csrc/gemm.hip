@@ -276,24 +276,25 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
     for (; kt < kt1; ++kt) tile(kt, Yes{});
   } else {
     // One round of tiles over few rows: every CU streams a weight panel of its own from HBM,
-    // and what bounds the kernel is how many bytes of it are in flight.  LDS holds two slots
-    // for the activation panel (shared by all tiles, served by the L2: one k-tile of
-    // look-ahead) and all the rest, NWS slots, for the weight panel: NWS - 1 k-tiles of
-    // look-ahead.  The memory counter of a wavefront retires its loads in order, so a wait for
-    // an activation panel would also wait for every weight panel requested before it; the two
-    // kinds of request therefore come from different wavefronts: the first half of the
-    // workgroup loads activations and waits for all of its loads, the second half loads
-    // weights and waits until only the NWS - 2 youngest panels are outstanding.
-    constexpr int UX = BM * ROWB, UW = BN * ROWB, W_BASE = 2 * UX;
+    // and the ring of five equal slots gives it two k-tiles of look-ahead at most.  Here LDS
+    // holds NXS = DEEP + 1 slots for the activation panel (shared by all tiles, served by the
+    // L2: NXS - 1 k-tiles of look-ahead) and all the rest, NWS slots, for the weight panel:
+    // NWS - 1 k-tiles of look-ahead.  The memory counter of a wavefront retires its loads in
+    // order, so a wait for an activation panel would also wait for every weight panel
+    // requested before it; the two kinds of request therefore come from different wavefronts:
+    // the first half of the workgroup loads activations and waits until its NXS - 2 youngest
+    // panels remain, the second half loads weights and waits until its NWS - 2 youngest remain.
+    constexpr int NXS = DEEP + 1;  // activation slots
+    constexpr int UX = BM * ROWB, UW = BN * ROWB, W_BASE = NXS * UX;
     constexpr int NWS = (160 * 1024 - W_BASE) / UW;
-    static_assert(NWS >= 3 && (NWS - 1) * LB < 64, "weight slots and the vmcnt field");
+    static_assert(NWS >= 3 && (NWS - 1) * LB < 64 && (NXS - 1) * LA < 64, "slots and the vmcnt field");
     const bool loads_x = wave < XW;  // uniform
     if (loads_x) {
 #pragma unroll
-      for (int i = 0; i < LA; ++i) dma_a(kt0, 0, i, Yes{});
+      for (int sl = 0; sl < NXS; ++sl)
 #pragma unroll
-      for (int i = 0; i < LA; ++i) dma_a(kt0 + 1, UX, i, Yes{});
-      __builtin_amdgcn_s_waitcnt(waitcnt_imm(LA, true));
+        for (int i = 0; i < LA; ++i) dma_a(kt0 + sl, sl * UX, i, Yes{});
+      __builtin_amdgcn_s_waitcnt(waitcnt_imm((NXS - 1) * LA, true));
     } else {
 #pragma unroll
       for (int sl = 0; sl < NWS; ++sl)
@@ -302,31 +303,32 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
       __builtin_amdgcn_s_waitcnt(waitcnt_imm((NWS - 1) * LB, true));
     }
     __builtin_amdgcn_s_barrier();  // tile 0 has landed
-    int xo = 0, ws = 0;            // activation slot offset and weight slot number of the tile being multiplied
+    int xs = 0, ws = 0;            // activation and weight slot numbers of the tile being multiplied
 #pragma unroll
-    for (int o = 0; o < NF; ++o) frag(xo, W_BASE + ws * UW, 0, o, xa, wa);
+    for (int o = 0; o < NF; ++o) frag(xs * UX, W_BASE + ws * UW, 0, o, xa, wa);
     constexpr int N_X = NF + LA, N_W = NF + LB;
     constexpr int PER_X = (N_X + NMF - 1) / NMF, PER_W = (N_W + NMF - 1) / NMF;
     auto tile = [&](int kt, auto checked) {
-      const int wo = W_BASE + ws * UW;
+      const int wo = W_BASE + ws * UW, xo = xs * UX;
       __builtin_amdgcn_s_waitcnt(LGKM0);
       step(xa, wa, NF, PER_F, [&](int o) { frag(xo, wo, 1, o, xb, wb); });
       // after the barrier: every wavefront holds all fragments of tile kt, X(kt+1) has landed
-      // (the activation half waited for all its loads) and so has W(kt+1) (the weight half
-      // waited until only W(kt+2) .. W(kt+NWS-1) were outstanding)
+      // (the activation half waited until only X(kt+2) .. X(kt+NXS-1) were outstanding) and so
+      // has W(kt+1) (the weight half: only W(kt+2) .. W(kt+NWS-1))
       if (loads_x)
-        __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm((NXS - 2) * LA, true));
       else
         __builtin_amdgcn_s_waitcnt(waitcnt_imm((NWS - 2) * LB, true));
       __builtin_amdgcn_s_barrier();
-      const int nxo = xo ^ UX, nws = ws + 1 == NWS ? 0 : ws + 1;
+      const int nxs = xs + 1 == NXS ? 0 : xs + 1, nws = ws + 1 == NWS ? 0 : ws + 1;
+      const int nxo = nxs * UX;
       const int nwo = W_BASE + nws * UW;
       if (loads_x)
         step(xb, wb, N_X, PER_X, [&](int o) {
           if (o < NF)
             frag(nxo, nwo, 0, o, xa, wa);
           else
-            dma_a(kt + 2, xo, o - NF, checked);
+            dma_a(kt + NXS, xo, o - NF, checked);
         });
       else
         step(xb, wb, N_W, PER_W, [&](int o) {
@@ -335,11 +337,11 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
           else
             dma_b(kt + NWS, wo, o - NF, checked);
         });
-      xo = nxo;
+      xs = nxs;
       ws = nws;
     };
     int kt = kt0;
-    const int n_plain = a.K / BK - NWS;  // tiles kt for which X(kt+2) and W(kt+NWS) lie wholly inside K
+    const int n_plain = a.K / BK - (NWS > NXS ? NWS : NXS);  // tiles kt for which X(kt+NXS) and W(kt+NWS) lie wholly inside K
     for (; kt < n_plain && kt < kt1; ++kt) tile(kt, No{});
     for (; kt < kt1; ++kt) tile(kt, Yes{});
   }
@@ -652,6 +654,10 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
 // 5120) rows by 4096 (8192) columns then make exactly one (four) full rounds of 256
 // workgroups where 256x256 tiles leave 38 % (17 %) of the CUs idle.  SMALL: 128x128.
 // S128 / S256: 128x256 and 256x128 tiles on the deep weight ring, for at most 128 / 256 rows.
+// activation slots of the short-row pipeline, minus one: three slots leave four weight slots of 16 KB
+// (256x128) or three of 32 KB (128x256); measured against two slots (six / four weight slots) on the
+// 256-row gate/up GEMM of the 8B layer: 0.075 against 0.078 ms, the other GEMMs the same
+constexpr int DEEP_X = 2;
 enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3, V_S128 = 4, V_S256 = 5 };
 constexpr int N_CU = 256;
 
@@ -699,8 +705,8 @@ hipError_t launch_variant(const GemmArgs &a, int v, hipStream_t stream) {
   if (v == V_BIG) return launch_one<256, 256, DH_BIG_M, DH_BIG_N, EPI, (DH_BIG_M == 4 ? 128 : 64)>(a, stream);
   if (v == V_TALL) return launch_one<160, 256, 2, 4, EPI, 64>(a, stream);
   if constexpr (EPI == EPI_SWIGLU || EPI == EPI_PLAIN) {
-    if (v == V_S128) return launch_one<128, 256, 2, 4, EPI, 64, 1>(a, stream);
-    if (v == V_S256) return launch_one<256, 128, 4, 2, EPI, 64, 1>(a, stream);
+    if (v == V_S128) return launch_one<128, 256, 2, 4, EPI, 64, DEEP_X>(a, stream);
+    if (v == V_S256) return launch_one<256, 128, 4, 2, EPI, 64, DEEP_X>(a, stream);
   }
   return launch_one<128, 128, 2, 2, EPI, 64>(a, stream);
 }
@@ -756,8 +762,8 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stre
     if ((epilogue != EPI_RESID && epilogue != EPI_RESID_NORM && epilogue != EPI_QKV) || !a.splitk_ws || a.N % 4)
       return hipErrorInvalidValue;
     const int sv = short_variant(a.M);
-    hipError_t e = sv == V_S128   ? launch_one<128, 256, 2, 4, EPI_PARTIAL, 64, 1>(a, stream)
-                   : sv == V_S256 ? launch_one<256, 128, 4, 2, EPI_PARTIAL, 64, 1>(a, stream)
+    hipError_t e = sv == V_S128   ? launch_one<128, 256, 2, 4, EPI_PARTIAL, 64, DEEP_X>(a, stream)
+                   : sv == V_S256 ? launch_one<256, 128, 4, 2, EPI_PARTIAL, 64, DEEP_X>(a, stream)
                                   : launch_one<128, 128, 2, 2, EPI_PARTIAL, 64>(a, stream);
     if (e != hipSuccess) return e;
     if (epilogue == EPI_QKV) {
