@@ -269,6 +269,8 @@ def main():
         "roofline": roofline,
         "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
     }
+    if batch.n_prefill and batch.n_seq > batch.n_prefill and kernels["attn_prefill"]["launches_per_step"] == 0:
+        out["kernels_note"] = "attn_decode is the one launch that runs prefill and decode attention together"
     if not args.no_cpu_baseline:
         note("timing the CPU oracle on a sample")
         out["cpu_baseline"], _ = cpu_baseline(shape, batch, tens)
