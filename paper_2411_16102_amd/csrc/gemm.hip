@@ -18,8 +18,10 @@
 // halves fetched separately (measured: 41 against 26 B/clk/CU into LDS).  LDS is a ring
 // of five 32 KB units, one unit holding the activation panel or the weight panel of one
 // k-tile, so two and a half k-tiles fit in the 160 KB: while tile kt is multiplied,
-// tile kt+1 has landed or is landing and the activation panel of tile kt+2 is in
-// flight.  Rows are 128 B whose eight 16-byte chunks are XOR-swizzled with
+// tile kt+1 has landed or is landing and the weight panel of tile kt+2 is in flight.
+// (GEMMs of at most 256 rows use a second pipeline, DEEP in the kernel below: one row
+// of tiles, a few slots for the activation panel and all other LDS for the weight
+// panel, the two kinds of panel requested by different wavefronts.)  Rows are 128 B whose eight 16-byte chunks are XOR-swizzled with
 // ((row >> 1) & 7): two consecutive rows fill the 256-byte bank row, so the swizzle
 // must change every two rows for the ds_read_b128 of a fragment (16 rows by four chunk
 // columns) to be conflict-free.  Waits on the LDS-DMA loads are placed by hand
