@@ -184,7 +184,9 @@ int bs_set_chunk_pages(bs_ctx *ctx, int32_t pages);
 int bs_set_overlap_cus(bs_ctx *ctx, int32_t decode_cus);
 
 /* Tuning knob: GEMM tile shape, process-wide: 0 = chosen per problem (default), 1 = 256x256,
- * 2 = 160x256 (not for the QKV GEMM), 3 = 128x128. */
+ * 2 = 160x256 (not for the QKV GEMM), 3 = 128x128.  With 0, GEMMs of at most 256 rows run as one
+ * row of 128x256 or 256x128 tiles on a pipeline with its own look-ahead for the weight panel; a
+ * forced shape switches that off. */
 int bs_set_gemm_tiles(bs_ctx *ctx, int32_t variant);
 
 /* Stand-alone entry points of the individual operators (the same kernels the
