@@ -240,6 +240,18 @@ def test_few_rows_take_the_deep_weight_ring(lib, n_decode, q_rows):
     check_step(lib, shape, batch, tens, mae_tol=3 * MAE)
 
 
+@pytest.mark.parametrize("d_model,d_ffn", [(256, 32768), (512, 33024)])
+def test_rounds_of_full_tiles_in_gate_up(lib, d_model, d_ffn):
+    # 512 rows and a wide FFN: the gate/up GEMM has two whole rounds of full 256x256 tiles (four and
+    # eight k-tiles per tile); the second shape adds a last round that goes out on the small tiles
+    shape = W.LayerShape(d_model, 4, 2, 64, d_ffn)
+    batch = W.assemble_batch(16, [(300, 300, -1), (150, 180, -1)] + [(1, 20 + 3 * i, -1) for i in range(62)], 2,
+                             [], np.random.default_rng(9))
+    assert batch.n_rows == 512
+    tens = W.make_tensors(shape, batch, 9)
+    check_step(lib, shape, batch, tens, mae_tol=3 * MAE)
+
+
 def test_decode_only_and_prefill_only(lib):
     for batch in (W.batch_decode_only(33, 130, seed=2), W.batch_prefill_only(3, 75, seed=2)):
         tens = W.make_tensors(W.TINY, batch, 2)
