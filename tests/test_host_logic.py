@@ -136,3 +136,12 @@ def test_inconsistent_nodes_are_rejected(host_layer):
 def test_empty_batch_is_valid(host_layer):
     b = W.assemble_batch(16, [], 0, [], None)
     assert host_layer.validate(b) == 0
+
+
+def test_tuning_knobs_reject_values_outside_their_range(host_layer):
+    for bad in (0, 1, 3, 66, -2):
+        assert host_layer.lib.bs_set_chunk_pages(host_layer.h, bad) == -1 and "chunk_pages" in host_layer.last_error()
+    for ok in (2, 32, 64):
+        assert host_layer.lib.bs_set_chunk_pages(host_layer.h, ok) == 0
+    assert host_layer.lib.bs_set_gemm_tiles(host_layer.h, 4) == -1
+    assert host_layer.lib.bs_set_gemm_tiles(host_layer.h, 0) == 0
