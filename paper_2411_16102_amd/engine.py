@@ -25,7 +25,13 @@ counted once in the memory account while any sharer is resident, and the descrip
 prefix nodes let decode attention read it once per group.
 
 Output lengths: the order and the memory reservation use the estimate `d_est`; a request
-finishes after `d_true` tokens.
+finishes after `d_true` tokens.  The batch adapts to misjudged lengths as Section 5.4 describes:
+a request that ends early frees its reservation at once and the scanners admit others in its
+place; one that runs past its estimate has its account grow token by token; and one admitted
+from the compute-intensive end whose output has grown to `relocate_factor` times its estimate
+(a severe underestimate: it is a memory-intensive request after all) is moved, with its own
+reservation, from the left memory partition to the right one, so that the left scanner gets its
+share back for the requests it is meant to admit.
 """
 from __future__ import annotations
 
@@ -54,8 +60,9 @@ class _Live:
 class Engine:
     def __init__(self, builder, requests: Sequence[PoolRequest], mem_tokens: int, policy: str = "blend",
                  token_budget: int = 2560, split_t: int = 0, split_budget: int = -1, seed: int = 0,
-                 mem_model: str = "expanded"):
+                 mem_model: str = "expanded", relocate_factor: float = 2.0):
         assert policy in ("blend", "dfs", "random")
+        self.relocate_factor = float(relocate_factor)   # 0: requests stay on the side that admitted them
         if mem_model != "expanded":
             builder.set_mem_model(mem_model)   # densities with shared prefix pages read once per step
             split_t = 0                        # node splitting is defined for the additive model
@@ -105,7 +112,7 @@ class Engine:
         self.node_owner = np.full(n_nodes, -1, dtype=np.int64)
         self.node_side = np.zeros(n_nodes, dtype=np.int64)
         self.stats = dict(steps=0, rows=0, prefill_rows=0, decode_rows=0, prompt_tokens_skipped=0, tokens_out=0,
-                          finished=0, peak_tokens=0, kv_tokens_read=0)
+                          finished=0, peak_tokens=0, kv_tokens_read=0, relocated=0)
 
     # -- helpers ---------------------------------------------------------------------------
     def _path(self, r: int) -> List[int]:
@@ -277,6 +284,13 @@ class Engine:
             if lv.generated > self.reqs[r].d_est:     # ran past its estimate: the account follows
                 lv.reserved += 1
                 self.used[lv.side] += 1
+                if (self.policy == "blend" and lv.side == 0 and self.relocate_factor > 0
+                        and lv.generated >= self.relocate_factor * self.reqs[r].d_est):
+                    # severely underestimated (Section 5.4): from the left partition to the right one
+                    self.used[0] -= lv.reserved
+                    self.used[1] += lv.reserved
+                    lv.side = 1
+                    st["relocated"] += 1
             if lv.generated >= self.reqs[r].d_true:
                 st["finished"] += 1
                 self._release(lv)

@@ -102,3 +102,29 @@ def test_pool_is_served_under_the_shared_memory_model():
     ref = make_engine(reqs, "blend")
     t_s, t_e = eng.b.tree(), ref.b.tree()
     assert int(t_s["B"][0]) < int(t_e["B"][0]) and int(t_s["A"][0]) == int(t_e["A"][0])
+
+
+def test_a_severely_underestimated_request_moves_to_the_memory_side():
+    # prompt-heavy requests with short estimated outputs sit at the compute-intensive end; a few of
+    # them decode eight times longer than estimated.  With relocation their reservations move to
+    # the right partition once they have produced twice their estimate; the accounts still close.
+    rng = np.random.default_rng(11)
+    reqs = []
+    for i in range(40):
+        reqs.append(E.PoolRequest([int(t) for t in rng.integers(0, 1000, 300)], 8, 64 if i % 5 == 0 else 8))
+    for i in range(40):
+        reqs.append(E.PoolRequest([int(t) for t in rng.integers(0, 1000, 20)], 200, 200))
+    stats = {}
+    for factor in (2.0, 0.0):
+        eng = make_engine(reqs, "blend", mem_tokens=6000, budget=512, relocate_factor=factor)
+        peak_left = [0]
+
+        def step(d, eng=eng, peak_left=peak_left):
+            peak_left[0] = max(peak_left[0], eng.used[0])
+
+        st = eng.run(step)
+        assert eng.done and st["finished"] == len(reqs) and st["tokens_out"] == sum(r.d_true for r in reqs)
+        assert eng.used == [0, 0] and not eng.node_ref.any()
+        stats[factor] = (st["relocated"], st["steps"])
+    assert stats[0.0][0] == 0
+    assert 0 < stats[2.0][0] <= 8          # only the eight long decoders can move, and only those admitted on the left
