@@ -57,7 +57,7 @@ def pool_run(args, lib, W, note):
         b = lib.Builder(8_030_000_000, kv_bytes * 32, PEAK_MFMA_BF16, PEAK_HBM, args.pool_mem_tokens * kv_bytes * 32, 16)
         eng = E.Engine(b, reqs, args.pool_mem_tokens, policy=policy, token_budget=budget, seed=args.seed,
                        split_t=4096 if policy == "blend" else 0, split_budget=int(0.01 * prompt),
-                       mem_model=args.pool_mem_model)
+                       mem_model=args.pool_mem_model, row_multiple=args.pool_row_multiple)
         stepper.events = []
         t0 = time.perf_counter()
         st = eng.run(stepper, progress=lambda s_: note("%s: step %d, %d finished" % (policy, s_["steps"], s_["finished"])))
@@ -70,7 +70,7 @@ def pool_run(args, lib, W, note):
             "output_tokens": outp, "prefill_rows": st["prefill_rows"], "prompt_tokens_skipped": st["prompt_tokens_skipped"],
             "decode_rows": st["decode_rows"], "mean_rows_per_step": st["rows"] / max(1, st["steps"]),
             "peak_kv_tokens": st["peak_tokens"], "kv_capacity_tokens": args.pool_mem_tokens,
-            "split": eng.split_info, "mem_model": args.pool_mem_model, "dtype": "bf16", "data": "synthetic",
+            "split": eng.split_info, "mem_model": args.pool_mem_model, "row_multiple": args.pool_row_multiple, "relocated": st["relocated"], "dtype": "bf16", "data": "synthetic",
             "config": {"workload": "pool(seed=%d, groups=%d, fresh=%d)" % (args.seed, args.pool_groups, args.pool_fresh), "token_budget": budget,
                        "d_model": shape.d_model, "d_ffn": shape.d_ffn}}), flush=True)
 
@@ -133,6 +133,8 @@ def main():
                          "driver, admission order blend | dfs | random | all (one JSON line each)")
     ap.add_argument("--pool-mem-tokens", type=int, default=200_000, help="KV capacity of the pool run, in tokens")
     ap.add_argument("--pool-groups", type=int, default=24, help="prefix groups of 12 requests (short, medium, long outputs in turn)")
+    ap.add_argument("--pool-row-multiple", type=int, default=1,
+                    help="steps of more rows than this are cut to a multiple of it (1: off)")
     ap.add_argument("--pool-mem-model", default="expanded", choices=["expanded", "shared"],
                     help="memory model of the densities: the paper's, or shared prefix pages charged once per step")
     ap.add_argument("--pool-fresh", type=int, default=1500, help="prompt-heavy requests without shared prefix")

@@ -128,3 +128,18 @@ def test_a_severely_underestimated_request_moves_to_the_memory_side():
         stats[factor] = (st["relocated"], st["steps"])
     assert stats[0.0][0] == 0
     assert 0 < stats[2.0][0] <= 8          # only the eight long decoders can move, and only those admitted on the left
+
+
+def test_steps_with_prefill_rows_come_in_multiples_of_128():
+    reqs = E.synthetic_pool(2, n_groups=6, per_group=5, n_fresh=30)
+    rows = {}
+    for mult in (128, 1):
+        eng = make_engine(reqs, "blend", mem_tokens=30_000, budget=1024, row_multiple=mult)
+        seen = []
+        st = eng.run(lambda d, seen=seen: seen.append((d["n_rows"], int(d["row_start"][d["n_prefill"]]))))
+        assert eng.done and st["finished"] == len(reqs) and st["tokens_out"] == sum(r.d_true for r in reqs)
+        assert st["prefill_rows"] + st["prompt_tokens_skipped"] == sum(len(r.tokens) for r in reqs)
+        rows[mult] = seen
+    # a step of more than 128 rows keeps a ragged row count only when it has no prefill rows left to give up
+    assert all(n <= 128 or n % 128 == 0 or pf == 0 for n, pf in rows[128])
+    assert any(n > 128 and n % 128 and pf for n, pf in rows[1])
