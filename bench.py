@@ -252,7 +252,9 @@ def main():
         kv_bytes = work["kv_tokens_once"] * shape.kv_bytes_per_token
         roofline = {"bound": "hbm", "kernel": "decode_attn (paged, prefix-aware)",
                     "achieved": kv_bytes / (dec_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
-                    "traffic": None}
+                    "traffic": (measured_traffic("decode_8b_decode_attn_trace_and_hbm_traffic.txt",
+                                                 ["attn.hip", "attn.hpp", "common.hpp"])
+                                if args.workload == "decode_8b" else None)}
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
 
     out = {
