@@ -41,6 +41,43 @@ def measured_traffic(profile_name, sources):
     return int(val.group(1))
 
 
+def overlap_timeline(layer, shape, run_step):
+    """One more co-scheduled step with the in-kernel timeline on; per launch: how long the GEMM tiles
+    ran, how long the launch lasted, and the KV bytes the attention wavefronts read meanwhile."""
+    import numpy as np
+    layer.overlap_trace(True)
+    run_step()
+    names = ["o_proj", "gate_up", "down", "rest_of_queue"]
+    per_token = 2 * shape.head_dim * 2   # K and V of one token and KV head
+    out = {}
+    for k, name in enumerate(names):
+        rec = layer.overlap_trace_read(k)
+        kind = (rec[:, 2] & np.uint64(0xFF)).astype(int) if len(rec) else np.zeros(0, int)
+        used = kind > 0
+        if not used.any():
+            out[name] = None
+            continue
+        t0 = int(rec[used, 0].min())
+        us = lambda ticks: (int(ticks) - t0) / 100.0    # 100 MHz clock
+        tiles, attn = rec[kind == 2], rec[kind == 1]
+        info = {"launch_us": us(rec[used, 1].max()), "tiles": int(len(tiles)), "attention_wavefronts": int(len(attn))}
+        if len(tiles):
+            info["tiles_end_us"] = us(tiles[:, 1].max())
+            info["tile_us_mean"] = float(np.mean((tiles[:, 1] - tiles[:, 0]).astype(np.int64))) / 100.0
+        if len(attn):
+            tokens = (attn[:, 3] >> np.uint64(32)).astype(np.int64)
+            units = (attn[:, 3] & np.uint64(0xFFFFFFFF)).astype(np.int64)
+            busy = units > 0
+            info["kv_bytes"] = int(tokens.sum()) * per_token
+            info["units"] = int(units.sum())
+            info["attention_end_us"] = us(attn[busy, 1].max()) if busy.any() else 0.0
+            info["attention_cus"] = int(len(np.unique((attn[busy, 2] >> np.uint64(8)) & np.uint64(0xFFFFFF0F00)))) if busy.any() else 0
+            info["attention_GBps"] = info["kv_bytes"] / max(info["launch_us"], 1e-9) / 1e3
+        out[name] = info
+    layer.overlap_trace(False)
+    return out
+
+
 def pool_run(args, lib, W, note):
     """The multi-step driver on a synthetic pool (8B-shaped layer): tokens served per second of
     device time under each admission order."""
@@ -123,7 +160,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-pages", type=int, default=0)
-    ap.add_argument("--decode-cus", type=int, default=-1)
+    ap.add_argument("--overlap-knobs", default="",
+                    help="knobs of the co-scheduled schedule as name=value,name=value (see bs_overlap_knobs)")
     ap.add_argument("--gemm-tiles", type=int, default=0, help="force one GEMM tile shape (0: cost model)")
     ap.add_argument("--layers", type=int, default=1,
                     help="a step = this many layers back to back through bs_blend_layers (same weights and pool "
@@ -138,6 +176,8 @@ def main():
     ap.add_argument("--pool-mem-model", default="expanded", choices=["expanded", "shared"],
                     help="memory model of the densities: the paper's, or shared prefix pages charged once per step")
     ap.add_argument("--pool-fresh", type=int, default=1500, help="prompt-heavy requests without shared prefix")
+    ap.add_argument("--overlap-trace", action="store_true",
+                    help="with the co-scheduled schedule: add the in-kernel timeline of one more step to the line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy (for scaling HBM traffic counters)")
     args = ap.parse_args()
@@ -167,8 +207,8 @@ def main():
         layer.set_chunk_pages(args.chunk_pages)
     if args.gemm_tiles:
         layer.set_gemm_tiles(args.gemm_tiles)
-    if args.decode_cus >= 0:
-        layer.set_overlap_cus(args.decode_cus)
+    if args.overlap_knobs:
+        layer.set_overlap(**{kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.overlap_knobs.split(",")})
     note("uploading")
     dev = layer.upload(tens, batch)
     desc = lib.marshal_batch(batch)
@@ -273,6 +313,10 @@ def main():
         "roofline": roofline,
         "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
     }
+    if flags:
+        out["overlap_kv_bytes"] = layer.overlap_report()
+        if args.overlap_trace:
+            out["overlap_timeline"] = overlap_timeline(layer, shape, lambda: run_once(flags))
     if batch.n_prefill and batch.n_seq > batch.n_prefill and kernels["attn_prefill"]["launches_per_step"] == 0:
         out["kernels_note"] = "attn_decode is the one launch that runs prefill and decode attention together"
     if not args.no_cpu_baseline:

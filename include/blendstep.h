@@ -104,10 +104,17 @@ typedef struct bs_batch {
 typedef struct bs_ctx bs_ctx;
 
 /* Flags of bs_blend_step. */
-#define BS_FLAG_SERIAL 0u   /* every kernel on the caller's stream, in order */
-#define BS_FLAG_OVERLAP 1u  /* decode attention on a side stream with its own CU set,
-                               concurrent with the prefill rows' GEMMs (Section 2.2,
-                               operator-level overlapping; Appendix A.2, backend engine) */
+#define BS_FLAG_SERIAL 0u   /* every operator of the step over all rows, one launch after the other */
+#define BS_FLAG_OVERLAP 1u  /* memory-bound decode attention co-scheduled with the compute-bound GEMMs
+                               of the prefill rows (Section 3.3: overlapped, a step costs the larger of
+                               its compute and memory times, not their sum; Section 2.2, operator-level
+                               overlapping between parts of a batch; Appendix A.2, backend engine):
+                               the decode units of at most 16 query rows form a queue that attention
+                               workgroups drain inside the prefill rows' output-projection, gate/up and
+                               down-projection launches, on CUs of their own; the decode rows' projection
+                               and FFN follow.  Still one stream and no events.  Steps without prefill
+                               rows or without such units run the serial schedule.  Results differ from
+                               the serial schedule by GEMM tile shapes only (same arithmetic per element). */
 
 /* Create a context on `device`; allocates the RoPE table and workspace that
  * grows on demand.  *out is NULL on failure; bs_last_error(NULL) then returns
@@ -168,7 +175,10 @@ int bs_resolve_rows(bs_ctx *ctx, const bs_batch *batch, int32_t *page_out, int32
  * attention as one launch, booked under BS_K_ATTN_DECODE (BS_K_ATTN_PREFILL
  * then has no launches). */
 enum { BS_K_PREP = 0, BS_K_GEMM_QKV, BS_K_ATTN_PREFILL, BS_K_ATTN_DECODE, BS_K_ATTN_MERGE,
-       BS_K_GEMM_O, BS_K_GEMM_GATE_UP, BS_K_GEMM_DOWN, BS_K_COUNT };
+       BS_K_GEMM_O, BS_K_GEMM_GATE_UP, BS_K_GEMM_DOWN,
+       BS_K_ATTN_QUEUE_REST,   /* BS_FLAG_OVERLAP: the launch that drains what the carrying GEMMs left of the queue */
+       BS_K_GEMM_DECODE_ROWS,  /* BS_FLAG_OVERLAP: output projection, gate/up and down of the decode rows */
+       BS_K_COUNT };
 int bs_profile_enable(bs_ctx *ctx, int on);
 int bs_profile_read(bs_ctx *ctx, int which, double *total_ms, int64_t *launches);
 int bs_profile_reset(bs_ctx *ctx);
@@ -179,9 +189,55 @@ int bs_profile_reset(bs_ctx *ctx);
  * costs one partial state per member row); a call sets both. */
 int bs_set_chunk_pages(bs_ctx *ctx, int32_t pages);
 
-/* Tuning knob: CUs reserved for decode attention in the BS_FLAG_OVERLAP schedule (0, 64, 128 or
- * 192; default 64; 0 = side streams without CU masks).  Synchronises the device. */
-int bs_set_overlap_cus(bs_ctx *ctx, int32_t decode_cus);
+/* Tuning knobs of the BS_FLAG_OVERLAP schedule. */
+typedef struct bs_overlap_knobs {
+  int32_t head_cus_min;     /* CUs that a carrying GEMM launch gives to attention for its whole duration: */
+                            /* chosen per launch between head_cus_min and head_cus_max (multiples of 8,
+                               0..192; defaults 0 and 96) so that the tiles fill whole rounds on the rest */
+  int32_t tail_workgroups;  /* attention workgroups placed behind the tiles of a carrying launch, which start
+                               on the CUs that its last round of tiles leaves idle (0..256; default 208) */
+  int32_t close_margin;     /* a carrying launch whose last round of tiles leaves CUs idle stops handing out
+                               decode units when all but this many of its tiles have finished (0..256;
+                               default 8); one whose last round is at least three quarters full stops as
+                               soon as the first tile of that round has finished */
+  int32_t min_prefill_rows; /* steps with fewer prefill rows run the serial schedule (default 256) */
+  int32_t ride_percent;     /* at most this share of the 16-row units' KV bytes waits for the carrying
+                               launches; the rest joins the first attention launch (0..100; -1, the
+                               default: what the head CUs are expected to read while the tiles run) */
+  int32_t attention_waves;  /* wavefronts of an attention workgroup (of its eight) that take units (1..8;
+                               default 2: a CU streams nearly as fast with two as with eight, and a unit
+                               is finished sooner) */
+  int32_t carry_down;       /* 0 (default): the output projection and gate/up of the prefill rows carry
+                               attention and one down projection runs over all rows at the end; 1: the down
+                               projection is split into prefill and decode rows too and carries attention */
+  int32_t drain_in_last;    /* 1 (default): the last carrying launch goes on until the queue is empty;
+                               0: it closes like the others and one more launch drains the queue */
+  int32_t head_cus_max;
+} bs_overlap_knobs;
+int bs_set_overlap(bs_ctx *ctx, const bs_overlap_knobs *knobs);
+int bs_get_overlap(const bs_ctx *ctx, bs_overlap_knobs *knobs);
+
+/* Where the decode attention of the last BS_FLAG_OVERLAP step ran: key/value bytes of the 16-row units
+ * read by [0] the first attention launch (with the prefill rows and the wide items), [1..3] the attention
+ * workgroups inside the output-projection, gate/up and down-projection launches of the prefill rows,
+ * [4] the launch after them (drain_in_last = 0).  kv_bytes: HOST array of 5.  Synchronises the device.
+ * Meaningful only after a step that took the co-scheduled path. */
+int bs_overlap_report(bs_ctx *ctx, int64_t *kv_bytes);
+
+/* Timeline of the co-scheduled launches, taken inside the kernels (a kernel trace sees one launch where
+ * attention and GEMM workgroups run side by side; this shows what ran when, and on which CU).
+ * bs_overlap_trace(ctx, 1) allocates the record buffer (8 MB) and makes every later BS_FLAG_OVERLAP step
+ * record; (ctx, 0) frees it.  Both synchronise the device.  bs_overlap_trace_read copies the records of
+ * one launch of the last such step (launch 0..2: the output-projection, gate/up and down-projection
+ * launches of the prefill rows; 3: the launch that drains the rest of the queue) to the HOST array `out`
+ * of cap_records x 4 uint64 and sets *n_records to the number the launch has (8 per workgroup, in grid
+ * order; 0 if no timeline was taken or the launch had more than 8192 workgroups).  A record is
+ * {begin, end} in ticks of the GPU's constant 100 MHz clock, {kind (1 attention wavefront, 2 GEMM tile;
+ * 0 = unused record) | HW_ID << 8 | XCC_ID << 32}, {units | KV tokens << 32} that an attention wavefront
+ * served.  Recording costs a few stores per wavefront; a step that records clears the buffer with a memset
+ * on the stream, so it is not for steps captured into a graph. */
+int bs_overlap_trace(bs_ctx *ctx, int on);
+int bs_overlap_trace_read(bs_ctx *ctx, int32_t launch, uint64_t *out, int64_t cap_records, int64_t *n_records);
 
 /* Tuning knob: GEMM tile shape, process-wide: 0 = chosen per problem (default), 1 = 256x256,
  * 2 = 160x256 (not for the QKV GEMM), 3 = 128x128.  With 0, GEMMs of at most 256 rows run as one

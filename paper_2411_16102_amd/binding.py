@@ -21,7 +21,8 @@ _HEADERS = [os.path.join(_ROOT, "include", "blendstep.h"), os.path.join(_ROOT, "
 
 _i32p = C.POINTER(C.c_int32)
 
-K_NAMES = ["prep", "gemm_qkv", "attn_prefill", "attn_decode", "attn_merge", "gemm_o", "gemm_gate_up", "gemm_down"]
+K_NAMES = ["prep", "gemm_qkv", "attn_prefill", "attn_decode", "attn_merge", "gemm_o", "gemm_gate_up", "gemm_down",
+           "attn_queue_rest", "gemm_decode_rows"]
 FLAG_SERIAL, FLAG_OVERLAP = 0, 1
 
 
@@ -41,6 +42,11 @@ class BatchDesc(C.Structure):
                 ("n_nodes", C.c_int32), ("node_parent", _i32p), ("node_page_start", _i32p),
                 ("node_page_ids", _i32p), ("node_seq_first", _i32p), ("node_seq_count", _i32p),
                 ("seq_leaf_node", _i32p)]
+
+
+class OverlapKnobs(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("head_cus_min", "tail_workgroups", "close_margin", "min_prefill_rows",
+                                         "ride_percent", "attention_waves", "carry_down", "drain_in_last", "head_cus_max")]
 
 
 class SplitInfo(C.Structure):
@@ -112,7 +118,11 @@ def raw():
         lib.bs_profile_reset.argtypes = [C.c_void_p]
         lib.bs_set_chunk_pages.argtypes = [C.c_void_p, C.c_int32]
         lib.bs_set_gemm_tiles.argtypes = [C.c_void_p, C.c_int32]
-        lib.bs_set_overlap_cus.argtypes = [C.c_void_p, C.c_int32]
+        lib.bs_set_overlap.argtypes = [C.c_void_p, C.POINTER(OverlapKnobs)]
+        lib.bs_get_overlap.argtypes = [C.c_void_p, C.POINTER(OverlapKnobs)]
+        lib.bs_overlap_report.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
+        lib.bs_overlap_trace.argtypes = [C.c_void_p, C.c_int]
+        lib.bs_overlap_trace_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.c_int64, C.POINTER(C.c_int64)]
         lib.bs_gemm_nt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                    C.c_void_p]
         lib.bs_attention.argtypes = [C.c_void_p, C.POINTER(BatchDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
@@ -317,8 +327,39 @@ class Layer:
     def set_chunk_pages(self, pages: int):
         self._check(self.lib.bs_set_chunk_pages(self.h, pages))
 
-    def set_overlap_cus(self, decode_cus: int):
-        self._check(self.lib.bs_set_overlap_cus(self.h, decode_cus))
+    def get_overlap(self) -> dict:
+        k = OverlapKnobs()
+        self._check(self.lib.bs_get_overlap(self.h, C.byref(k)))
+        return {n: getattr(k, n) for n, _ in OverlapKnobs._fields_}
+
+    def set_overlap(self, **knobs):
+        """Change some knobs of the co-scheduled schedule (see bs_overlap_knobs), keeping the others."""
+        cur = self.get_overlap()
+        for n in knobs:
+            if n not in cur:
+                raise ValueError("unknown overlap knob " + n)
+        cur.update(knobs)
+        k = OverlapKnobs(**cur)
+        self._check(self.lib.bs_set_overlap(self.h, C.byref(k)))
+
+    def overlap_report(self):
+        """KV bytes of the 16-row units per launch of the last co-scheduled step: first attention launch, the
+        three carrying GEMM launches, the launch after them."""
+        out = (C.c_int64 * 5)()
+        self._check(self.lib.bs_overlap_report(self.h, out))
+        return [int(v) for v in out]
+
+    def overlap_trace(self, on: bool):
+        self._check(self.lib.bs_overlap_trace(self.h, 1 if on else 0))
+
+    def overlap_trace_read(self, launch: int):
+        """Records of one launch of the last co-scheduled step: uint64 array [n, 4] (see blendstep.h)."""
+        n = C.c_int64()
+        self._check(self.lib.bs_overlap_trace_read(self.h, launch, None, 0, C.byref(n)))
+        out = np.zeros((max(1, n.value), 4), dtype=np.uint64)
+        self._check(self.lib.bs_overlap_trace_read(self.h, launch, out.ctypes.data_as(C.POINTER(C.c_uint64)), n.value,
+                                                   C.byref(n)))
+        return out[:n.value]
 
     def set_gemm_tiles(self, variant: int):
         self._check(self.lib.bs_set_gemm_tiles(self.h, variant))

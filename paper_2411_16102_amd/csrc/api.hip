@@ -22,6 +22,7 @@ using namespace bs;
 namespace {
 
 constexpr int RING = 4;
+constexpr long TRACE_CAP = 8192;  // workgroups per launch that a timeline can hold
 std::string g_create_error;
 
 struct Plan {
@@ -61,10 +62,15 @@ struct bs_ctx {
   std::vector<int32_t> refcount, path_pages, path_chunks, members, blob;
   std::vector<DecodeItem> items, items_wide;
   std::vector<int32_t> pf_work;
-  // overlap
-  hipStream_t side_a = nullptr, side_b = nullptr;  // CU-masked: GEMM side, decode-attention side
-  int cus_a = 256, cus_b = 256;
-  hipEvent_t ev_fork = nullptr, ev_a = nullptr, ev_b = nullptr;
+  // co-scheduling of decode attention with the prefill rows' GEMMs (BS_FLAG_OVERLAP)
+  unsigned *sync_words = nullptr;  // [0..3] queue counters of the launches of a step, [4..6] finished tiles, [8..10] queue position at which each launch closed
+  bs_overlap_knobs ov = {0, 208, 8, 256, -1, 2, 0, 1, 96};
+  int64_t ov_first_bytes = 0;      // KV bytes of the 16-row units that the last co-scheduled step gave to its first attention launch
+  int ov_first_items = 0;          // and their number
+  // optional timeline of the co-scheduled launches: TRACE_CAP workgroups of 8 wavefront records per launch
+  uint64_t *trace_buf = nullptr;
+  long trace_wgs[4] = {0, 0, 0, 0};  // workgroups of the last step's launches
+  int n_cu = 256;
   // tunables
   int chunk_pages = 64;       // pages per chunk of decode-attention work: private tails and nodes with few member rows
   int chunk_pages_wide = 32;  // nodes whose items carry more than 16 query rows: four wavefronts share an item, and every
@@ -510,96 +516,219 @@ int run_attention(bs_ctx *c, const Plan &p, const uint16_t *q, uint16_t *out, co
   return run_decode_merge(c, p, out, st);
 }
 
-// output projection (+ first residual, second norm) and gate/up (+ SwiGLU) for rows [r0, r1)
-int run_o_gate_up(bs_ctx *c, const bs_weights *w, const uint16_t *x, int r0, int r1, hipStream_t st, int n_cu) {
-  const int rows = r1 - r0;
-  if (rows <= 0) return BS_OK;
+// GEMM arguments of the output projection (+ first residual, second norm), of gate/up (+ SwiGLU)
+// and of the down projection (+ second residual) for rows [r0, r1)
+GemmArgs o_proj_args(bs_ctx *c, const bs_weights *w, const uint16_t *x, int r0, int r1) {
   const bs_layer_cfg &g = c->cfg;
-  const int hd = g.n_q_heads * g.head_dim, d = g.d_model, f = g.d_ffn;
+  const int hd = g.n_q_heads * g.head_dim, d = g.d_model;
   GemmArgs o{};
-  o.n_cu = n_cu;
   o.A = c->attn + (size_t)r0 * hd; o.lda = hd; o.B = (const uint16_t *)w->w_o; o.ldb = hd;
-  o.M = rows; o.N = d; o.K = hd;
+  o.M = r1 - r0; o.N = d; o.K = hd;
   o.C32 = c->x1 + (size_t)r0 * d; o.ldc = d; o.resid = x + (size_t)r0 * d; o.ldr = d;
   o.gain = (const uint16_t *)w->g_ffn; o.C_gain = c->xg2 + (size_t)r0 * d;
   o.ss_out = c->ss2 + r0; o.ss_stride = c->cap_rows;
-  o.k_splits = gemm_splitk_choice(rows, d, hd, EPI_RESID_NORM, n_cu);
+  return o;
+}
+
+GemmArgs gate_up_args(bs_ctx *c, const bs_weights *w, int r0, int r1) {
+  const bs_layer_cfg &g = c->cfg;
+  const int d = g.d_model, f = g.d_ffn;
+  GemmArgs u{};
+  u.A = c->xg2 + (size_t)r0 * d; u.lda = d; u.B = (const uint16_t *)w->w_gate_up; u.ldb = d;
+  u.M = r1 - r0; u.N = f; u.K = d;
+  u.C = c->act + (size_t)r0 * f; u.ldc = f;
+  u.rstd = c->rstd2 + r0;
+  return u;
+}
+
+GemmArgs down_args(bs_ctx *c, const bs_weights *w, uint16_t *y, int r0, int r1) {
+  const bs_layer_cfg &g = c->cfg;
+  const int d = g.d_model, f = g.d_ffn;
+  GemmArgs dn{};
+  dn.A = c->act + (size_t)r0 * f; dn.lda = f; dn.B = (const uint16_t *)w->w_down; dn.ldb = f;
+  dn.M = r1 - r0; dn.N = d; dn.K = f;
+  dn.C = y + (size_t)r0 * d; dn.ldc = d; dn.resid32 = c->x1 + (size_t)r0 * d; dn.ldr = d;
+  return dn;
+}
+
+// output projection and gate/up for rows [r0, r1)
+int run_o_gate_up(bs_ctx *c, const bs_weights *w, const uint16_t *x, int r0, int r1, hipStream_t st, int k_o = BS_K_GEMM_O,
+                  int k_gu = BS_K_GEMM_GATE_UP) {
+  const int rows = r1 - r0;
+  if (rows <= 0) return BS_OK;
+  const bs_layer_cfg &g = c->cfg;
+  const int d = g.d_model;
+  GemmArgs o = o_proj_args(c, w, x, r0, r1);
+  o.k_splits = gemm_splitk_choice(rows, d, o.K, EPI_RESID_NORM, 0);
   if (o.k_splits > 1) {
     int rc = ensure_splitk(c, (size_t)o.k_splits * rows * d);
     if (rc) return rc;
     o.splitk_ws = c->splitk_ws;
   }
   const int parts = gemm_ss_parts(o, EPI_RESID_NORM, g.head_dim);
-  SPAN(c, BS_K_GEMM_O, st, {
+  SPAN(c, k_o, st, {
     HIP_TRY(c, launch_gemm(o, EPI_RESID_NORM, g.head_dim, st));
     HIP_TRY(c, launch_rstd_finalize(c->ss2 + r0, parts, c->cap_rows, c->rstd2 + r0, rows, d, g.rms_eps, st));
   });
-  GemmArgs u{};
-  u.n_cu = n_cu;
-  u.A = c->xg2 + (size_t)r0 * d; u.lda = d; u.B = (const uint16_t *)w->w_gate_up; u.ldb = d;
-  u.M = rows; u.N = f; u.K = d;
-  u.C = c->act + (size_t)r0 * f; u.ldc = f;
-  u.rstd = c->rstd2 + r0;
+  const GemmArgs u = gate_up_args(c, w, r0, r1);
   GemmArgs head, tail;
   if (gemm_round_split(u, EPI_SWIGLU, g.head_dim, &head, &tail)) {
-    SPAN(c, BS_K_GEMM_GATE_UP, st, HIP_TRY(c, launch_gemm(head, EPI_SWIGLU, g.head_dim, st)));
-    SPAN(c, BS_K_GEMM_GATE_UP, st, HIP_TRY(c, launch_gemm(tail, EPI_SWIGLU, g.head_dim, st)));
+    SPAN(c, k_gu, st, HIP_TRY(c, launch_gemm(head, EPI_SWIGLU, g.head_dim, st)));
+    SPAN(c, k_gu, st, HIP_TRY(c, launch_gemm(tail, EPI_SWIGLU, g.head_dim, st)));
   } else {
-    SPAN(c, BS_K_GEMM_GATE_UP, st, HIP_TRY(c, launch_gemm(u, EPI_SWIGLU, g.head_dim, st)));
+    SPAN(c, k_gu, st, HIP_TRY(c, launch_gemm(u, EPI_SWIGLU, g.head_dim, st)));
   }
   return BS_OK;
 }
 
 // down projection and second residual for rows [r0, r1)
-int run_down(bs_ctx *c, const bs_weights *w, uint16_t *y, int r0, int r1, hipStream_t st, int n_cu) {
+int run_down(bs_ctx *c, const bs_weights *w, uint16_t *y, int r0, int r1, hipStream_t st, int k_dn = BS_K_GEMM_DOWN) {
   const int rows = r1 - r0;
   if (rows <= 0) return BS_OK;
   const bs_layer_cfg &g = c->cfg;
-  const int d = g.d_model, f = g.d_ffn;
-  GemmArgs dn{};
-  dn.n_cu = n_cu;
-  dn.A = c->act + (size_t)r0 * f; dn.lda = f; dn.B = (const uint16_t *)w->w_down; dn.ldb = f;
-  dn.M = rows; dn.N = d; dn.K = f;
-  dn.C = y + (size_t)r0 * d; dn.ldc = d; dn.resid32 = c->x1 + (size_t)r0 * d; dn.ldr = d;
-  dn.k_splits = gemm_splitk_choice(rows, d, f, EPI_RESID, n_cu);
+  GemmArgs dn = down_args(c, w, y, r0, r1);
+  dn.k_splits = gemm_splitk_choice(rows, dn.N, dn.K, EPI_RESID, 0);
   if (dn.k_splits > 1) {
-    int rc = ensure_splitk(c, (size_t)dn.k_splits * rows * d);
+    int rc = ensure_splitk(c, (size_t)dn.k_splits * rows * dn.N);
     if (rc) return rc;
     dn.splitk_ws = c->splitk_ws;
   }
-  SPAN(c, BS_K_GEMM_DOWN, st, HIP_TRY(c, launch_gemm(dn, EPI_RESID, g.head_dim, st)));
+  SPAN(c, k_dn, st, HIP_TRY(c, launch_gemm(dn, EPI_RESID, g.head_dim, st)));
   return BS_OK;
 }
 
-// Side streams restricted to disjoint CU sets: `decode_cus` CUs (a multiple of 64, the same
-// number in every XCD under either CU numbering) for decode attention, the rest for the GEMMs.
-int make_side_streams(bs_ctx *c, int decode_cus) {
-  if (c->side_a) { (void)hipStreamDestroy(c->side_a); c->side_a = nullptr; }
-  if (c->side_b) { (void)hipStreamDestroy(c->side_b); c->side_b = nullptr; }
-  hipDeviceProp_t prop;
-  HIP_TRY(c, hipGetDeviceProperties(&prop, c->device));
-  const int n_cu = prop.multiProcessorCount;
-  const int words = (n_cu + 31) / 32;
-  std::vector<uint32_t> ma(words, 0u), mb(words, 0u);
-  int na = 0, nb = 0;
-  const int per32 = decode_cus * 32 / std::max(32, n_cu);  // CUs of each block of 32 that go to decode attention
-  for (int i = 0; i < n_cu; ++i) {
-    if (decode_cus > 0 && (i % 32) < per32) { mb[i / 32] |= 1u << (i % 32); ++nb; }
-    else { ma[i / 32] |= 1u << (i % 32); ++na; }
+// The co-scheduled part of a step (BS_FLAG_OVERLAP; Section 3.3: overlapped, compute-bound and
+// memory-bound work cost the larger of their times; Section 2.2, operator-level overlapping
+// between the parts of a batch).  The prefill rows and the decode units that carry more
+// than 16 query rows (shared prefix nodes) have their attention first, in one launch; the
+// 16-row units (private tails: nearly all of the KV bytes) then form a queue that is drained
+// by attention workgroups inside the prefill rows' three GEMM launches, on CUs of their own,
+// and by one launch over the whole chip for what is left.  The decode rows' output
+// projection and FFN follow.  One stream, no events: what overlaps shares a launch.
+int run_coscheduled(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, uint16_t *y, uint16_t *pool,
+                    hipStream_t st) {
+  int rc;
+  const bs_layer_cfg &g = c->cfg;
+  const bs_overlap_knobs &k = c->ov;
+  const int T = p.n_rows, Tp = p.n_prefill_rows, d = g.d_model;
+  const DecodeArgs dargs = decode_args(c, p, c->qbuf, pool);
+  const bool carry_down = k.carry_down != 0;
+  const int n_carriers = carry_down ? 3 : 2;
+
+  // The carrying launches: for each, the tile shape and the number of CUs that go to attention for
+  // its whole duration.  Measured on MI355X: a CU reads 36 GB/s of KV pages whatever its
+  // neighbours do, while the whole chip reads 5.3 TB/s (20.7 GB/s per CU), so a CU that streams
+  // pages beside a GEMM shortens the step's attention time by more than it lengthens the GEMM, as
+  // long as the tiles still fill whole rounds on the CUs that remain: the choice minimises
+  //   rounds(tiles, CUs - head) * tile time  -  head * 36 GB/s * that time / 5.3 TB/s
+  // over both tile shapes and head = head_cus_min, +8, ... (a 256x256 tile sustains 5.8 TFLOP/s
+  // per CU, a 160x256 tile 4.5), never hiding more than the queue still holds.
+  GemmArgs ga[3] = {o_proj_args(c, w, x, 0, Tp), gate_up_args(c, w, 0, Tp), down_args(c, w, y, 0, Tp)};
+  const int epi[3] = {EPI_RESID_NORM, EPI_SWIGLU, EPI_RESID};
+  const int kclass[3] = {BS_K_GEMM_O, BS_K_GEMM_GATE_UP, BS_K_GEMM_DOWN};
+  const size_t per_token = (size_t)2 * g.head_dim * 2 * g.n_kv_heads;
+  int64_t narrow_bytes = 0;
+  for (const DecodeItem &it : c->items) narrow_bytes += (int64_t)it.n_tokens * per_token;
+  const double cu_stream = 36e9, chip_stream = 5.3e12;
+  int head[3], margin[3];
+  double ride_bytes = 0;
+  double left = k.ride_percent >= 0 ? narrow_bytes * (k.ride_percent / 100.0) : (double)narrow_bytes;
+  for (int l = 0; l < n_carriers; ++l) {
+    const int b_rows = epi[l] == EPI_SWIGLU ? 2 * ga[l].N : ga[l].N;
+    double best = 1e300, best_hidden = 0;
+    for (int v = 1; v <= 2; ++v) {  // 256x256, 160x256
+      ga[l].tile_variant = v;
+      const long tiles = gemm_ride_tiles(ga[l], epi[l]);
+      const double tile_s = 2.0 * (v == 1 ? 256 : 160) * 256 * ga[l].K / (v == 1 ? 5.8e12 : 4.5e12);
+      for (int h = k.head_cus_min; h <= std::max(k.head_cus_min, k.head_cus_max); h += 8) {
+        const long cus = c->n_cu - h;
+        if (cus < 8) break;
+        const double t = (double)((tiles + cus - 1) / cus) * tile_s;
+        const double hidden = std::min(left, h * cu_stream * t);
+        const double net = t - hidden / chip_stream;
+        if (net < best) { best = net; best_hidden = hidden; head[l] = h; margin[l] = v; }
+      }
+    }
+    ga[l].tile_variant = margin[l];
+    left -= best_hidden;
+    ride_bytes += best_hidden;
+    // When to stop handing out units.  Tiles of one round end within a few microseconds of each
+    // other, and a unit once begun is finished: where the last round is (nearly) full, the queue
+    // closes as soon as the first tile of that round is done, so the workgroups behind the tiles
+    // find it closed; where the last round leaves CUs idle, those workgroups work on them until
+    // all but close_margin tiles are done.
+    const long tiles = gemm_ride_tiles(ga[l], epi[l]);
+    const long cus = c->n_cu - head[l];
+    const long in_last = tiles - (tiles - 1) / cus * cus;
+    margin[l] = 4 * in_last >= 3 * cus ? (int)in_last - 1 : k.close_margin;
   }
-  if (decode_cus <= 0 || nb == 0 || na == 0 ||
-      hipExtStreamCreateWithCUMask(&c->side_a, words, ma.data()) != hipSuccess ||
-      hipExtStreamCreateWithCUMask(&c->side_b, words, mb.data()) != hipSuccess) {
-    (void)hipGetLastError();
-    if (c->side_a) { (void)hipStreamDestroy(c->side_a); c->side_a = nullptr; }
-    if (c->side_b) { (void)hipStreamDestroy(c->side_b); c->side_b = nullptr; }
-    HIP_TRY(c, hipStreamCreateWithFlags(&c->side_a, hipStreamNonBlocking));
-    HIP_TRY(c, hipStreamCreateWithFlags(&c->side_b, hipStreamNonBlocking));
-    na = nb = n_cu;
+
+  // The 16-row units are sorted longest first; the first attention launch takes the long ones and
+  // the queue what the carrying launches are expected to hide.
+  int n_first = 0;
+  int64_t first_bytes = 0;
+  while (n_first < p.n_narrow && (double)(narrow_bytes - first_bytes) > ride_bytes) {
+    first_bytes += (int64_t)c->items[n_first].n_tokens * per_token;
+    ++n_first;
   }
-  c->cus_a = na;
-  c->cus_b = nb;
-  return BS_OK;
+  c->ov_first_bytes = first_bytes;
+  c->ov_first_items = n_first;
+
+  // attention of the prefill rows, of the wide decode items and of the 16-row units that do not ride
+  if ((p.n_wide > 0 || n_first > 0) && p.n_pf_work > 0 && blended_attn_possible(attn_shape(c))) {
+    const PrefillArgs pf = prefill_args(c, p, c->qbuf, c->attn, pool);
+    SPAN(c, BS_K_ATTN_DECODE, st, HIP_TRY(c, launch_blended_attn(dargs, p.n_wide, n_first, pf, st)));
+  } else {
+    if ((rc = run_prefill_attn(c, p, c->qbuf, c->attn, pool, st))) return rc;
+    if (p.n_wide > 0 || n_first > 0)
+      SPAN(c, BS_K_ATTN_DECODE, st, HIP_TRY(c, launch_decode_attn(dargs, p.n_wide, n_first, st)));
+  }
+
+  GemmRide ride{};
+  ride.q.d = dargs;
+  ride.q.first_item = p.n_wide + n_first;
+  ride.q.n_units = (p.n_narrow - n_first) * g.n_kv_heads;
+  ride.q.waves = k.attention_waves;
+  if (c->trace_buf) HIP_TRY(c, hipMemsetAsync(c->trace_buf, 0, sizeof(uint64_t) * 4 * TRACE_CAP * 8 * TRACE_WORDS, st));
+  // timeline records of launch l (grid of `wgs` workgroups), if a timeline is being taken and the grid fits
+  auto trace_of = [&](int l, long wgs) -> uint64_t * {
+    c->trace_wgs[l] = (c->trace_buf && wgs <= TRACE_CAP) ? wgs : 0;
+    return c->trace_wgs[l] ? c->trace_buf + (size_t)l * TRACE_CAP * 8 * TRACE_WORDS : nullptr;
+  };
+  for (long &n : c->trace_wgs) n = 0;
+  for (int l = 0; l < n_carriers; ++l) {
+    const bool last = l == n_carriers - 1;
+    ride.head = head[l];
+    ride.tail = k.tail_workgroups;
+    // the last carrying launch never closes the queue when it is to drain it: its attention
+    // workgroups (at least eight behind the tiles) then go on until the queue is empty
+    ride.close_margin = (last && k.drain_in_last) ? -1 : margin[l];
+    if (last && k.drain_in_last) ride.tail = std::max(ride.tail, c->n_cu - ride.head);
+    ride.q.ticket = c->sync_words + l;
+    ride.ticket_next = c->sync_words + l + 1;
+    ride.done = c->sync_words + 4 + l;
+    ride.closed_at = c->sync_words + 8 + l;
+    ride.q.trace = trace_of(l, ride.head + ride.tail + gemm_ride_tiles(ga[l], epi[l]));
+    if (l == 0) {
+      const int parts = gemm_ss_parts(ga[0], EPI_RESID_NORM, g.head_dim);
+      SPAN(c, kclass[0], st, {
+        HIP_TRY(c, launch_gemm_with_attention(ga[0], epi[0], g.head_dim, ride, st));
+        HIP_TRY(c, launch_rstd_finalize(c->ss2, parts, c->cap_rows, c->rstd2, Tp, d, g.rms_eps, st));
+      });
+    } else {
+      SPAN(c, kclass[l], st, HIP_TRY(c, launch_gemm_with_attention(ga[l], epi[l], g.head_dim, ride, st)));
+    }
+  }
+  if (!k.drain_in_last) {  // what the carrying launches left of the queue, on the whole chip
+    DecodeQueue rest = ride.q;
+    rest.ticket = c->sync_words + n_carriers;
+    rest.trace = trace_of(3, c->n_cu);
+    SPAN(c, BS_K_ATTN_QUEUE_REST, st, HIP_TRY(c, launch_decode_queue(rest, c->n_cu, st)));
+  }
+  if ((rc = run_decode_merge(c, p, c->attn, st))) return rc;
+  if ((rc = run_o_gate_up(c, w, x, Tp, T, st, BS_K_GEMM_DECODE_ROWS, BS_K_GEMM_DECODE_ROWS))) return rc;
+  if (carry_down) return run_down(c, w, y, Tp, T, st, BS_K_GEMM_DECODE_ROWS);
+  return run_down(c, w, y, 0, T, st);
 }
 
 int check_cfg(const bs_layer_cfg *g) {
@@ -642,10 +771,13 @@ int bs_create(const bs_layer_cfg *cfg, int device, bs_ctx **out) {
   if (e != hipSuccess) { c->err = std::string("rope table: ") + hipGetErrorString(e); return bail(BS_EHIP); }
   for (int i = 0; i < RING; ++i)
     if (hipEventCreateWithFlags(&c->h_ev[i], hipEventDisableTiming) != hipSuccess) { c->err = "hipEventCreate failed"; return bail(BS_EHIP); }
-  if (make_side_streams(c, 64) != BS_OK ||
-      hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&c->ev_a, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&c->ev_b, hipEventDisableTiming) != hipSuccess) { if (c->err.empty()) c->err = "side stream setup failed"; return bail(BS_EHIP); }
+  if ((rc = dev_alloc(c, &c->sync_words, 16))) return bail(rc);
+  if (hipMemset(c->sync_words, 0, 16 * sizeof(unsigned)) != hipSuccess) { c->err = "hipMemset failed"; return bail(BS_EHIP); }
+  {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) { c->err = "hipGetDeviceProperties failed"; return bail(BS_EHIP); }
+    c->n_cu = prop.multiProcessorCount;
+  }
   *out = c;
   return BS_OK;
 }
@@ -657,17 +789,12 @@ void bs_destroy(bs_ctx *c) {
   (void)hipDeviceSynchronize();
   for (void *p : {(void *)c->rope_cos, (void *)c->rope_sin, (void *)c->xg, (void *)c->qbuf, (void *)c->attn, (void *)c->x1,
                   (void *)c->xg2, (void *)c->act, (void *)c->rstd1, (void *)c->rstd2, (void *)c->ss2, (void *)c->part_acc, (void *)c->part_m,
-                  (void *)c->part_l, (void *)c->d_blob, (void *)c->splitk_ws, (void *)c->hid[0], (void *)c->hid[1]})
+                  (void *)c->part_l, (void *)c->d_blob, (void *)c->splitk_ws, (void *)c->hid[0], (void *)c->hid[1], (void *)c->sync_words, (void *)c->trace_buf})
     if (p) (void)hipFree(p);
   for (int i = 0; i < RING; ++i) {
     if (c->h_blob[i]) (void)hipHostFree(c->h_blob[i]);
     (void)hipEventDestroy(c->h_ev[i]);
   }
-  if (c->side_a) (void)hipStreamDestroy(c->side_a);
-  if (c->side_b) (void)hipStreamDestroy(c->side_b);
-  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
-  if (c->ev_a) (void)hipEventDestroy(c->ev_a);
-  if (c->ev_b) (void)hipEventDestroy(c->ev_b);
   for (auto &v : c->spans) for (auto &s : v) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
   for (auto e : c->free_events) (void)hipEventDestroy(e);
   delete c;
@@ -726,8 +853,9 @@ int run_layer(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, 
               uint32_t flags) {
   int rc;
   const bs_layer_cfg &g = c->cfg;
-  const int T = p.n_rows, d = g.d_model, hd = g.n_q_heads * g.head_dim;
-  SPAN(c, BS_K_PREP, st, HIP_TRY(c, launch_norm_prep(x, (const uint16_t *)w->g_attn, c->xg, c->rstd1, T, d, g.rms_eps, st)));
+  const int T = p.n_rows, d = g.d_model;
+  // (the prep kernel also clears the counters of the co-scheduled launches)
+  SPAN(c, BS_K_PREP, st, HIP_TRY(c, launch_norm_prep(x, (const uint16_t *)w->g_attn, c->xg, c->rstd1, T, d, g.rms_eps, c->sync_words, 16, st)));
   GemmArgs q{};
   q.A = c->xg; q.lda = d; q.B = (const uint16_t *)w->w_qkv; q.ldb = d;
   q.M = T; q.N = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim; q.K = d;
@@ -742,32 +870,14 @@ int run_layer(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, 
     q.splitk_ws = c->splitk_ws;
   }
   SPAN(c, BS_K_GEMM_QKV, st, HIP_TRY(c, launch_gemm(q, EPI_QKV, g.head_dim, st)));
-  (void)hd;
 
-  const bool overlap = (flags & BS_FLAG_OVERLAP) && p.n_decode > 0 && p.n_prefill_rows > 0;
-  if (!overlap) {
-    if ((rc = run_attention(c, p, c->qbuf, c->attn, pool, st))) return rc;
-    if ((rc = run_o_gate_up(c, w, x, 0, T, st, 0))) return rc;
-    if ((rc = run_down(c, w, y, 0, T, st, 0))) return rc;
-  } else {
-    // Decode attention (HBM-bound) on its own CU set while the prefill rows go through
-    // attention, output projection and gate/up (MFMA-bound) on the other CUs; then the decode
-    // rows' projection and gate/up, and one down projection over all rows, on the whole chip.
-    const int Tp = p.n_prefill_rows;
-    HIP_TRY(c, hipEventRecord(c->ev_fork, st));
-    HIP_TRY(c, hipStreamWaitEvent(c->side_b, c->ev_fork, 0));
-    HIP_TRY(c, hipStreamWaitEvent(c->side_a, c->ev_fork, 0));
-    if ((rc = run_decode_attn(c, p, c->qbuf, c->attn, pool, c->side_b))) return rc;
-    HIP_TRY(c, hipEventRecord(c->ev_b, c->side_b));
-    if ((rc = run_prefill_attn(c, p, c->qbuf, c->attn, pool, c->side_a))) return rc;
-    if ((rc = run_o_gate_up(c, w, x, 0, Tp, c->side_a, c->cus_a))) return rc;
-    HIP_TRY(c, hipEventRecord(c->ev_a, c->side_a));
-    HIP_TRY(c, hipStreamWaitEvent(st, c->ev_a, 0));
-    HIP_TRY(c, hipStreamWaitEvent(st, c->ev_b, 0));
-    if ((rc = run_o_gate_up(c, w, x, Tp, T, st, 0))) return rc;
-    if ((rc = run_down(c, w, y, 0, T, st, 0))) return rc;
-  }
-  return BS_OK;
+  // co-scheduling pays where there are GEMM rows that do not wait for decode attention (the
+  // prefill rows) and 16-row decode units to run beside them
+  const bool blend = (flags & BS_FLAG_OVERLAP) && p.n_narrow > 0 && p.n_prefill_rows >= c->ov.min_prefill_rows;
+  if (blend) return run_coscheduled(c, p, w, x, y, pool, st);
+  if ((rc = run_attention(c, p, c->qbuf, c->attn, pool, st))) return rc;
+  if ((rc = run_o_gate_up(c, w, x, 0, T, st))) return rc;
+  return run_down(c, w, y, 0, T, st);
 }
 
 bool weights_ok(const bs_weights *w) {
@@ -905,13 +1015,81 @@ int bs_set_gemm_tiles(bs_ctx *c, int32_t variant) {
   return BS_OK;
 }
 
-int bs_set_overlap_cus(bs_ctx *c, int32_t decode_cus) {
+int bs_overlap_trace(bs_ctx *c, int on) {
   if (!c) return BS_EINVAL;
   if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
-  if (decode_cus < 0 || decode_cus > 192 || decode_cus % 64) return fail(c, BS_EINVAL, "decode_cus %d (0, 64, 128 or 192)", decode_cus);
   HIP_TRY(c, hipSetDevice(c->device));
   HIP_TRY(c, hipDeviceSynchronize());
-  return make_side_streams(c, decode_cus);
+  for (long &n : c->trace_wgs) n = 0;
+  if (on && !c->trace_buf) return dev_alloc(c, &c->trace_buf, (size_t)4 * TRACE_CAP * 8 * TRACE_WORDS);
+  if (!on && c->trace_buf) return dev_alloc(c, &c->trace_buf, 0);
+  return BS_OK;
+}
+
+int bs_overlap_trace_read(bs_ctx *c, int32_t launch, uint64_t *out, int64_t cap_records, int64_t *n_records) {
+  if (!c) return BS_EINVAL;
+  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
+  if (launch < 0 || launch > 3 || !n_records || cap_records < 0 || (cap_records > 0 && !out))
+    return fail(c, BS_EINVAL, "bs_overlap_trace_read: bad argument");
+  const int64_t n = c->trace_buf ? c->trace_wgs[launch] * 8 : 0;
+  *n_records = n;
+  if (n == 0 || cap_records == 0) return BS_OK;
+  HIP_TRY(c, hipSetDevice(c->device));
+  HIP_TRY(c, hipDeviceSynchronize());
+  HIP_TRY(c, hipMemcpy(out, c->trace_buf + (size_t)launch * TRACE_CAP * 8 * TRACE_WORDS,
+                       sizeof(uint64_t) * TRACE_WORDS * (size_t)std::min(n, cap_records), hipMemcpyDeviceToHost));
+  return BS_OK;
+}
+
+int bs_overlap_report(bs_ctx *c, int64_t *kv_bytes) {
+  if (!c) return BS_EINVAL;
+  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
+  if (!kv_bytes) return fail(c, BS_EINVAL, "bs_overlap_report: NULL argument");
+  HIP_TRY(c, hipSetDevice(c->device));
+  HIP_TRY(c, hipDeviceSynchronize());
+  unsigned words[16];
+  HIP_TRY(c, hipMemcpy(words, c->sync_words, sizeof words, hipMemcpyDeviceToHost));
+  const int hkv = c->cfg.n_kv_heads;
+  const long first = (long)c->ov_first_items * hkv;
+  const long n_units = (long)c->items.size() * hkv - first;
+  // the queue positions at which the carrying launches closed; a launch that did not close (the one
+  // that drains the queue, or a launch that did not run) took everything that was left
+  long pos[5] = {0, n_units, n_units, n_units, n_units};
+  for (int l = 1; l <= 3; ++l)
+    if (words[l - 1] >= DECODE_QUEUE_CLOSED) pos[l] = std::min<long>(words[8 + l - 1], n_units);
+  for (int l = 1; l <= 3; ++l) pos[l] = std::max(pos[l], pos[l - 1]);
+  const int64_t per_token = (int64_t)2 * c->cfg.head_dim * 2;  // K and V of one token and KV head
+  kv_bytes[0] = c->ov_first_bytes;
+  for (int l = 0; l < 4; ++l) {
+    int64_t tokens = 0;
+    for (long u = pos[l]; u < pos[l + 1]; ++u) tokens += c->items[(size_t)((first + u) / hkv)].n_tokens;
+    kv_bytes[1 + l] = tokens * per_token;
+  }
+  return BS_OK;
+}
+
+int bs_set_overlap(bs_ctx *c, const bs_overlap_knobs *k) {
+  if (!c) return BS_EINVAL;
+  if (!k) return fail(c, BS_EINVAL, "bs_set_overlap: NULL argument");
+  if (k->head_cus_min < 0 || k->head_cus_min > 192 || k->head_cus_min % 8)
+    return fail(c, BS_EINVAL, "head_cus_min %d (a multiple of 8, 0..192)", k->head_cus_min);
+  if (k->tail_workgroups < 0 || k->tail_workgroups > 256) return fail(c, BS_EINVAL, "tail_workgroups %d (0..256)", k->tail_workgroups);
+  if (k->close_margin < 0 || k->close_margin > 256) return fail(c, BS_EINVAL, "close_margin %d (0..256)", k->close_margin);
+  if (k->min_prefill_rows < 1) return fail(c, BS_EINVAL, "min_prefill_rows %d (at least 1)", k->min_prefill_rows);
+  if (k->ride_percent < -1 || k->ride_percent > 100) return fail(c, BS_EINVAL, "ride_percent %d (-1 or 0..100)", k->ride_percent);
+  if (k->attention_waves < 1 || k->attention_waves > 8) return fail(c, BS_EINVAL, "attention_waves %d (1..8)", k->attention_waves);
+  if (k->head_cus_max < 0 || k->head_cus_max > 192 || k->head_cus_max % 8)
+    return fail(c, BS_EINVAL, "head_cus_max %d (a multiple of 8, 0..192)", k->head_cus_max);
+  c->ov = *k;
+  c->ov.carry_down = k->carry_down != 0;
+  c->ov.drain_in_last = k->drain_in_last != 0;
+  return BS_OK;
+}
+
+int bs_get_overlap(const bs_ctx *c, bs_overlap_knobs *k) {
+  if (!c || !k) return BS_EINVAL;
+  *k = c->ov;
+  return BS_OK;
 }
 
 /* Tuning knob used by the benchmark sweeps: pages per decode-attention chunk. */

@@ -37,6 +37,28 @@ struct DecodeArgs {
   float *part_m, *part_l;     // [slots][Hq]
 };
 
+// The 16-row units of a step as a queue that several launches drain in turn: unit u is
+// (item first_item + u / Hkv, KV head u % Hkv); a wavefront takes the next unit by adding one
+// to *ticket and stops at the first number >= n_units.  A launch that must hand the rest of
+// the queue on (a GEMM launch that carries attention workgroups: when its last tiles finish)
+// closes its counter by adding DECODE_QUEUE_CLOSED to it and stores the position it found
+// there, capped at n_units, as the start value of the next launch's counter.
+constexpr unsigned DECODE_QUEUE_CLOSED = 0x40000000u;
+struct DecodeQueue {
+  DecodeArgs d;
+  int first_item, n_units;
+  unsigned *ticket;
+  int waves;  // wavefronts of an attention workgroup (of eight) that take units
+  // Optional timeline of the launch (NULL: none): record 8 b + w of 4 x uint64 belongs to wavefront
+  // w of workgroup b: {begin, end} in ticks of the constant 100 MHz clock, {kind | HW_ID << 8 |
+  // XCC_ID << 32}, {units | KV tokens << 32} served in between (tiles: wavefront 0 only).
+  uint64_t *trace;
+};
+enum { TRACE_ATTENTION = 1, TRACE_TILE = 2 };
+constexpr int TRACE_WORDS = 4;
+// what is left in the queue, on the whole chip: workgroups of eight wavefronts, each drawing units
+hipError_t launch_decode_queue(const DecodeQueue &q, int n_workgroups, hipStream_t stream);
+
 // one launch over items [0, n_wide) of up to 64 query rows each, then [n_wide, n_wide + n_narrow) of up to 16
 hipError_t launch_decode_attn(const DecodeArgs &a, int n_wide, int n_narrow, hipStream_t stream);
 

@@ -28,6 +28,7 @@
 // (s_waitcnt vmcnt + s_barrier); the compiler does not track them.
 #include <algorithm>
 #include "gemm.hpp"
+#include "attn_device.hpp"
 #include "common.hpp"
 
 namespace bs {
@@ -77,8 +78,9 @@ constexpr int waitcnt_imm(int vm, bool lgkm0) {
   return (vm & 0xF) | ((vm >> 4) << 14) | 0x70 | (lgkm0 ? 0 : 0xF00);
 }
 
+// One workgroup's tile; `bid` is the workgroup's number among the GEMM workgroups of the launch.
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH, int DEEP = 0>
-__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int bid) {
   constexpr int NW = WAVES_M * WAVES_N;
   // DEEP: the pipeline for one round of tiles over few rows, where every CU streams a weight
   // panel of its own from HBM; the first half of the wavefronts requests the activation
@@ -103,8 +105,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   const int n_lim = a.n_count ? a.n_begin + a.n_count : a.N;  // end of the output columns of this launch
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (n_lim - a.n_begin + OUT_BN - 1) / OUT_BN;
   // split-K: consecutive workgroups are the k-ranges of one tile
-  const int split = (EPI == EPI_PARTIAL) ? (int)blockIdx.x % a.k_splits : 0;
-  const int tile_id = (EPI == EPI_PARTIAL) ? (int)blockIdx.x / a.k_splits : (int)blockIdx.x;
+  const int split = (EPI == EPI_PARTIAL) ? bid % a.k_splits : 0;
+  const int tile_id = (EPI == EPI_PARTIAL) ? bid / a.k_splits : bid;
   const TileCoord tc = map_tile(tile_id, tiles_m * tiles_n, tiles_m, tiles_n);
   const int m0 = tc.tm * BM, n0 = a.n_begin + tc.tn * OUT_BN;
 
@@ -538,6 +540,47 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
     epilogue(Yes{});
 }
 
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH, int DEEP = 0>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmArgs a) {
+  gemm_tile<BM, BN, WAVES_M, WAVES_N, EPI, DH, DEEP>(a, (int)blockIdx.x);
+}
+
+// A GEMM launch that carries decode attention (Section 3.3: a step whose compute-bound and
+// memory-bound operators overlap costs the larger of their times; Section 2.2, operator-level
+// overlapping).  Grid: `head` attention workgroups, the GEMM tiles, `tail` attention
+// workgroups.  A workgroup of either kind takes a whole CU (the tile all of its LDS, either
+// kind half of every SIMD's registers per wavefront), so the two kinds never share one: the
+// head workgroups hold their CUs for as long as the GEMM runs and stream KV pages beside it,
+// the tail workgroups start on the CUs that the last, partly filled round of tiles leaves
+// idle.  The attention wavefronts draw 16-row units from the step's queue; the tile that
+// brings the count of finished tiles to `close_at` closes the queue for this launch and
+// hands its position to the next one, so nobody starts a unit that would outlast the GEMM
+// by more than its own length.  No workgroup ever waits for another.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH, int ADH>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_attn_kernel(const GemmArgs a, const GemmRide r, const int n_tiles,
+                                                                              const unsigned close_at) {
+  static_assert(WAVES_M * WAVES_N == 8, "attention workgroups are written for eight wavefronts");
+  const int b = (int)blockIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  uint64_t *rec = r.q.trace ? r.q.trace + (size_t)TRACE_WORDS * (8 * b + wave) : nullptr;
+  if (b < r.head || b >= r.head + n_tiles) {
+    attn_dev::decode_queue_worker<ADH>(r.q, wave, threadIdx.x & 63, rec);
+    return;
+  }
+  const uint64_t t0 = rec ? wall_clock64() : 0;
+  gemm_tile<BM, BN, WAVES_M, WAVES_N, EPI, DH>(a, b - r.head);
+  if (threadIdx.x == 0) {
+    const unsigned before = atomicAdd(r.done, 1u);
+    if (before + 1 == close_at) {
+      const unsigned pos = atomicAdd(r.q.ticket, DECODE_QUEUE_CLOSED);
+      const unsigned capped = pos < (unsigned)r.q.n_units ? pos : (unsigned)r.q.n_units;
+      atomicExch(r.ticket_next, capped);
+      if (r.closed_at) *r.closed_at = capped;
+    }
+    if (rec) attn_dev::trace_record(rec, t0, TRACE_TILE, before + 1 == close_at ? 1u : 0u, 0u);
+  }
+}
+
 constexpr int MAX_SPLITS = 8;
 
 // four consecutive columns of one row, summed over the k-ranges in a fixed order; the loads are
@@ -652,6 +695,28 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int ADH>
+hipError_t launch_ride(const GemmArgs &a, const GemmRide &r, hipStream_t stream) {
+  constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  constexpr int LDS = NU * (BM > BN ? BM : BN) * BK * 2;
+  static_assert(LDS == 160 * 1024, "a workgroup of either kind must take the whole LDS of its CU");
+  auto kern = gemm_attn_kernel<BM, BN, WAVES_M, WAVES_N, EPI, 64, ADH>;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + OUT_BN - 1) / OUT_BN);
+  if (tiles <= 0) return hipErrorInvalidValue;
+  // (a negative margin: no tile closes the queue, the launch drains it)
+  const int close_at = r.close_margin < 0 ? tiles + 1 : (tiles - r.close_margin > 1 ? tiles - r.close_margin : 1);
+  hipLaunchKernelGGL(kern, dim3(r.head + tiles + r.tail), dim3(WAVES_M * WAVES_N * 64), LDS, stream, a, r, tiles,
+                     (unsigned)close_at);
+  return hipGetLastError();
+}
+
 // Tile shapes.  BIG: 256x256, 8 wavefronts.  TALL: 160x256, 8 wavefronts of 80x64: 2560 (and
 // 5120) rows by 4096 (8192) columns then make exactly one (four) full rounds of 256
 // workgroups where 256x256 tiles leave 38 % (17 %) of the CUs idle.  SMALL: 128x128.
@@ -754,9 +819,55 @@ int gemm_splitk_choice(int M, int N, int K, int epilogue, int n_cu) {
 
 int gemm_ss_parts(const GemmArgs &a, int epilogue, int dh) {
   if (a.k_splits > 1) return 1;  // the split-K reduction leaves whole row sums
-  const int v = choose_variant(a.M, a.N, epilogue, dh, a.n_cu);
+  const int v = a.tile_variant ? a.tile_variant : choose_variant(a.M, a.N, epilogue, dh, a.n_cu);
   // partial row sums: one per (column tile, wavefront column)
   return v == V_SMALL ? ((a.N + 127) / 128) * 2 : ((a.N + 255) / 256) * 4;
+}
+
+int gemm_ride_variant(int m, int n_b_rows, int n_cu) {
+  // the eight-wavefront tiles only: 256x256 or 160x256, by the same cost model of rounds
+  struct Cand { int v, bm; double T, a; };
+  const Cand cands[2] = {{V_BIG, 256, 1.00, 0.72}, {V_TALL, 160, 0.76, 0.65}};
+  if (n_cu <= 0) n_cu = N_CU;
+  int best = V_BIG;
+  double best_t = 1e300;
+  for (const Cand &c : cands) {
+    const long tiles = n_tiles(m, n_b_rows, c.bm, 256);
+    const long full = tiles / n_cu, rem = tiles % n_cu;
+    const double t = (double)full * c.T + (rem ? c.T * (c.a + (1.0 - c.a) * (double)rem / (double)n_cu) : 0.0);
+    if (t < best_t) { best_t = t; best = c.v; }
+  }
+  return best;
+}
+
+int gemm_ride_tiles(const GemmArgs &a, int epilogue) {
+  const int bm = a.tile_variant == V_TALL ? 160 : 256, out_bn = epilogue == EPI_SWIGLU ? 128 : 256;
+  return ((a.M + bm - 1) / bm) * ((a.N + out_bn - 1) / out_bn);
+}
+
+hipError_t launch_gemm_with_attention(const GemmArgs &a, int epilogue, int dh, const GemmRide &r, hipStream_t stream) {
+  (void)dh;
+  if (a.k_splits > 1 || a.n_count || r.head < 0 || r.head % XCDS || r.tail < 0 || !r.done || !r.ticket_next || !r.q.ticket)
+    return hipErrorInvalidValue;
+  const int b_rows = (epilogue == EPI_SWIGLU) ? 2 * a.N : a.N;
+  if ((size_t)a.M * a.lda * 2 >= ((size_t)1 << 32) || (size_t)b_rows * a.ldb * 2 >= ((size_t)1 << 32))
+    return hipErrorInvalidValue;
+  const int v = a.tile_variant ? a.tile_variant : gemm_ride_variant(a.M, b_rows, N_CU - r.head);
+  if (v != V_BIG && v != V_TALL) return hipErrorInvalidValue;
+  const int adh = r.q.d.s.head_dim;
+  if (adh != 64 && adh != 128) return hipErrorInvalidValue;
+#define BS_RIDE(EPI)                                                                                  \
+  return v == V_BIG ? (adh == 128 ? launch_ride<256, 256, 2, 4, EPI, 128>(a, r, stream)               \
+                                  : launch_ride<256, 256, 2, 4, EPI, 64>(a, r, stream))               \
+                    : (adh == 128 ? launch_ride<160, 256, 2, 4, EPI, 128>(a, r, stream)               \
+                                  : launch_ride<160, 256, 2, 4, EPI, 64>(a, r, stream))
+  switch (epilogue) {
+    case EPI_RESID_NORM: BS_RIDE(EPI_RESID_NORM);
+    case EPI_SWIGLU: BS_RIDE(EPI_SWIGLU);
+    case EPI_RESID: BS_RIDE(EPI_RESID);
+    default: return hipErrorInvalidValue;
+  }
+#undef BS_RIDE
 }
 
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream) {

@@ -6,6 +6,8 @@
 #include <stdint.h>
 #include <hip/hip_runtime.h>
 
+#include "attn.hpp"
+
 namespace bs {
 
 enum GemmEpilogue {
@@ -51,6 +53,24 @@ struct GemmArgs {
   uint16_t *q_out;    // [M, Hq*dh]
   uint16_t *kv_pool;  // pages: [2][Hkv][...]
 };
+
+// Decode attention that shares a GEMM launch (see gemm_attn_kernel in gemm.hip).
+struct GemmRide {
+  DecodeQueue q;          // the step's queue of 16-row units; q.ticket is this launch's counter
+  int head, tail;         // attention workgroups ahead of the tiles (a multiple of 8) and behind them
+  unsigned *done;         // tiles of this launch that have finished (zero at launch)
+  int close_margin;       // the queue closes for this launch when all but this many tiles have finished (negative: never)
+  unsigned *ticket_next;  // where the closing tile leaves the queue position for the next launch
+  unsigned *closed_at;    // and a copy that nobody adds to, for the report of where the attention ran (may be NULL)
+};
+// The GEMM on `n_cu - ride.head` CUs' worth of 256x256 or 160x256 tiles with the attention
+// workgroups of `ride` around them.  Epilogues RESID_NORM, SWIGLU and RESID; no split-K.
+hipError_t launch_gemm_with_attention(const GemmArgs &a, int epilogue, int dh, const GemmRide &ride, hipStream_t stream);
+// tile shape (a value for GemmArgs::tile_variant) that such a launch takes for M rows, `n_b_rows`
+// weight rows and `n_cu` CUs left to the tiles
+int gemm_ride_variant(int m, int n_b_rows, int n_cu);
+// tiles of such a launch (a.tile_variant set)
+int gemm_ride_tiles(const GemmArgs &a, int epilogue);
 
 // Picks a tile shape for the problem and launches on `stream`.  dh is the head
 // dimension (used by EPI_QKV only).  Returns hipSuccess or the launch error.

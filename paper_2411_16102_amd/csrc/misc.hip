@@ -11,8 +11,12 @@ namespace {
 // row; the 1/rms factor commutes with the contraction and is applied in the GEMM
 // epilogue) and rstd = 1 / sqrt(mean(x^2) + eps).
 __global__ __launch_bounds__(256) void norm_prep_kernel(const uint16_t *x, const uint16_t *g, uint16_t *xg,
-                                                       float *rstd, int rows, int d, float eps) {
+                                                       float *rstd, int rows, int d, float eps, unsigned *zero_words,
+                                                       int n_zero) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  // the first kernel of a step also clears the step's counters (a fill in a kernel, not a
+  // memset on the stream, so that a captured step replays it like any other launch)
+  if (blockIdx.x == 0 && (int)threadIdx.x < n_zero) zero_words[threadIdx.x] = 0u;
   const int row = blockIdx.x * 4 + wave;
   if (row >= rows) return;
   const uint16_t *xr = x + (size_t)row * d;
@@ -92,9 +96,10 @@ __global__ void kv_pack_kernel(const uint16_t *k, const uint16_t *v, uint16_t *p
 }  // namespace
 
 hipError_t launch_norm_prep(const uint16_t *x, const uint16_t *g, uint16_t *xg, float *rstd, int rows, int d,
-                            float eps, hipStream_t stream) {
+                            float eps, unsigned *zero_words, int n_zero, hipStream_t stream) {
   if (rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(norm_prep_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, x, g, xg, rstd, rows, d, eps);
+  hipLaunchKernelGGL(norm_prep_kernel, dim3((rows + 3) / 4), dim3(256), 0, stream, x, g, xg, rstd, rows, d, eps,
+                     zero_words, zero_words ? n_zero : 0);
   return hipGetLastError();
 }
 

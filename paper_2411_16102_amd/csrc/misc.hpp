@@ -5,7 +5,7 @@
 
 namespace bs {
 hipError_t launch_norm_prep(const uint16_t *x, const uint16_t *g, uint16_t *xg, float *rstd, int rows, int d,
-                            float eps, hipStream_t stream);
+                            float eps, unsigned *zero_words, int n_zero, hipStream_t stream);
 hipError_t launch_rstd_finalize(const float *part, int n_part, int stride, float *rstd, int rows, int d, float eps,
                                 hipStream_t stream);
 hipError_t launch_rope_table(float *cos_t, float *sin_t, int max_pos, int half, double theta, hipStream_t stream);

@@ -351,12 +351,64 @@ def test_layers_back_to_back(lib):
     assert torch.equal(y0, y1)
 
 
-def test_overlap_mode_matches_serial(lib):
+def run_coscheduled(lib, shape, batch, tens, knobs, chunk_pages=0):
+    import torch
+    layer = lib.Layer(shape, device=0)
+    layer.set_overlap(**knobs)
+    if chunk_pages:
+        layer.set_chunk_pages(chunk_pages)
+    dev = layer.upload(tens, batch)
+    y = layer.blend_step(dev, batch, flags=lib.FLAG_OVERLAP)
+    torch.cuda.synchronize()
+    k, v = layer.unpack_pool(dev.kv_pool, dev.n_pages)
+    return to_np(y), to_np(k), to_np(v)
+
+
+@pytest.mark.parametrize("shape", [W.TINY, W.LayerShape(512, 8, 2, 128, 1288)])
+@pytest.mark.parametrize("knobs", [
+    dict(head_cus_min=8, tail_workgroups=16, close_margin=2, ride_percent=100),
+    dict(head_cus_min=0, tail_workgroups=24, close_margin=0, ride_percent=60),
+    dict(head_cus_min=16, tail_workgroups=0, close_margin=256, ride_percent=100, drain_in_last=0),
+    dict(head_cus_min=48, tail_workgroups=208, close_margin=8, ride_percent=-1, attention_waves=4),
+    dict(head_cus_min=8, tail_workgroups=8, close_margin=1, ride_percent=80, carry_down=0),
+    dict(head_cus_min=8, tail_workgroups=8, close_margin=1, ride_percent=0)])
+def test_coscheduled_step_matches_the_oracle(lib, shape, knobs):
+    # decode attention of the 16-row units inside the prefill rows' GEMM launches: attention
+    # workgroups ahead of the tiles only, behind them only, both; a queue that closes at once
+    # (margin beyond the tile count) with everything left to a launch of its own; all units,
+    # some or none of them waiting for the carrying launches; two or three carrying launches;
+    # several chunks per tail, so the queue is longer than the workers are many
+    knobs = dict(knobs, min_prefill_rows=1)
+    batch = W.batch_random(17, n_prefill=4, n_decode=60, max_q=150, max_ctx=700, n_roots=3)
+    tens = W.make_tensors(shape, batch, 17, gains="random")
+    ref = O.layer_step(shape, tens, batch)
+    y, k, v = run_coscheduled(lib, shape, batch, tens, knobs, chunk_pages=4)
+    maxrel, mae = errs(y, ref["y"])
+    print("co-scheduled %s: maxrel=%.3e mae=%.3e" % (knobs, maxrel, mae))
+    assert np.isfinite(y).all()
+    assert maxrel <= MAXREL and mae <= (MAE if shape is W.TINY else 2 * MAE)
+    kn = k[ref["dest"][:, 0], ref["dest"][:, 1]]
+    assert errs(kn, ref["k_new"])[0] <= MAXREL
+
+
+def test_coscheduled_step_agrees_with_the_serial_one(lib):
+    # same arithmetic per output element; the GEMM tile shapes differ (the carrying launches use the
+    # eight-wavefront tiles), so the fp32 sums may round differently: equal to within a bf16 step
     batch = W.batch_random(4, n_prefill=4, n_decode=30, max_q=120, max_ctx=500)
     tens = W.make_tensors(W.TINY, batch, 4)
     y0, _, _, _ = run_step(lib, W.TINY, batch, tens, 0)
-    y1, _, _, _ = run_step(lib, W.TINY, batch, tens, 1)
-    assert np.array_equal(y0, y1)
+    y1, _, _ = run_coscheduled(lib, W.TINY, batch, tens, dict(head_cus_min=8, tail_workgroups=16, min_prefill_rows=1))
+    assert np.max(np.abs(y0 - y1)) <= 2.0 ** -7 * np.max(np.abs(y0))
+    assert np.mean(np.abs(y0 - y1)) <= 1e-4
+
+
+def test_coscheduled_flag_falls_back_where_nothing_can_overlap(lib):
+    # no prefill rows, or no decode rows: the flag changes nothing
+    for batch in (W.batch_decode_only(33, 130, seed=2), W.batch_prefill_only(3, 75, seed=2)):
+        tens = W.make_tensors(W.TINY, batch, 2)
+        y0, _, _, _ = run_step(lib, W.TINY, batch, tens, 0)
+        y1, _, _ = run_coscheduled(lib, W.TINY, batch, tens, dict(head_cus_min=8, tail_workgroups=16, min_prefill_rows=1))
+        assert np.array_equal(y0, y1)
 
 
 def test_repeated_calls_and_growing_workspace(lib):

@@ -145,3 +145,13 @@ def test_tuning_knobs_reject_values_outside_their_range(host_layer):
         assert host_layer.lib.bs_set_chunk_pages(host_layer.h, ok) == 0
     assert host_layer.lib.bs_set_gemm_tiles(host_layer.h, 4) == -1
     assert host_layer.lib.bs_set_gemm_tiles(host_layer.h, 0) == 0
+    good = host_layer.get_overlap()
+    for bad in (dict(head_cus_min=4), dict(head_cus_min=200), dict(head_cus_min=-8), dict(tail_workgroups=257),
+                dict(close_margin=-1), dict(min_prefill_rows=0), dict(ride_percent=101), dict(ride_percent=-2),
+                dict(attention_waves=0), dict(attention_waves=9), dict(head_cus_max=7), dict(head_cus_max=200)):
+        with pytest.raises(binding.BlendStepError):
+            host_layer.set_overlap(**bad)
+    assert host_layer.get_overlap() == good
+    host_layer.set_overlap(head_cus_min=48, ride_percent=50)
+    assert host_layer.get_overlap()["head_cus_min"] == 48 and host_layer.get_overlap()["ride_percent"] == 50
+    host_layer.set_overlap(**good)
