@@ -256,6 +256,19 @@ int bs_gemm_nt(bs_ctx *ctx, const void *a, const void *b, void *c,
 int bs_attention(bs_ctx *ctx, const bs_batch *batch, const void *q, void *out,
                  const void *kv_pool, int64_t n_pages, void *stream, uint32_t flags);
 
+/*   bs_attention_noalloc: bs_attention for callers that cannot allocate device memory during the call
+ *   (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same
+ *   arguments, same kernels, same result; the descriptor and the partial softmax states of the call live
+ *   in a 16 MiB array that is part of the library's code object (every GPU the library runs on holds its
+ *   own copy until the process ends) instead of the context's growing workspace.  Limits, checked before
+ *   anything is enqueued (BS_EINVAL with a message): the planned descriptor at most 1 MiB, the partial
+ *   states at most 15 MiB (one state of n_q_heads x (head_dim + 2) floats per sequence and chunk of up to
+ *   64 pages along its prefix path and tail), at most 2^15 sequences and prefix nodes, 2^20 pages.  Calls
+ *   on one GPU share the array, whatever their context: calls that overlap in time on one GPU race, and
+ *   nothing in it survives a call.  Makes no hipMalloc / hipFree (bs_create has made all of them). */
+int bs_attention_noalloc(bs_ctx *ctx, const bs_batch *batch, const void *q, void *out,
+                         const void *kv_pool, int64_t n_pages, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

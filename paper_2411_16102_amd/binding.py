@@ -120,6 +120,8 @@ def raw():
         lib.bs_set_gemm_tiles.argtypes = [C.c_void_p, C.c_int32]
         lib.bs_set_overlap.argtypes = [C.c_void_p, C.POINTER(OverlapKnobs)]
         lib.bs_get_overlap.argtypes = [C.c_void_p, C.POINTER(OverlapKnobs)]
+        lib.bs_attention_noalloc.argtypes = [C.c_void_p, C.POINTER(BatchDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                             C.c_void_p]
         lib.bs_overlap_report.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
         lib.bs_overlap_trace.argtypes = [C.c_void_p, C.c_int]
         lib.bs_overlap_trace_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_uint64), C.c_int64, C.POINTER(C.c_int64)]
@@ -300,6 +302,13 @@ class Layer:
         out = self.torch.zeros_like(q)
         self._check(self.lib.bs_attention(self.h, C.byref(d), C.c_void_p(q.data_ptr()), C.c_void_p(out.data_ptr()),
                                           C.c_void_p(kv_pool.data_ptr()), n_pages, self._stream(stream), flags))
+        return out
+
+    def attention_noalloc(self, batch, q, kv_pool, n_pages: int, out, stream=None):
+        """bs_attention_noalloc; `out` is the caller's (nothing is allocated here either)."""
+        d, keep = marshal_batch(batch)
+        self._check(self.lib.bs_attention_noalloc(self.h, C.byref(d), C.c_void_p(q.data_ptr()), C.c_void_p(out.data_ptr()),
+                                                  C.c_void_p(kv_pool.data_ptr()), n_pages, self._stream(stream)))
         return out
 
     def gemm_nt(self, a, b, stream=None):

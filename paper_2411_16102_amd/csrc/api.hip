@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -19,7 +20,19 @@
 
 using namespace bs;
 
+// Scratch of bs_attention_noalloc: the descriptor blob and the partial softmax states of one call live
+// in this array, which every GPU the library runs on holds from the moment the code object is loaded
+// until the process ends.  Host code never uses the array's name as an address: bs_create asks the
+// runtime for the device address once per device and keeps it in g_scratch_ptr.
+#define BS_NOALLOC_BLOB_BYTES (1u << 20)
+#define BS_NOALLOC_SCRATCH_BYTES (16u << 20)
+static __device__ __align__(256) unsigned char scratch[BS_NOALLOC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+unsigned char *g_scratch_ptr[MAX_DEVICES] = {nullptr};
+std::mutex g_scratch_mutex;
 
 constexpr int RING = 4;
 constexpr long TRACE_CAP = 8192;  // workgroups per launch that a timeline can hold
@@ -62,6 +75,8 @@ struct bs_ctx {
   std::vector<int32_t> refcount, path_pages, path_chunks, members, blob;
   std::vector<DecodeItem> items, items_wide;
   std::vector<int32_t> pf_work;
+  std::vector<std::pair<int, std::pair<int, int>>> pf_order;
+  unsigned char *scratch_ptr = nullptr;  // this device's copy of the static scratch array
   // co-scheduling of decode attention with the prefill rows' GEMMs (BS_FLAG_OVERLAP)
   unsigned *sync_words = nullptr;  // [0..3] queue counters of the launches of a step, [4..6] finished tiles, [8..10] queue position at which each launch closed
   bs_overlap_knobs ov = {0, 208, 8, 256, -1, 2, 0, 1, 96};
@@ -156,14 +171,7 @@ int ensure_splitk(bs_ctx *c, size_t floats) {
   return BS_OK;
 }
 
-int ensure_blob(bs_ctx *c, long ints, int slot) {
-  if (ints > c->cap_blob) {
-    const long cap = ints + ints / 4 + 1024;
-    c->cap_blob = 0;
-    int rc = dev_alloc(c, &c->d_blob, (size_t)cap);
-    if (rc) return rc;
-    c->cap_blob = cap;
-  }
+int ensure_blob_host(bs_ctx *c, long ints, int slot) {
   if (ints > c->h_cap[slot]) {
     const long cap = ints + ints / 4 + 1024;
     if (c->h_blob[slot]) { HIP_TRY(c, hipHostFree(c->h_blob[slot])); c->h_blob[slot] = nullptr; c->h_cap[slot] = 0; }
@@ -172,6 +180,17 @@ int ensure_blob(bs_ctx *c, long ints, int slot) {
     c->h_cap[slot] = cap;
   }
   return BS_OK;
+}
+
+int ensure_blob(bs_ctx *c, long ints, int slot) {
+  if (ints > c->cap_blob) {
+    const long cap = ints + ints / 4 + 1024;
+    c->cap_blob = 0;
+    int rc = dev_alloc(c, &c->d_blob, (size_t)cap);
+    if (rc) return rc;
+    c->cap_blob = cap;
+  }
+  return ensure_blob_host(c, ints, slot);
 }
 
 // ---------------------------------------------------------------------------------
@@ -374,7 +393,8 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
   }
   // prefill work: (sequence, block of 64 query rows), longest contexts first
   c->pf_work.clear();
-  std::vector<std::pair<int, std::pair<int, int>>> order;
+  std::vector<std::pair<int, std::pair<int, int>>> &order = c->pf_order;
+  order.clear();
   for (int s = 0; s < b->n_prefill; ++s) {
     const int q = b->row_start[s + 1] - b->row_start[s];
     for (int k = 0; k * 64 < q; ++k) order.push_back({-(b->kv_len[s] - q + std::min(q, k * 64 + 64)), {s, k}});
@@ -408,15 +428,22 @@ int build_plan(bs_ctx *c, const bs_batch *b, Plan &p, bool with_rows) {
   return BS_OK;
 }
 
-int upload_plan(bs_ctx *c, const Plan &p, hipStream_t stream) {
+// Stages the plan in the pinned ring and copies it to `dst` (the context's descriptor buffer, grown
+// on demand, or - no_grow - a buffer of the caller's that is known to be large enough, with the
+// staging slots of bs_create, which are).
+int upload_plan(bs_ctx *c, const Plan &p, hipStream_t stream, int32_t *dst = nullptr, bool no_grow = false) {
   const int slot = c->ring_pos;
   c->ring_pos = (c->ring_pos + 1) % RING;
   if (c->h_ev_live[slot]) HIP_TRY(c, hipEventSynchronize(c->h_ev[slot]));
-  int rc = ensure_blob(c, p.total_ints, slot);
-  if (rc) return rc;
+  if (no_grow) {
+    if (p.total_ints > c->h_cap[slot]) return fail(c, BS_EINVAL, "descriptor of %ld words exceeds the staging slot", p.total_ints);
+  } else {
+    int rc = ensure_blob(c, p.total_ints, slot);
+    if (rc) return rc;
+  }
   if (p.total_ints == 0) return BS_OK;
   std::memcpy(c->h_blob[slot], c->blob.data(), sizeof(int32_t) * p.total_ints);
-  HIP_TRY(c, hipMemcpyAsync(c->d_blob, c->h_blob[slot], sizeof(int32_t) * p.total_ints, hipMemcpyHostToDevice, stream));
+  HIP_TRY(c, hipMemcpyAsync(dst ? dst : c->d_blob, c->h_blob[slot], sizeof(int32_t) * p.total_ints, hipMemcpyHostToDevice, stream));
   HIP_TRY(c, hipEventRecord(c->h_ev[slot], stream));
   c->h_ev_live[slot] = true;
   return BS_OK;
@@ -634,7 +661,6 @@ int run_coscheduled(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_
   double ride_bytes = 0;
   double left = k.ride_percent >= 0 ? narrow_bytes * (k.ride_percent / 100.0) : (double)narrow_bytes;
   for (int l = 0; l < n_carriers; ++l) {
-    const int b_rows = epi[l] == EPI_SWIGLU ? 2 * ga[l].N : ga[l].N;
     double best = 1e300, best_hidden = 0;
     for (int v = 1; v <= 2; ++v) {  // 256x256, 160x256
       ga[l].tile_variant = v;
@@ -771,6 +797,29 @@ int bs_create(const bs_layer_cfg *cfg, int device, bs_ctx **out) {
   if (e != hipSuccess) { c->err = std::string("rope table: ") + hipGetErrorString(e); return bail(BS_EHIP); }
   for (int i = 0; i < RING; ++i)
     if (hipEventCreateWithFlags(&c->h_ev[i], hipEventDisableTiming) != hipSuccess) { c->err = "hipEventCreate failed"; return bail(BS_EHIP); }
+  {  // this device's copy of the static scratch array (each GPU holds its own, at its own address)
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (device < MAX_DEVICES && !g_scratch_ptr[device]) {
+      void *ptr = nullptr;
+      const hipError_t es = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+      if (es != hipSuccess || !ptr) { c->err = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(es); return bail(BS_EHIP); }
+      g_scratch_ptr[device] = static_cast<unsigned char *>(ptr);
+    }
+    c->scratch_ptr = device < MAX_DEVICES ? g_scratch_ptr[device] : nullptr;
+  }
+  // pinned staging for descriptors up to the size bs_attention_noalloc accepts, and host vectors that
+  // such a call then never has to grow
+  for (int i = 0; i < RING; ++i)
+    if ((rc = ensure_blob_host(c, BS_NOALLOC_BLOB_BYTES / sizeof(int32_t), i))) return bail(rc);
+  try {
+    c->blob.reserve(BS_NOALLOC_BLOB_BYTES / sizeof(int32_t));
+    c->items.reserve(BS_NOALLOC_BLOB_BYTES / sizeof(DecodeItem));
+    c->items_wide.reserve(BS_NOALLOC_BLOB_BYTES / sizeof(DecodeItem));
+    c->pf_order.reserve(1 << 15);
+    c->pf_work.reserve(1 << 16);
+    c->refcount.reserve(1 << 20);
+    c->path_pages.reserve(1 << 15); c->path_chunks.reserve(1 << 15); c->members.reserve(1 << 15);
+  } catch (const std::bad_alloc &) { c->err = "out of host memory"; return bail(BS_ENOMEM); }
   if ((rc = dev_alloc(c, &c->sync_words, 16))) return bail(rc);
   if (hipMemset(c->sync_words, 0, 16 * sizeof(unsigned)) != hipSuccess) { c->err = "hipMemset failed"; return bail(BS_EHIP); }
   {
@@ -953,6 +1002,47 @@ int bs_attention(bs_ctx *c, const bs_batch *b, const void *q, void *out, const v
   if ((rc = upload_plan(c, p, st))) return rc;
   if ((rc = run_attention(c, p, (const uint16_t *)q, (uint16_t *)out, (const uint16_t *)pool, st))) return rc;
   return BS_OK;
+}
+
+int bs_attention_noalloc(bs_ctx *c, const bs_batch *b, const void *q, void *out, const void *pool, int64_t n_pages,
+                         void *stream_) {
+  if (!c) return BS_EINVAL;
+  if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
+  if (!c->scratch_ptr) return fail(c, BS_EHIP, "bs_attention_noalloc: no scratch array on device %d", c->device);
+  if (n_pages > (1 << 20)) return fail(c, BS_EINVAL, "bs_attention_noalloc: n_pages %lld exceeds the limit of %d", (long long)n_pages, 1 << 20);
+  if (b && ((long)b->n_seq > (1 << 15) || (long)b->n_nodes > (1 << 15) || (long)b->n_rows > (1 << 20)))
+    return fail(c, BS_EINVAL, "bs_attention_noalloc: more than %d sequences or prefix nodes", 1 << 15);
+  int rc = validate(c, b, n_pages);
+  if (rc) return rc;
+  if (b->n_rows == 0) return BS_OK;
+  if (!q || !out || !pool) return fail(c, BS_EINVAL, "bs_attention_noalloc: NULL pointer");
+  HIP_TRY(c, hipSetDevice(c->device));
+  hipStream_t st = (hipStream_t)stream_;
+  Plan p;
+  if ((rc = build_plan(c, b, p, false))) return rc;
+  // layout of the scratch array: descriptor blob | m | l | acc of the partial states (m and l padded
+  // to whole 16-byte units, so that the accumulators after them stay 16-byte aligned)
+  const size_t hq = c->cfg.n_q_heads, dh = c->cfg.head_dim;
+  const size_t ml_floats = ((size_t)p.n_slots * hq + 3) / 4 * 4;
+  const size_t state_bytes = (2 * ml_floats + (size_t)p.n_slots * hq * dh) * sizeof(float);
+  if ((size_t)p.total_ints * sizeof(int32_t) > BS_NOALLOC_BLOB_BYTES)
+    return fail(c, BS_EINVAL, "bs_attention_noalloc: descriptor of %ld bytes exceeds the limit of %u", p.total_ints * 4L, BS_NOALLOC_BLOB_BYTES);
+  if (state_bytes > BS_NOALLOC_SCRATCH_BYTES - BS_NOALLOC_BLOB_BYTES)
+    return fail(c, BS_EINVAL, "bs_attention_noalloc: %ld partial softmax states (%zu bytes) exceed the limit of %u bytes",
+                p.n_slots, state_bytes, BS_NOALLOC_SCRATCH_BYTES - BS_NOALLOC_BLOB_BYTES);
+  // the kernels take their buffers from the context; for this call they are parts of the scratch array
+  int32_t *const blob0 = c->d_blob;
+  float *const acc0 = c->part_acc, *const m0 = c->part_m, *const l0 = c->part_l;
+  unsigned char *ptr = c->scratch_ptr;
+  c->d_blob = reinterpret_cast<int32_t *>(ptr);
+  c->part_m = reinterpret_cast<float *>(ptr + BS_NOALLOC_BLOB_BYTES);
+  c->part_l = c->part_m + ml_floats;
+  c->part_acc = c->part_l + ml_floats;
+  rc = upload_plan(c, p, st, c->d_blob, true);
+  if (!rc) rc = run_attention(c, p, (const uint16_t *)q, (uint16_t *)out, (const uint16_t *)pool, st);
+  c->d_blob = blob0;
+  c->part_acc = acc0; c->part_m = m0; c->part_l = l0;
+  return rc;
 }
 
 int bs_gemm_nt(bs_ctx *c, const void *a, const void *b, void *out, int32_t m, int32_t n, int32_t k, void *stream) {
