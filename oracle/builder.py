@@ -86,13 +86,21 @@ Figure 6; the batch-density = request-density identity of Section 4.2; linearity
 the memory model in loaded tokens (the ratios of Table 1); brute-force shared-prefix
 lengths, distinct-token counts and sibling order on small random pools; the
 invariants that sorting keeps every parent's child set and that every node's
-requests are contiguous in leaf order.  Absolute densities of the paper's traces
-need its datasets: parity unpinned for those.  Node splitting: pinned by its bounds
-and invariants only (no round without a split, at most N_leaf splits, t = 0 changes
-nothing, unlimited t ends in a non-increasing leaf order, sharing lost = the sum of the
-costs, the worked example of Figure 3 where the low-density request moves to the right
-end); which leaves are outliers where several choices are equally good is this
-file's reading: parity unpinned for that choice.
+requests are contiguous in leaf order.  Admission (`next_batch`): a pool of six
+requests whose M_L, M_R, N_X, C_X are worked out by hand from Algorithm 3's formulas
+in exact fractions, with the requests and chunk lengths that each scanner then admits
+written out, also under prefill and decode caps.  Descriptor (`emit`): the page tables,
+node pages, member runs and leaf nodes of that step and of a two-level prefix tree
+written out by hand.  Absolute densities of the paper's traces need its datasets:
+parity unpinned for those.  Node splitting: its bounds and invariants (no round
+without a split, at most N_leaf splits, t = 0 changes nothing, unlimited t ends in a
+non-increasing leaf order, sharing lost = the sum of the costs, the worked example of
+Figure 3 where the low-density request moves to the right end) and the stopping
+conditions of Section 5.4 by enumeration on pools of at most six leaves: the search
+ends with non-increasing leaf densities (C1) or with no affordable split left (C2)
+among the leaves that lie in no longest non-increasing subsequence at all; which
+leaves are taken as outliers where several choices are equally good is this file's
+reading: parity unpinned for that choice.
 """
 from __future__ import annotations
 

@@ -24,14 +24,20 @@ squares over d and eps inside the root; rotate-half RoPE pairing (i, i+dh/2)
 with angle pos * theta^(-2i/dh); scale 1/sqrt(dh); silu(z) = z / (1 + exp(-z));
 K cached after RoPE) are fields of the shape or stated where they are used.
 
-Arithmetic is float64 throughout (numpy matmul is the one library step).  With
-storage="bf16" the tensors a bf16 pipeline keeps in memory or feeds to a bf16
-matrix unit are rounded to bfloat16 at that point: the GEMM operands x * g_attn
-and x1 * g_ffn (the 1/rms factor is applied to the product afterwards, which is
-the same mathematics), q, k, v, the attention output, the SwiGLU output and y;
-x1 itself stays unrounded (the residual stream inside the layer is kept wider
-than bf16).  This second mode exists to separate operand-rounding error, which
-no bf16 kernel can avoid, from kernel error.
+Arithmetic is float64 throughout (numpy matmul is the one library step): the
+inputs are bfloat16 values, and in float64 the sums of up to 28672 products are
+exact to 1e-13 of their size, so what a comparison against this oracle shows is
+the error of the path under test alone.  A float32 oracle would add an error of
+its own of about 1e-5 relative, and its matmul would have to be blocked to run at
+all at the full sizes; float64 is the stricter reference and the plainer code.
+Parity is claimed against this exact mode only.
+
+storage="bf16" is a DIAGNOSTIC, not a reference: it rounds to bfloat16 every
+tensor that a plain bfloat16 layer writes to memory between two operators, in
+the textbook order (the normalised activations h and h2, q, k, v, the softmax
+probabilities as operand of their product with V, the attention output, x1, the
+SwiGLU output, y), whatever a particular kernel pipeline keeps wider.  Its distance from the exact mode shows how much error bfloat16 storage
+alone puts into the output at a given shape; no test gates on it.
 
 Pins (tests/test_oracle_layer.py): brute-force dense masked attention in pure
 Python on tiny inputs; closed forms for RMSNorm, RoPE and SwiGLU; kv_len = 1,
@@ -107,12 +113,15 @@ def gather_kv(batch, s: int, n_tokens: int, k_pool: np.ndarray, v_pool: np.ndarr
     return K, V
 
 
-def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, first_pos: int) -> np.ndarray:
+def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, first_pos: int, storage: str = "exact") -> np.ndarray:
     """Exact softmax attention of n query rows over one sequence's keys.
 
     q: [n, Hq, dh]; K, V: [L, Hkv, dh] with L = first_pos + n.  Row j sits at
     position first_pos + j and sees keys 0 .. first_pos + j.  Query head h reads
     key/value head h // (Hq / Hkv).  Two passes: row maximum, then exp and sum.
+    storage="bf16" (diagnostic, see the module header): the probabilities are rounded to
+    bfloat16 where they become the operand of the product with V, as in any bfloat16
+    attention; the row sums keep the unrounded values.
     """
     n, hq, dh = q.shape
     L, hkv, _ = K.shape
@@ -127,7 +136,8 @@ def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, first_pos: int) -> np
         s = np.where(visible, s, -np.inf)
         m = np.max(s, axis=1, keepdims=True)
         p = np.exp(s - m)
-        out[:, h, :] = (p @ V[:, kh, :]) / np.sum(p, axis=1, keepdims=True)
+        pv = _store_bf16(p) if storage == "bf16" else p
+        out[:, h, :] = (pv @ V[:, kh, :]) / np.sum(p, axis=1, keepdims=True)
     return out
 
 
@@ -176,11 +186,7 @@ def layer_step(shape, tensors, batch, rows=None, storage: str = "exact"):
         dest[r] = resolve(batch, int(row_seq[r]), int(pos[r]))
 
     idx = np.nonzero(need_qkv)[0]
-    if storage == "bf16":
-        rstd = 1.0 / np.sqrt(np.mean(x[idx] * x[idx], axis=-1, keepdims=True) + shape.rms_eps)
-        qkv = (st(x[idx] * np.asarray(tensors.g_attn, dtype=np.float64)) @ w_qkv) * rstd
-    else:
-        qkv = rmsnorm(x[idx], tensors.g_attn, shape.rms_eps) @ w_qkv
+    qkv = st(rmsnorm(x[idx], tensors.g_attn, shape.rms_eps)) @ w_qkv
     q = rope(qkv[:, :hq * dh].reshape(-1, hq, dh), pos[idx], shape.rope_theta)
     k = rope(qkv[:, hq * dh:(hq + hkv) * dh].reshape(-1, hkv, dh), pos[idx], shape.rope_theta)
     v = qkv[:, (hq + hkv) * dh:].reshape(-1, hkv, dh)
@@ -199,27 +205,21 @@ def layer_step(shape, tensors, batch, rows=None, storage: str = "exact"):
         V = np.concatenate([Vc, v_new[r0:r1]], axis=0)
         sel = np.nonzero(want[r0:r1])[0]
         if len(sel) == r1 - r0:
-            o = attention(q_all[r0:r1], K, V, c)
+            o = attention(q_all[r0:r1], K, V, c, storage)
             attn[r0:r1] = o.reshape(r1 - r0, hq * dh)
         else:
             for j in sel:  # one row at a time over its visible keys
-                o = attention(q_all[r0 + j:r0 + j + 1], K[:c + j + 1], V[:c + j + 1], c + j)
+                o = attention(q_all[r0 + j:r0 + j + 1], K[:c + j + 1], V[:c + j + 1], c + j, storage)
                 attn[r0 + j] = o.reshape(hq * dh)
 
     w = np.nonzero(want)[0]
     a_in = st(attn[w])
     attn[w] = a_in
-    x1w = x[w] + a_in @ np.asarray(tensors.w_o, dtype=np.float64)
+    x1w = st(x[w] + a_in @ np.asarray(tensors.w_o, dtype=np.float64))
     x1[w] = x1w
-    if storage == "bf16":
-        rstd2 = 1.0 / np.sqrt(np.mean(x1w * x1w, axis=-1, keepdims=True) + shape.rms_eps)
-        h2_op = st(x1w * np.asarray(tensors.g_ffn, dtype=np.float64))
-        gate = (h2_op @ np.asarray(tensors.w_gate, dtype=np.float64)) * rstd2
-        up = (h2_op @ np.asarray(tensors.w_up, dtype=np.float64)) * rstd2
-    else:
-        h2 = rmsnorm(x1w, tensors.g_ffn, shape.rms_eps)
-        gate = h2 @ np.asarray(tensors.w_gate, dtype=np.float64)
-        up = h2 @ np.asarray(tensors.w_up, dtype=np.float64)
+    h2 = st(rmsnorm(x1w, tensors.g_ffn, shape.rms_eps))
+    gate = h2 @ np.asarray(tensors.w_gate, dtype=np.float64)
+    up = h2 @ np.asarray(tensors.w_up, dtype=np.float64)
     act = st(silu(gate) * up)
     y[w] = st(x1w + act @ np.asarray(tensors.w_down, dtype=np.float64))
     return dict(y=y, k_new=k_new, v_new=v_new, dest=dest, attn=attn, x1=x1, q=q_all, pos=pos)

@@ -243,3 +243,22 @@ def test_kv_bytes_of_the_attention_variants_match_the_oracle():
         binding.kv_bytes_per_token("gqa", 32, 32, 128, n_kv_heads=5)
     with pytest.raises(ValueError):
         binding.kv_bytes_per_token("xyz", 1)
+
+
+def test_hand_worked_pool_of_the_oracle_pins():
+    # the six-request pool whose admission tests/test_oracle_builder.py works out by hand from
+    # Algorithm 3: the C++ builder must give those same numbers (asserted here directly, not only
+    # through the oracle) and the same descriptor
+    reqs = [OB.Request([1] * 40, 10, 0), OB.Request([2] * 30, 10, 0), OB.Request([3] * 20, 20, 0),
+            OB.Request([4] * 20 + [5] * 4, 40, 33), OB.Request([4] * 20 + [6] * 12, 40, 35),
+            OB.Request([7] * 10, 100, 40)]
+    unit = dict(p_model=1, kv_bytes=1, compute=4.0, bandwidth=1.0)
+    o, b = both(reqs, 1000, hw=unit)
+    assert_same_tree(o, b)
+    gi, gd = assert_same_batch(o, b)
+    assert (gi["n_l"], gi["n_r"], gi["c_l"], gi["c_r"]) == (3, 14, 9, 1)
+    assert list(gd["seq_request"]) == [1, 2, 3, 4, 5] and list(np.diff(gd["row_start"])) == [9, 1, 1, 1, 1]
+    assert list(gd["page_ids"]) == [1, 2, 0, 3, 4, 0, 5, 6, 7, 8, 9] and list(gd["node_page_ids"]) == [0]
+    o2, b2 = both(reqs, 1000, hw=unit)
+    _, gd2 = assert_same_batch(o2, b2, prefill_budget=5, decode_budget=2)
+    assert list(gd2["seq_request"]) == [1, 4, 5]

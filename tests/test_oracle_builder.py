@@ -480,3 +480,159 @@ def test_kv_bytes_of_the_attention_variants():
                 dict(variant="xyz", n_layers=1, n_heads=1, head_dim=1)):
         with pytest.raises(ValueError):
             B.kv_bytes_per_token(**bad)
+
+
+# ---------------------------------------------------------------------------
+# hand-worked pins of the admission (Algorithm 3, Section 5.3), of the descriptor numbering and of
+# the stopping conditions of node splitting (Section 5.4)
+# ---------------------------------------------------------------------------
+def unit_cost_model(mem_bytes):
+    # 2 P / compute = 1/2 and kappa / (2 bandwidth) = 1/2, so rho(R) = A / B; kappa = 1 byte per token
+    return B.CostModel(p_model=1, kv_bytes=1, compute=4.0, bandwidth=1.0, mem_bytes=mem_bytes, page_size=16)
+
+
+def hand_pool():
+    """Six requests.  0, 1, 2: prompts still to be prefilled, short outputs (compute-intensive);
+    3 and 4 decode and share a 20-token prefix; 5 decodes a long output (memory-intensive)."""
+    return [B.Request([1] * 40, d_est=10, n_cached=0),
+            B.Request([2] * 30, d_est=10, n_cached=0),
+            B.Request([3] * 20, d_est=20, n_cached=0),
+            B.Request([4] * 20 + [5] * 4, d_est=40, n_cached=33),
+            B.Request([4] * 20 + [6] * 12, d_est=40, n_cached=35),
+            B.Request([7] * 10, d_est=100, n_cached=40)]
+
+
+def test_next_batch_admits_what_algorithm_3_says_on_a_hand_worked_pool():
+    # Densities by hand, rho(r) = (p + d) / (2 p d + d^2) (Section 4.1 without the p^2 term):
+    #   r0 50/900   r1 40/700   r2 40/1200   r3 64/3520   r4 72/4160   r5 110/12000
+    #   group G = {r3, r4}: A = 20 + 4 + 12 distinct prompt tokens + 80 outputs = 116, B = 7680
+    # Root children by density, compute-intensive first: r1, r0, r2, G (r3 before r4), r5.
+    o = B.BuilderOracle(unit_cost_model(1000), hand_pool())
+    assert o.leaf_order == [1, 0, 2, 3, 4, 5]
+    # Algorithm 3 with R_L = r1, R_R = r5 and the root: A = 136 + 220 = 356, B = 22480
+    rho_rt, rho_l, rho_r = Fraction(356, 22480), Fraction(40, 700), Fraction(110, 12000)
+    M = 1000
+    m_l = M * (rho_rt - rho_r) / (rho_l - rho_r)
+    m_r = M - m_l
+    assert 139 < m_l < 140                                   # 139.02 by hand
+    n_l = math.floor(m_l / (30 + Fraction(10, 2)))           # N = M_X / ((p + d/2) kappa)
+    n_r = math.floor(m_r / (10 + Fraction(100, 2)))
+    c_l = math.floor(n_l * Fraction(30, 10))                 # C = N p / d
+    c_r = math.floor(n_r * Fraction(10, 100))
+    assert (n_l, n_r, c_l, c_r) == (3, 14, 9, 1)
+    info, d = o.next_batch()
+    assert abs(info["m_l"] - float(m_l)) < 1e-9 and abs(info["m_r"] - float(m_r)) < 1e-9
+    assert (info["n_l"], info["n_r"], info["c_l"], info["c_r"]) == (3, 14, 9, 1)
+    # The scanners alternate, left first, and each stops at its first refusal:
+    #   left  r1: 30 prompt tokens against C_L = 9 -> a chunk of 9;   right r5 decodes (N_R 14 -> 13)
+    #   left  r0: C_L is spent -> the left scanner stops;              right r4, then r3 decode
+    #   right r2: 20 prompt tokens against C_R = 1 -> a chunk of 1;   right r0: C_R is spent -> stop
+    assert (info["n_prefill"], info["n_decode"]) == (2, 3)
+    assert list(d["seq_request"]) == [1, 2, 3, 4, 5]          # prefill in admission order, decode in leaf order
+    assert list(np.diff(d["row_start"])) == [9, 1, 1, 1, 1]
+    assert list(d["kv_len"]) == [9, 1, 34, 36, 41]
+    # the same descriptor, every array written out: G's 20 shared tokens hold one whole page, which is
+    # numbered first and heads the tables of r3 and r4; then the prefill segments' pages, then the
+    # decode sequences' private pages in leaf order
+    assert list(d["page_start"]) == [0, 1, 2, 5, 8, 11]
+    assert list(d["page_ids"]) == [1, 2, 0, 3, 4, 0, 5, 6, 7, 8, 9]
+    assert d["n_nodes"] == 1 and list(d["node_parent"]) == [-1]
+    assert list(d["node_page_start"]) == [0, 1] and list(d["node_page_ids"]) == [0]
+    assert list(d["node_seq_first"]) == [2] and list(d["node_seq_count"]) == [2]
+    assert list(d["seq_leaf_node"]) == [-1, -1, 0, 0, -1]
+    assert d["n_pages"] == 10
+
+
+def test_next_batch_caps_split_the_budgets_in_proportion():
+    # the same pool with a prefill cap of 5 tokens and a decode cap of 2 sequences: C_L : C_R = 9 : 1
+    # gives 4 and 1, N_L : N_R = 3 : 14 gives 0 and 2, so the right scanner admits r5 and r4 and then
+    # stops at r3, before it ever reaches r2
+    o = B.BuilderOracle(unit_cost_model(1000), hand_pool())
+    info, d = o.next_batch(prefill_budget=5, decode_budget=2)
+    assert list(d["seq_request"]) == [1, 4, 5]
+    assert list(np.diff(d["row_start"])) == [4, 1, 1]
+    assert d["n_nodes"] == 0                                  # one member of G alone shares nothing
+
+
+def test_emit_numbers_nested_prefix_nodes_by_hand():
+    # Three decoding requests share 32 tokens (two pages), two of them 16 more (a third page); a fourth
+    # shares nothing.  Trie: root -> P[0,32) -> {Q[32,48) -> {a, b}, c}, d.
+    P, Q = list(range(100, 132)), list(range(200, 216))
+    reqs = [B.Request(P + Q + [1, 2], d_est=50, n_cached=50 + 7),         # a: kv 58 -> 4 pages
+            B.Request(P + Q + [3], d_est=60, n_cached=49 + 30),           # b: kv 80 -> 5 pages
+            B.Request(P + [4, 5, 6], d_est=70, n_cached=35),              # c: kv 36 -> 3 pages
+            B.Request([9] * 5, d_est=4000, n_cached=20)]                  # d: kv 21 -> 2 pages
+    o = B.BuilderOracle(unit_cost_model(10 ** 6), reqs)
+    order = o.leaf_order
+    assert sorted(order) == [0, 1, 2, 3]
+    d = o.emit([], [(r, reqs[r].n_cached) for r in range(4)])
+    pos = {r: k for k, r in enumerate(order)}
+    assert list(d["seq_request"]) == order
+    # node 0 = P: pages 0, 1, members a, b, c; node 1 = Q below it: page 2, members a, b
+    assert d["n_nodes"] == 2 and list(d["node_parent"]) == [-1, 0]
+    assert list(d["node_page_start"]) == [0, 2, 3] and list(d["node_page_ids"]) == [0, 1, 2]
+    assert list(d["node_seq_count"]) == [3, 2]
+    assert d["node_seq_first"][0] == min(pos[0], pos[1], pos[2]) and d["node_seq_first"][1] == min(pos[0], pos[1])
+    # private pages follow in sequence order, from page 3 on
+    n_private = {0: 4 - 3, 1: 5 - 3, 2: 3 - 2, 3: 2}
+    nxt = 3
+    for k, r in enumerate(order):
+        tab = list(d["page_ids"][d["page_start"][k]:d["page_start"][k + 1]])
+        shared = [0, 1, 2] if r in (0, 1) else ([0, 1] if r == 2 else [])
+        assert tab == shared + list(range(nxt, nxt + n_private[r])), (r, tab)
+        nxt += n_private[r]
+        assert d["seq_leaf_node"][k] == (1 if r in (0, 1) else (0 if r == 2 else -1))
+    assert d["n_pages"] == nxt == 9
+    # a prefill chunk of request c's sibling position: segments come first and push the members' indices
+    d2 = o.emit([(3, 0, 5)], [(0, reqs[0].n_cached), (1, reqs[1].n_cached)])
+    assert d2["n_prefill"] == 1 and list(d2["kv_len"])[0] == 5 and list(d2["row_start"]) == [0, 5, 6, 7]
+    # with two members left, P and Q share the same member set: P keeps its two pages, Q adds the third
+    assert d2["n_nodes"] == 2 and list(d2["node_seq_first"]) == [1, 1] and list(d2["node_seq_count"]) == [2, 2]
+    assert list(d2["node_page_ids"]) == [0, 1, 2] and list(d2["page_ids"][:1]) == [3]
+
+
+def leaves_in_no_longest_non_increasing_subsequence(vals):
+    n = len(vals)
+    best, sets = 0, []
+    for mask in range(1 << n):
+        pick = [i for i in range(n) if mask >> i & 1]
+        if all(vals[pick[k]] >= vals[pick[k + 1]] for k in range(len(pick) - 1)):
+            if len(pick) > best:
+                best, sets = len(pick), [set(pick)]
+            elif len(pick) == best:
+                sets.append(set(pick))
+    in_any = set().union(*sets) if sets else set()
+    return [i for i in range(n) if i not in in_any]
+
+
+@pytest.mark.parametrize("seed", range(150))
+def test_split_stops_on_c1_or_c2_brute_force(seed):
+    # Section 5.4: the search ends when the leaf densities are non-increasing (C1) or when every
+    # remaining split costs more than t (C2), and no leaf is split twice.  Pools of at most six
+    # leaves; "remaining split" is taken in the narrowest sense that any reading shares: a leaf
+    # that belongs to NO longest non-increasing subsequence of the leaf densities (found by
+    # enumeration here) is out of place whichever subsequence one keeps.
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(3, 7))
+    pref = [[int(t) for t in rng.integers(0, 50, int(rng.integers(4, 40)))] for _ in range(2)]
+    reqs = []
+    for _ in range(n):
+        g = int(rng.integers(0, 3))
+        own = [int(t) for t in rng.integers(50, 1000, int(rng.integers(1, 12)))]
+        reqs.append(B.Request((pref[g] if g < 2 else []) + own, d_est=int(rng.choice([2, 5, 50, 400, 3000]))))
+    base = B.BuilderOracle(cm(), reqs)
+    for t in (10, 25, 10 ** 9):
+        o = B.BuilderOracle(cm(), reqs)
+        info = o.split(t)
+        assert info["n_split"] == len(o.detached) <= n and info["rounds"] <= n
+        for r in o.detached:                      # only leaves that shared at most t tokens moved
+            assert [x for x in base.nodes if x.req == r][0].start <= t
+        dens = [Fraction(10 ** 30) if b == 0 else Fraction(a, b) for a, b in o.leaf_keys()]
+        assert info["monotone"] == non_increasing(leaf_density(o))
+        if info["monotone"]:
+            continue                              # C1
+        leaf_of = {nd.req: nd for nd in o.nodes if nd.req >= 0}
+        for i in leaves_in_no_longest_non_increasing_subsequence(dens):     # C2
+            r = o.leaf_order[i]
+            lf = leaf_of[r]
+            assert lf.parent == 0 or lf.start > t, "request %d is out of place and could still be split for %d <= %d" % (r, lf.start, t)
