@@ -238,12 +238,16 @@ def main():
         return (time.perf_counter() - t0) / max(1, n)
 
     flags = args.flags
+    schedules_ms = None
     if flags < 0:
+        # both schedules, alternating, the same number of steps each; the faster one is timed
+        n_try = max(5, args.warmup)
         run(max(2, args.warmup // 2), 0)
-        t_serial = run(max(3, args.warmup // 2), 0)
         run(max(2, args.warmup // 2), 1)
-        t_overlap = run(max(3, args.warmup // 2), 1)
+        t_serial = min(run(n_try, 0), run(n_try, 0))
+        t_overlap = min(run(n_try, 1), run(n_try, 1))
         flags = 1 if t_overlap < t_serial else 0
+        schedules_ms = {"serial": t_serial * 1e3 / args.layers, "co_scheduled": t_overlap * 1e3 / args.layers}
     run(args.warmup, flags)
     sec = run(args.steps, flags) / args.layers
 
@@ -266,36 +270,85 @@ def main():
     run(args.steps, flags)
     prof = layer.profile_read()
     layer.profile(False)
+    carried = layer.overlap_report() if flags else None   # of the last step of that pass
+    if schedules_ms is not None:
+        # how much any overlap could give at most: the serial step without its attention launches
+        n0 = max(5, args.warmup)
+        layer.profile(True)
+        run(n0, 0)
+        p0 = layer.profile_read()
+        layer.profile(False)
+        attn_ms = sum(p0[k][0] for k in ("attn_prefill", "attn_decode", "attn_merge")) / (n0 * args.layers)
+        schedules_ms["serial_attention_launches"] = attn_ms
+        schedules_ms["serial_if_attention_were_free"] = schedules_ms["serial"] - attn_ms
     # per kernel class: milliseconds per step and layer (all launches of the class added up)
     kernels = {k: {"ms": ms / (args.steps * args.layers), "launches_per_step": n / (args.steps * args.layers)}
                for k, (ms, n) in prof.items()}
 
     T, d, f = batch.n_rows, shape.d_model, shape.d_ffn
-    gu_flops = 2.0 * T * d * 2 * f
-    # the gate/up GEMM may go out as two launches (whole rounds of tiles, then the rest): its
-    # duration is the sum of its launches' durations, averaged over the GEMMs of the pass
-    n_gemms = args.steps * args.layers
-    gu_ms = prof["gemm_gate_up"][0] / n_gemms
-    gu_flops_per_launch = gu_flops
+    Tp = int(batch.row_start[batch.n_prefill])
+    hd = shape.n_q_heads * shape.head_dim
     t_flop = work["flops"] / PEAK_MFMA_BF16
     t_byte = work["bytes_once"] / PEAK_HBM
     bound = "mfma" if t_flop >= t_byte else "hbm"
-    if bound == "mfma":
-        roofline = {"bound": "mfma", "kernel": "gemm_gate_up (SwiGLU epilogue)",
-                    "achieved": gu_flops_per_launch / (gu_ms * 1e-3) / 1e12, "peak": PEAK_MFMA_BF16 / 1e12,
-                    "unit": "TFLOP/s",
-                    "traffic": (measured_traffic("blended_8b_gemm_gate_up_hbm_traffic.txt",
-                                                 ["gemm.hip", "gemm.hpp", "common.hpp"])
-                                if args.workload == "blended_8b" else None)}
-    else:
-        dec_ms = prof["attn_decode"][0] / n_gemms
-        kv_bytes = work["kv_tokens_once"] * shape.kv_bytes_per_token
-        roofline = {"bound": "hbm", "kernel": "decode_attn (paged, prefix-aware)",
-                    "achieved": kv_bytes / (dec_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
-                    "traffic": (measured_traffic("decode_8b_decode_attn_trace_and_hbm_traffic.txt",
-                                                 ["attn.hip", "attn.hpp", "common.hpp"])
-                                if args.workload == "decode_8b" else None)}
-    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    co = bool(flags) and kernels["gemm_decode_rows"]["launches_per_step"] > 0   # the step took the co-scheduled path
+    rows_g = Tp if co else T     # rows of the output-projection and gate/up launches (co-scheduled: the prefill rows)
+    rows_dn = Tp if (co and layer.get_overlap()["carry_down"]) else T
+    kv_bytes = work["kv_tokens_once"] * shape.kv_bytes_per_token
+
+    def mfma(name, cls, flops, traffic_file=None, extra=None):
+        ms = kernels[cls]["ms"]
+        if ms <= 0:
+            return None
+        r = {"bound": "mfma", "kernel": name, "ms": ms, "achieved": flops / (ms * 1e-3) / 1e12, "peak": PEAK_MFMA_BF16 / 1e12,
+             "unit": "TFLOP/s", "traffic": (measured_traffic(traffic_file, ["gemm.hip", "gemm.hpp", "common.hpp", "attn_device.hpp"])
+                                            if traffic_file else None)}
+        r["frac"] = r["achieved"] / r["peak"]
+        if extra:
+            r.update(extra)
+        return r
+
+    def hbm(name, cls, nbytes, traffic_file=None):
+        ms = kernels[cls]["ms"]
+        if ms <= 0:
+            return None
+        r = {"bound": "hbm", "kernel": name, "ms": ms, "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+             "traffic": (measured_traffic(traffic_file, ["attn.hip", "attn.hpp", "attn_device.hpp", "common.hpp"]) if traffic_file else None)}
+        r["frac"] = r["achieved"] / r["peak"]
+        return r
+
+    def riding(k):   # KV bytes per second that the attention workgroups of carrying launch k read beside its tiles
+        cls = ["gemm_o", "gemm_gate_up", "gemm_down"][k]
+        return {"carried_kv_bytes": carried[1 + k], "carried_kv_GBps": carried[1 + k] / (kernels[cls]["ms"] * 1e-3) / 1e9}
+
+    tag = " of the prefill rows, carrying decode attention" if co else ""
+    per_kernel = [
+        mfma("gemm_qkv (RMSNorm factor, RoPE, KV append)", "gemm_qkv", 2.0 * T * d * shape.n_qkv),
+        mfma("gemm_o (residual, norm statistics)" + tag, "gemm_o", 2.0 * rows_g * hd * d, None, riding(0) if co else None),
+        mfma("gemm_gate_up (SwiGLU epilogue)" + tag, "gemm_gate_up", 2.0 * rows_g * d * 2 * f,
+             "blended_8b_gemm_gate_up_hbm_traffic.txt" if args.workload == "blended_8b" and not co else None,
+             riding(1) if co else None),
+        mfma("gemm_down (residual)" + (tag if rows_dn != T else ""), "gemm_down", 2.0 * rows_dn * f * d, None,
+             riding(2) if (co and rows_dn != T) else None),
+        mfma("output projection, gate/up and down of the decode rows", "gemm_decode_rows",
+             2.0 * (T - Tp) * (hd * d + 2 * d * f) + 2.0 * (T - rows_dn) * f * d) if co else None,
+    ]
+    if co:
+        per_kernel.append(hbm("attention of the prefill rows, the wide decode items and the decode units that do not ride",
+                              "attn_decode", kv_bytes - sum(carried[1:])))
+    elif kernels["attn_decode"]["ms"] > 0:
+        per_kernel.append(hbm("attention (paged, prefix-aware; prefill rows in the same launch)" if kernels["attn_prefill"]["ms"] == 0
+                              else "decode_attn (paged, prefix-aware)", "attn_decode",
+                              kv_bytes if kernels["attn_prefill"]["ms"] == 0 else
+                              kv_bytes - float(np.sum(batch.kv_len[:batch.n_prefill])) * shape.kv_bytes_per_token,
+                              {"blended_8b": "blended_8b_attention_hbm_traffic.txt",
+                               "decode_8b": "decode_8b_decode_attn_trace_and_hbm_traffic.txt"}.get(args.workload)))
+    per_kernel = [r for r in per_kernel if r]
+    # the dominant kernel = the longest launch of the step; the bound-side kernel = the longest one of the
+    # kind that bounds the whole step (a GEMM where the step is MFMA-bound, attention where it is HBM-bound)
+    roofline = max(per_kernel, key=lambda r: r["ms"])
+    side = [r for r in per_kernel if r["bound"] == bound]
+    roofline_bound_side = max(side, key=lambda r: r["ms"]) if side else None
 
     out = {
         "metric": "blended-step tokens/s per layer", "value": T / sec, "unit": "tokens/s",
@@ -306,15 +359,21 @@ def main():
                    "decode_seqs": batch.n_seq - batch.n_prefill, "prefix_nodes": batch.n_nodes,
                    "layers_per_call": args.layers, "d_model": d, "n_q_heads": shape.n_q_heads, "n_kv_heads": shape.n_kv_heads,
                    "head_dim": shape.head_dim, "d_ffn": f, "seed": args.seed,
-                   "schedule": "overlap" if flags else "serial"},
+                   "schedule": ("co-scheduled" if co else "serial")},
         "step_roofline": {"flops": work["flops"], "bytes": work["bytes_once"], "bytes_if_expanded": work["bytes_expanded"],
                           "t_flop_us": t_flop * 1e6, "t_byte_us": t_byte * 1e6, "bound": bound,
                           "frac": max(t_flop, t_byte) / sec},
         "roofline": roofline,
+        "roofline_bound_side": roofline_bound_side,
+        "roofline_per_kernel": [{k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()} for r in per_kernel],
         "kernels_ms": {k: round(v["ms"], 4) for k, v in kernels.items()},
     }
+    if schedules_ms:
+        # the step's compute-bound and memory-bound kernels one after the other (serial) against co-scheduled
+        out["schedules_ms"] = {k: round(v, 4) for k, v in schedules_ms.items()}
+        out["step_roofline"]["frac_if_attention_were_free"] = max(t_flop, t_byte) / (schedules_ms["serial_if_attention_were_free"] * 1e-3)
     if flags:
-        out["overlap_kv_bytes"] = layer.overlap_report()
+        out["overlap_kv_bytes"] = carried
         if args.overlap_trace:
             out["overlap_timeline"] = overlap_timeline(layer, shape, lambda: run_once(flags))
     if batch.n_prefill and batch.n_seq > batch.n_prefill and kernels["attn_prefill"]["launches_per_step"] == 0:

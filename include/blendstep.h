@@ -18,9 +18,13 @@
  *     throws or aborts across this boundary.  A batch is validated on the host
  *     before anything is enqueued: a malformed descriptor is an error code,
  *     never a GPU fault.
- *   - bs_blend_step is asynchronous on the given stream and never synchronises
- *     the device.  Calls on one context must not overlap in time on different
- *     streams (they share the workspace).
+ *   - bs_blend_step is asynchronous on the given stream.  A call that needs more
+ *     workspace than any call before it on the context (more rows, more partial
+ *     softmax states, a longer descriptor) frees and reallocates device memory,
+ *     which synchronises the device; calls within the sizes already seen do not,
+ *     except that a call waits on the host for the fourth-last call's descriptor
+ *     copy (its staging slot).  Calls on one context must not overlap in time on
+ *     different streams (they share the workspace).
  */
 #ifndef BLENDSTEP_H
 #define BLENDSTEP_H
@@ -239,7 +243,7 @@ int bs_overlap_report(bs_ctx *ctx, int64_t *kv_bytes);
 int bs_overlap_trace(bs_ctx *ctx, int on);
 int bs_overlap_trace_read(bs_ctx *ctx, int32_t launch, uint64_t *out, int64_t cap_records, int64_t *n_records);
 
-/* Tuning knob: GEMM tile shape, process-wide: 0 = chosen per problem (default), 1 = 256x256,
+/* Tuning knob: GEMM tile shape for the calls on this context: 0 = chosen per problem (default), 1 = 256x256,
  * 2 = 160x256 (not for the QKV GEMM), 3 = 128x128.  With 0, GEMMs of at most 256 rows run as one
  * row of 128x256 or 256x128 tiles on a pipeline with its own look-ahead for the weight panel; a
  * forced shape switches that off. */

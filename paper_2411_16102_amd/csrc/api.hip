@@ -86,6 +86,7 @@ struct bs_ctx {
   uint64_t *trace_buf = nullptr;
   long trace_wgs[4] = {0, 0, 0, 0};  // workgroups of the last step's launches
   int n_cu = 256;
+  int forced_tiles = 0;            // bs_set_gemm_tiles
   // tunables
   int chunk_pages = 64;       // pages per chunk of decode-attention work: private tails and nodes with few member rows
   int chunk_pages_wide = 32;  // nodes whose items carry more than 16 query rows: four wavefronts share an item, and every
@@ -109,6 +110,20 @@ int fail(bs_ctx *ctx, int code, const char *fmt, ...) {
   va_end(ap);
   if (ctx) ctx->err = buf; else g_create_error = buf;
   return code;
+}
+
+// No exception crosses the C boundary: host allocations (vectors that grow with the batch) can throw.
+template <class F>
+int guarded(bs_ctx *c, F &&body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc &) {
+    return fail(c, BS_ENOMEM, "out of host memory");
+  } catch (const std::exception &e) {
+    return fail(c, BS_EINVAL, "unexpected exception: %s", e.what());
+  } catch (...) {
+    return fail(c, BS_EINVAL, "unexpected exception");
+  }
 }
 
 #define HIP_TRY(ctx, expr)                                                                         \
@@ -856,32 +871,47 @@ int64_t bs_kv_page_bytes(const bs_ctx *c) {
 }
 
 int bs_kv_pack(bs_ctx *c, const void *k, const void *v, void *pool, int64_t n_pages, void *stream) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
   if (!k || !v || !pool || n_pages < 0) return fail(c, BS_EINVAL, "bs_kv_pack: bad argument");
   HIP_TRY(c, launch_kv_pack((const uint16_t *)k, (const uint16_t *)v, (uint16_t *)pool, n_pages, c->cfg.n_kv_heads, c->cfg.head_dim, (hipStream_t)stream));
   return BS_OK;
+  });
 }
 
 int bs_kv_unpack(bs_ctx *c, const void *pool, void *k, void *v, int64_t n_pages, void *stream) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
   if (!k || !v || !pool || n_pages < 0) return fail(c, BS_EINVAL, "bs_kv_unpack: bad argument");
   HIP_TRY(c, launch_kv_unpack((const uint16_t *)pool, (uint16_t *)k, (uint16_t *)v, n_pages, c->cfg.n_kv_heads, c->cfg.head_dim, (hipStream_t)stream));
   return BS_OK;
+  });
 }
 
 int bs_validate_batch(bs_ctx *c, const bs_batch *b, int64_t n_pages) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   return validate(c, b, n_pages);
+  });
 }
 
 int bs_resolve_rows(bs_ctx *c, const bs_batch *b, int32_t *page_out, int32_t *slot_out) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   if (!b || !page_out || !slot_out) return fail(c, BS_EINVAL, "bs_resolve_rows: NULL argument");
+  // the pool size is not an argument here: take the largest page id named (the arrays it sits in are
+  // checked for NULL first; everything else is validate()'s job)
+  if (b->n_seq < 0 || b->n_nodes < 0) return fail(c, BS_EINVAL, "bad counts: n_seq=%d n_nodes=%d", b->n_seq, b->n_nodes);
+  if (b->n_seq > 0 && (!b->page_start || (!b->page_ids && b->page_start[b->n_seq] > 0)))
+    return fail(c, BS_EINVAL, "a required array is NULL");
+  if (b->n_nodes > 0 && (!b->node_page_start || (!b->node_page_ids && b->node_page_start[b->n_nodes] > 0)))
+    return fail(c, BS_EINVAL, "a node array is NULL");
   int64_t max_page = 0;
   for (int i = 0; b->n_seq > 0 && i < b->page_start[b->n_seq]; ++i) max_page = std::max<int64_t>(max_page, b->page_ids[i]);
   for (int i = 0; b->n_nodes > 0 && i < b->node_page_start[b->n_nodes]; ++i) max_page = std::max<int64_t>(max_page, b->node_page_ids[i]);
+  if (max_page >= (int64_t)0x7fffffff) return fail(c, BS_EINVAL, "page id out of range");
   int rc = validate(c, b, max_page + 1);
   if (rc) return rc;
   Plan p;
@@ -891,6 +921,7 @@ int bs_resolve_rows(bs_ctx *c, const bs_batch *b, int32_t *page_out, int32_t *sl
     slot_out[r] = c->blob[p.off_row_slot + r];
   }
   return BS_OK;
+  });
 }
 
 }  // extern "C"
@@ -939,6 +970,7 @@ extern "C" {
 
 int bs_blend_step(bs_ctx *c, const bs_weights *w, const bs_batch *b, const void *x_, void *y_, void *pool_,
                   int64_t n_pages, void *stream_, uint32_t flags) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
   if (!weights_ok(w)) return fail(c, BS_EINVAL, "a weight pointer is NULL");
@@ -947,6 +979,7 @@ int bs_blend_step(bs_ctx *c, const bs_weights *w, const bs_batch *b, const void 
   if (b->n_rows == 0) return BS_OK;
   if (!x_ || !y_ || !pool_ || x_ == y_) return fail(c, BS_EINVAL, "x, y, kv_pool must be distinct non-NULL device pointers");
   HIP_TRY(c, hipSetDevice(c->device));
+  gemm_force_variant(c->forced_tiles);
   hipStream_t st = (hipStream_t)stream_;
   Plan p;
   if ((rc = build_plan(c, b, p, true))) return rc;
@@ -954,10 +987,12 @@ int bs_blend_step(bs_ctx *c, const bs_weights *w, const bs_batch *b, const void 
   if ((rc = ensure_slots(c, p.n_slots))) return rc;
   if ((rc = upload_plan(c, p, st))) return rc;
   return run_layer(c, p, w, (const uint16_t *)x_, (uint16_t *)y_, (uint16_t *)pool_, st, flags);
+  });
 }
 
 int bs_blend_layers(bs_ctx *c, int32_t n_layers, const bs_weights *w, const bs_batch *b, const void *x_, void *y_,
                     void *const *pools, int64_t n_pages, void *stream_, uint32_t flags) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
   if (n_layers < 1 || !w || !pools) return fail(c, BS_EINVAL, "bs_blend_layers: n_layers %d, weights or pools NULL", n_layers);
@@ -968,6 +1003,7 @@ int bs_blend_layers(bs_ctx *c, int32_t n_layers, const bs_weights *w, const bs_b
   if (b->n_rows == 0) return BS_OK;
   if (!x_ || !y_ || x_ == y_) return fail(c, BS_EINVAL, "x and y must be distinct non-NULL device pointers");
   HIP_TRY(c, hipSetDevice(c->device));
+  gemm_force_variant(c->forced_tiles);
   hipStream_t st = (hipStream_t)stream_;
   Plan p;
   if ((rc = build_plan(c, b, p, true))) return rc;
@@ -983,10 +1019,12 @@ int bs_blend_layers(bs_ctx *c, int32_t n_layers, const bs_weights *w, const bs_b
     in = out;
   }
   return BS_OK;
+  });
 }
 
 int bs_attention(bs_ctx *c, const bs_batch *b, const void *q, void *out, const void *pool, int64_t n_pages,
                  void *stream_, uint32_t flags) {
+  return guarded(c, [&]() -> int {
   (void)flags;
   if (!c) return BS_EINVAL;
   if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
@@ -1002,10 +1040,12 @@ int bs_attention(bs_ctx *c, const bs_batch *b, const void *q, void *out, const v
   if ((rc = upload_plan(c, p, st))) return rc;
   if ((rc = run_attention(c, p, (const uint16_t *)q, (uint16_t *)out, (const uint16_t *)pool, st))) return rc;
   return BS_OK;
+  });
 }
 
 int bs_attention_noalloc(bs_ctx *c, const bs_batch *b, const void *q, void *out, const void *pool, int64_t n_pages,
                          void *stream_) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
   if (!c->scratch_ptr) return fail(c, BS_EHIP, "bs_attention_noalloc: no scratch array on device %d", c->device);
@@ -1043,20 +1083,24 @@ int bs_attention_noalloc(bs_ctx *c, const bs_batch *b, const void *q, void *out,
   c->d_blob = blob0;
   c->part_acc = acc0; c->part_m = m0; c->part_l = l0;
   return rc;
+  });
 }
 
 int bs_gemm_nt(bs_ctx *c, const void *a, const void *b, void *out, int32_t m, int32_t n, int32_t k, void *stream) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
   if (m < 0 || n < 0 || k < 0 || (k % 8) || (n % 8)) return fail(c, BS_EINVAL, "bs_gemm_nt: m=%d n=%d k=%d (n, k multiples of 8)", m, n, k);
   if (m == 0 || n == 0) return BS_OK;
   if (!a || !b || !out) return fail(c, BS_EINVAL, "bs_gemm_nt: NULL pointer");
   HIP_TRY(c, hipSetDevice(c->device));
+  gemm_force_variant(c->forced_tiles);
   GemmArgs g{};
   g.A = (const uint16_t *)a; g.lda = k; g.B = (const uint16_t *)b; g.ldb = k;
   g.M = m; g.N = n; g.K = k; g.C = (uint16_t *)out; g.ldc = n;
   HIP_TRY(c, launch_gemm(g, EPI_PLAIN, c->cfg.head_dim, (hipStream_t)stream));
   return BS_OK;
+  });
 }
 
 int bs_profile_enable(bs_ctx *c, int on) {
@@ -1066,6 +1110,7 @@ int bs_profile_enable(bs_ctx *c, int on) {
 }
 
 int bs_profile_reset(bs_ctx *c) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   for (int k = 0; k < BS_K_COUNT; ++k) {
     for (auto &s : c->spans[k]) {
@@ -1078,9 +1123,11 @@ int bs_profile_reset(bs_ctx *c) {
     c->prof_n[k] = 0;
   }
   return BS_OK;
+  });
 }
 
 int bs_profile_read(bs_ctx *c, int which, double *total_ms, int64_t *launches) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   if (which < 0 || which >= BS_K_COUNT) return fail(c, BS_EINVAL, "bs_profile_read: class %d", which);
   for (auto &s : c->spans[which]) {
@@ -1096,16 +1143,18 @@ int bs_profile_read(bs_ctx *c, int which, double *total_ms, int64_t *launches) {
   if (total_ms) *total_ms = c->prof_ms[which];
   if (launches) *launches = c->prof_n[which];
   return BS_OK;
+  });
 }
 
 int bs_set_gemm_tiles(bs_ctx *c, int32_t variant) {
   if (!c) return BS_EINVAL;
   if (variant < 0 || variant > 3) return fail(c, BS_EINVAL, "gemm tile variant %d (0..3)", variant);
-  gemm_force_variant(variant);
+  c->forced_tiles = variant;
   return BS_OK;
 }
 
 int bs_overlap_trace(bs_ctx *c, int on) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
   HIP_TRY(c, hipSetDevice(c->device));
@@ -1114,9 +1163,11 @@ int bs_overlap_trace(bs_ctx *c, int on) {
   if (on && !c->trace_buf) return dev_alloc(c, &c->trace_buf, (size_t)4 * TRACE_CAP * 8 * TRACE_WORDS);
   if (!on && c->trace_buf) return dev_alloc(c, &c->trace_buf, 0);
   return BS_OK;
+  });
 }
 
 int bs_overlap_trace_read(bs_ctx *c, int32_t launch, uint64_t *out, int64_t cap_records, int64_t *n_records) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
   if (launch < 0 || launch > 3 || !n_records || cap_records < 0 || (cap_records > 0 && !out))
@@ -1129,9 +1180,11 @@ int bs_overlap_trace_read(bs_ctx *c, int32_t launch, uint64_t *out, int64_t cap_
   HIP_TRY(c, hipMemcpy(out, c->trace_buf + (size_t)launch * TRACE_CAP * 8 * TRACE_WORDS,
                        sizeof(uint64_t) * TRACE_WORDS * (size_t)std::min(n, cap_records), hipMemcpyDeviceToHost));
   return BS_OK;
+  });
 }
 
 int bs_overlap_report(bs_ctx *c, int64_t *kv_bytes) {
+  return guarded(c, [&]() -> int {
   if (!c) return BS_EINVAL;
   if (c->device == BS_DEVICE_NONE) return fail(c, BS_EINVAL, "host-only context");
   if (!kv_bytes) return fail(c, BS_EINVAL, "bs_overlap_report: NULL argument");
@@ -1156,6 +1209,7 @@ int bs_overlap_report(bs_ctx *c, int64_t *kv_bytes) {
     kv_bytes[1 + l] = tokens * per_token;
   }
   return BS_OK;
+  });
 }
 
 int bs_set_overlap(bs_ctx *c, const bs_overlap_knobs *k) {

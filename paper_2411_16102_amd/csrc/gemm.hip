@@ -728,7 +728,7 @@ constexpr int DEEP_X = 2;
 enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3, V_S128 = 4, V_S256 = 5 };
 constexpr int N_CU = 256;
 
-int g_forced_variant = V_AUTO;
+thread_local int g_forced_variant = V_AUTO;  // set by the calling entry point from its context, for the launches of that call
 
 long n_tiles(int m, int n, int bm, int bn) { return (long)((m + bm - 1) / bm) * ((n + bn - 1) / bn); }
 
@@ -871,6 +871,10 @@ hipError_t launch_gemm_with_attention(const GemmArgs &a, int epilogue, int dh, c
 }
 
 hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stream) {
+  // the kernels address operand rows with 32-bit byte offsets from the matrix base
+  if ((size_t)a.M * a.lda * 2 >= ((size_t)1 << 32) ||
+      (size_t)((epilogue == EPI_SWIGLU) ? 2 * a.N : a.N) * a.ldb * 2 >= ((size_t)1 << 32))
+    return hipErrorInvalidValue;
   if (a.k_splits > 1) {
     if ((epilogue != EPI_RESID && epilogue != EPI_RESID_NORM && epilogue != EPI_QKV) || !a.splitk_ws || a.N % 4)
       return hipErrorInvalidValue;
@@ -889,10 +893,6 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stre
     }
     return hipGetLastError();
   }
-  const int b_rows = (epilogue == EPI_SWIGLU) ? 2 * a.N : a.N;
-  // the kernels address operand rows with 32-bit byte offsets from the matrix base
-  if ((size_t)a.M * a.lda * 2 >= ((size_t)1 << 32) || (size_t)b_rows * a.ldb * 2 >= ((size_t)1 << 32))
-    return hipErrorInvalidValue;
   if (a.n_count && epilogue != EPI_SWIGLU && epilogue != EPI_PLAIN) return hipErrorInvalidValue;
   const int n_cols = a.n_count ? a.n_count : a.N;
   const int v = a.tile_variant ? a.tile_variant
