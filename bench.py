@@ -80,34 +80,38 @@ def overlap_timeline(layer, shape, run_step):
 
 def pool_run(args, lib, W, note):
     """The multi-step driver on a synthetic pool (8B-shaped layer): tokens served per second of
-    device time under each admission order."""
+    device time under each admission order, over one KV pool that persists across the steps."""
     from paper_2411_16102_amd import engine as E
     shape = W.LLAMA3_8B
     budget = 2560
-    reqs = E.synthetic_pool(args.seed, n_groups=args.pool_groups, per_group=12, n_fresh=args.pool_fresh)
+    reqs = W.synthetic_pool(args.seed, n_groups=args.pool_groups, per_group=12, n_fresh=args.pool_fresh,
+                            templates=args.pool_templates)
     prompt = sum(len(r.tokens) for r in reqs)
     outp = sum(r.d_true for r in reqs)
     pages = args.pool_mem_tokens // 16 * 2 + 16384
-    stepper = E.GpuStepper(lib, shape, budget, pages, seed=args.seed)
-    kv_bytes = shape.kv_bytes_per_token
+    stepper = E.GpuStepper(lib, shape, budget, pages, seed=args.seed, flags=max(0, args.flags))
+    hw = dict(p_model=8_030_000_000, kv_bytes=shape.kv_bytes_per_token * 32, compute=PEAK_MFMA_BF16, bandwidth=PEAK_HBM)
     for policy in (["blend", "dfs", "random"] if args.pool == "all" else [args.pool]):
-        b = lib.Builder(8_030_000_000, kv_bytes * 32, PEAK_MFMA_BF16, PEAK_HBM, args.pool_mem_tokens * kv_bytes * 32, 16)
-        eng = E.Engine(b, reqs, args.pool_mem_tokens, policy=policy, token_budget=budget, seed=args.seed,
-                       split_t=4096 if policy == "blend" else 0, split_budget=int(0.01 * prompt),
-                       mem_model=args.pool_mem_model, row_multiple=args.pool_row_multiple)
+        b, sched, split = E.make_scheduler(lib, reqs, hw, args.pool_mem_tokens, budget, pages, policy=policy, seed=args.seed,
+                                           split_t=4096 if policy == "blend" else 0, split_budget=int(0.01 * prompt),
+                                           mem_model=args.pool_mem_model, row_multiple=args.pool_row_multiple)
         stepper.events = []
+        stepper.pool.zero_()
         t0 = time.perf_counter()
-        st = eng.run(stepper, progress=lambda s_: note("%s: step %d, %d finished" % (policy, s_["steps"], s_["finished"])))
+        st = E.serve(sched, stepper, progress=lambda s_: note("%s: step %d, %d finished" % (policy, s_["steps"], s_["finished"])))
         ms = stepper.total_ms()
         wall = time.perf_counter() - t0
         print(json.dumps({
             "metric": "pool tokens/s per layer (prompt + output tokens over the device time of all steps)",
             "value": (prompt + outp) / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "policy": policy,
+            "schedule": "co-scheduled where a step allows" if stepper.flags else "serial",
             "device_ms": ms, "wall_s": wall, "steps": st["steps"], "requests": len(reqs), "prompt_tokens": prompt,
             "output_tokens": outp, "prefill_rows": st["prefill_rows"], "prompt_tokens_skipped": st["prompt_tokens_skipped"],
             "decode_rows": st["decode_rows"], "mean_rows_per_step": st["rows"] / max(1, st["steps"]),
-            "peak_kv_tokens": st["peak_tokens"], "kv_capacity_tokens": args.pool_mem_tokens,
-            "split": eng.split_info, "mem_model": args.pool_mem_model, "row_multiple": args.pool_row_multiple, "relocated": st["relocated"], "dtype": "bf16", "data": "synthetic",
+            "peak_kv_tokens": st["peak_tokens"], "peak_pages": st["peak_pages"], "kv_capacity_tokens": args.pool_mem_tokens,
+            "mem_left": st["mem_left"], "mem_right": st["mem_right"],
+            "split": split, "mem_model": args.pool_mem_model, "row_multiple": args.pool_row_multiple, "templates": args.pool_templates,
+            "relocated": st["relocated"], "dtype": "bf16", "data": "synthetic",
             "config": {"workload": "pool(seed=%d, groups=%d, fresh=%d)" % (args.seed, args.pool_groups, args.pool_fresh), "token_budget": budget,
                        "d_model": shape.d_model, "d_ffn": shape.d_ffn}}), flush=True)
 
@@ -176,6 +180,8 @@ def main():
     ap.add_argument("--pool-mem-model", default="expanded", choices=["expanded", "shared"],
                     help="memory model of the densities: the paper's, or shared prefix pages charged once per step")
     ap.add_argument("--pool-fresh", type=int, default=1500, help="prompt-heavy requests without shared prefix")
+    ap.add_argument("--pool-templates", default="by_kind", choices=["by_kind", "shuffled"],
+                    help="numbering of the datasets' template tokens: the order that hurts the prefix-DFS baseline, or a random one")
     ap.add_argument("--overlap-trace", action="store_true",
                     help="with the co-scheduled schedule: add the in-kernel timeline of one more step to the line")
     ap.add_argument("--copy-calibration", action="store_true",

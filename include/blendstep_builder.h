@@ -145,6 +145,65 @@ int bs_builder_emit(bs_builder *b, int32_t n_pre, const int32_t *pre_req, const 
                     bs_batch_owned **out);
 void bs_batch_free(bs_batch_owned *batch);
 
+/* ---------------------------------------------------------------------------------------------
+ * Multi-step driver: a pool of requests served to completion, one descriptor per step.
+ *
+ * The paper's engine re-forms the runtime batch every iteration (Section 3.2; Appendix A.2, batch
+ * scheduler): every decoding request contributes one row, the rest of the token budget goes to
+ * prefill chunks (Section 2.2), and new requests are admitted from the two ends of the sorted leaf
+ * order, one scanner per end, the KV memory split between the two by Algorithm 3 (Section 5.3) and a
+ * step's prefill rows split C_L : C_R, each side keeping room for one average request of its own.  A
+ * request that ends before its estimate frees its memory at once, one that runs past it is charged
+ * a token per step, and one admitted from the compute-intensive end whose output reaches
+ * relocate_pct per cent of its estimate moves, with its own reservation, to the memory-intensive
+ * partition (Section 5.4).  A shared prompt segment is computed once, by the first resident request
+ * that needs it (requests that need a segment somebody is still computing wait), counted once in
+ * the memory account while any request below it is resident, and its KV pages are referenced by
+ * all of them (Appendix A.2, runtime prefix tree).
+ *
+ * KV pages are physical and stable: a page is taken from the pool (smallest free number first)
+ * when a step first writes into it and keeps its number until its request finishes (private pages)
+ * or the last resident request below its segment leaves (shared pages), so the caller's pool
+ * carries real keys and values from step to step.  Sharing is page-granular: a segment that ends at
+ * token e shares the whole pages below e / 16 (below (e - 1) / 16 where some prompt ends exactly at
+ * e), and a request admitted behind complete segments starts at the first token after their pages.
+ *
+ * The scheduler reads the builder's finalized (and possibly split) tree; the builder must outlive
+ * it and must not change meanwhile.  Requests are taken as not yet prefilled (n_cached is ignored).
+ */
+typedef struct bs_sched_cfg {
+  int64_t mem_tokens;    /* M: tokens of KV the account may hold */
+  int32_t token_budget;  /* rows of a step */
+  int32_t n_pages;       /* physical pages of the caller's pool */
+  int32_t relocate_pct;  /* see above; 0 = requests stay in the partition that admitted them; 200 is the usual value */
+  int32_t row_multiple;  /* steps of more rows than this are cut to a multiple of it (Appendix A.2 uses 128); 1 = off */
+} bs_sched_cfg;
+
+typedef struct bs_sched_stats {
+  int64_t steps, rows, prefill_rows, decode_rows, prompt_tokens_skipped, tokens_out, finished, peak_tokens, peak_pages,
+          relocated, mem_left, mem_right;  /* mem_*: tokens of the two partitions */
+} bs_sched_stats;
+
+typedef struct bs_sched bs_sched;
+
+/* d_true[n_requests]: the output length after which each request ends (>= 1; it stands in for the
+ * end-of-sequence events a serving engine sees; admission and reservation use the builder's
+ * estimates only).  order: NULL = the leaf order of the sorted tree, scanned from both ends;
+ * else a permutation of the requests that one scanner walks from the left with all the memory
+ * (the orders that the resource-aware one is compared with). */
+int bs_sched_create(const bs_builder *b, const bs_sched_cfg *cfg, const int32_t *d_true, const int32_t *order,
+                    bs_sched **out);
+void bs_sched_destroy(bs_sched *s);
+const char *bs_sched_last_error(const bs_sched *s);
+
+/* The next step's descriptor (free it with bs_batch_free; `info` is zero; n_pages is the pool size),
+ * with the scheduler's state already advanced past the step: the caller runs the steps in the order
+ * it receives them.  Returns BS_OK, BS_SCHED_DONE when every request has been served (*out = NULL),
+ * BS_ENOMEM when the page pool is exhausted, BS_EINVAL when nothing fits the memory at all. */
+#define BS_SCHED_DONE 1
+int bs_sched_next(bs_sched *s, bs_batch_owned **out);
+int bs_sched_get_stats(const bs_sched *s, bs_sched_stats *out);
+
 #ifdef __cplusplus
 }
 #endif

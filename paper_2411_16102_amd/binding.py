@@ -69,6 +69,16 @@ class BatchOwned(C.Structure):
     _fields_ = [("batch", BatchDesc), ("seq_request", _i32p), ("n_pages", C.c_int64), ("info", ScanInfo)]
 
 
+class SchedCfg(C.Structure):
+    _fields_ = [("mem_tokens", C.c_int64), ("token_budget", C.c_int32), ("n_pages", C.c_int32),
+                ("relocate_pct", C.c_int32), ("row_multiple", C.c_int32)]
+
+
+class SchedStats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("steps", "rows", "prefill_rows", "decode_rows", "prompt_tokens_skipped", "tokens_out",
+                                         "finished", "peak_tokens", "peak_pages", "relocated", "mem_left", "mem_right")]
+
+
 class BlendStepError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__("blendstep error %d: %s" % (code, msg))
@@ -146,6 +156,13 @@ def raw():
         lib.bs_builder_next_batch.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.POINTER(C.POINTER(BatchOwned))]
         lib.bs_builder_emit.argtypes = [C.c_void_p, C.c_int32, _i32p, _i32p, _i32p, C.c_int32, _i32p, _i32p,
                                         C.POINTER(C.POINTER(BatchOwned))]
+        lib.bs_sched_create.argtypes = [C.c_void_p, C.POINTER(SchedCfg), _i32p, _i32p, C.POINTER(C.c_void_p)]
+        lib.bs_sched_destroy.argtypes = [C.c_void_p]
+        lib.bs_sched_destroy.restype = None
+        lib.bs_sched_last_error.argtypes = [C.c_void_p]
+        lib.bs_sched_last_error.restype = C.c_char_p
+        lib.bs_sched_next.argtypes = [C.c_void_p, C.POINTER(C.POINTER(BatchOwned))]
+        lib.bs_sched_get_stats.argtypes = [C.c_void_p, C.POINTER(SchedStats)]
         lib.bs_batch_free.argtypes = [C.POINTER(BatchOwned)]
         lib.bs_batch_free.restype = None
         _lib = lib
@@ -486,9 +503,56 @@ class Builder:
         return self._take(out)[1]
 
 
+class Scheduler:
+    """The multi-step driver over a finalized Builder (bs_sched_*): marshalling only."""
+
+    def __init__(self, builder: Builder, d_true, mem_tokens: int, token_budget: int, n_pages: int, order=None,
+                 relocate_pct: int = 200, row_multiple: int = 1):
+        self.lib = raw()
+        self.builder = builder          # must outlive the scheduler
+        cfg = SchedCfg(int(mem_tokens), int(token_budget), int(n_pages), int(relocate_pct), int(row_multiple))
+        dt = np.ascontiguousarray(d_true, dtype=np.int32)
+        od = None if order is None else np.ascontiguousarray(order, dtype=np.int32)
+        h = C.c_void_p()
+        rc = self.lib.bs_sched_create(builder.h, C.byref(cfg), _ptr(dt), None if od is None else _ptr(od), C.byref(h))
+        if rc != 0:
+            raise BlendStepError(rc, "bs_sched_create: invalid arguments")
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.bs_sched_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def next_step(self):
+        """The next step's descriptor as a dict of numpy arrays, or None when the pool is served."""
+        out = C.POINTER(BatchOwned)()
+        rc = self.lib.bs_sched_next(self.h, C.byref(out))
+        if rc == 1:
+            return None
+        if rc != 0:
+            raise BlendStepError(rc, (self.lib.bs_sched_last_error(self.h) or b"").decode())
+        return self.builder._take(out)[1]
+
+    def stats(self) -> dict:
+        st = SchedStats()
+        rc = self.lib.bs_sched_get_stats(self.h, C.byref(st))
+        if rc != 0:
+            raise BlendStepError(rc, "bs_sched_get_stats")
+        return {n: getattr(st, n) for n, _ in SchedStats._fields_}
+
+
 class _Api:
     Layer = Layer
     Builder = Builder
+    Scheduler = Scheduler
+    binding_device_state = DeviceState
     BlendStepError = BlendStepError
     FLAG_SERIAL = FLAG_SERIAL
     FLAG_OVERLAP = FLAG_OVERLAP

@@ -291,6 +291,35 @@ struct Dec { int32_t req, ctx; };            // a decode sequence: request, toke
 // sequences in leaf order.  Prefix nodes = trie nodes with at least two of the decode sequences
 // below them and at least one whole page of their own; pages are numbered afresh, node pages
 // first (DFS order), then every sequence's private pages.
+// A descriptor in memory that bs_batch_free releases; NULL when memory runs out.
+bs_batch_owned *own_batch(int32_t n_pre, int32_t n_dec, const std::vector<int32_t> &row_start, const std::vector<int32_t> &kv_len,
+                          const std::vector<int32_t> &page_start, const std::vector<int32_t> &page_ids,
+                          const std::vector<int32_t> &o_parent, const std::vector<int32_t> &o_pstart,
+                          const std::vector<int32_t> &o_pages, const std::vector<int32_t> &o_first,
+                          const std::vector<int32_t> &o_count, const std::vector<int32_t> &seq_leaf,
+                          const std::vector<int32_t> &seq_req, int64_t n_pages) {
+  bs_batch_owned *o = new (std::nothrow) bs_batch_owned();
+  if (!o) return nullptr;
+  std::memset(o, 0, sizeof *o);
+  bool ok = true;
+  auto dup = [&ok](const std::vector<int32_t> &v) -> int32_t * {
+    int32_t *p = new (std::nothrow) int32_t[v.size() ? v.size() : 1];
+    if (!p) { ok = false; return nullptr; }
+    if (!v.empty()) std::memcpy(p, v.data(), v.size() * sizeof(int32_t));
+    return p;
+  };
+  o->batch.n_seq = n_pre + n_dec; o->batch.n_prefill = n_pre; o->batch.n_rows = row_start.back();
+  o->batch.row_start = dup(row_start); o->batch.kv_len = dup(kv_len); o->batch.page_start = dup(page_start);
+  o->batch.page_ids = dup(page_ids);
+  o->batch.n_nodes = (int32_t)o_parent.size();
+  o->batch.node_parent = dup(o_parent); o->batch.node_page_start = dup(o_pstart); o->batch.node_page_ids = dup(o_pages);
+  o->batch.node_seq_first = dup(o_first); o->batch.node_seq_count = dup(o_count); o->batch.seq_leaf_node = dup(seq_leaf);
+  o->seq_request = dup(seq_req);
+  o->n_pages = n_pages;
+  if (!ok) { bs_batch_free(o); return nullptr; }
+  return o;
+}
+
 int emit(bs_builder *b, const std::vector<Pre> &pre, std::vector<Dec> dec, bs_batch_owned **out) {
   const std::vector<Node> &nd = b->nodes;
   const int32_t ps = b->cm.page_size;
@@ -356,24 +385,38 @@ int emit(bs_builder *b, const std::vector<Pre> &pre, std::vector<Dec> dec, bs_ba
     kv_len.push_back(kv); page_start.push_back((int32_t)page_ids.size()); seq_leaf.push_back(leaf); seq_req.push_back(ri);
   }
 
-  bs_batch_owned *o = new (std::nothrow) bs_batch_owned();
+  bs_batch_owned *o = own_batch(n_pre, n_dec, row_start, kv_len, page_start, page_ids, o_parent, o_pstart, o_pages, o_first,
+                                o_count, seq_leaf, seq_req, next_page);
   if (!o) return fail(b, BS_ENOMEM, "out of memory");
-  std::memset(o, 0, sizeof *o);
-  auto dup = [](const std::vector<int32_t> &v) {
-    int32_t *p = new int32_t[v.size() ? v.size() : 1];
-    if (!v.empty()) std::memcpy(p, v.data(), v.size() * sizeof(int32_t));
-    return p;
-  };
-  o->batch.n_seq = n_pre + n_dec; o->batch.n_prefill = n_pre; o->batch.n_rows = row_start.back();
-  o->batch.row_start = dup(row_start); o->batch.kv_len = dup(kv_len); o->batch.page_start = dup(page_start);
-  o->batch.page_ids = dup(page_ids);
-  o->batch.n_nodes = (int32_t)o_parent.size();
-  o->batch.node_parent = dup(o_parent); o->batch.node_page_start = dup(o_pstart); o->batch.node_page_ids = dup(o_pages);
-  o->batch.node_seq_first = dup(o_first); o->batch.node_seq_count = dup(o_count); o->batch.seq_leaf_node = dup(seq_leaf);
-  o->seq_request = dup(seq_req);
-  o->n_pages = next_page;
   *out = o;
   return BS_OK;
+}
+
+// Algorithm 3 on the first branching node's leftmost and rightmost subtree
+void scan_budgets(const bs_builder *b, bs_scan_info *out) {
+  const bs_cost_model &cm = b->cm;
+  const std::vector<Node> &nd = b->nodes;
+  int32_t rt = 0;
+  while (nd[rt].req < 0 && nd[rt].kids.size() == 1) rt = nd[rt].kids[0];
+  int32_t L = rt, R = rt;
+  if (nd[rt].req < 0 && nd[rt].kids.size() >= 2) { L = nd[rt].kids.front(); R = nd[rt].kids.back(); }
+  bs_scan_info info;
+  std::memset(&info, 0, sizeof info);
+  info.rho_rt = rho_of(cm, nd[rt].A, nd[rt].B);
+  info.rho_l = rho_of(cm, nd[L].A, nd[L].B);
+  info.rho_r = rho_of(cm, nd[R].A, nd[R].B);
+  partition(info.rho_rt, info.rho_l, info.rho_r, (double)cm.mem_bytes, &info.m_l, &info.m_r);
+  auto side = [&](const Node &s, double m, int64_t *n_out, int64_t *c_out) {
+    const double p_bar = (double)s.sum_p / (double)s.n_req;
+    const double d_bar = (double)s.sum_d / (double)s.n_req;
+    int64_t n = (int64_t)std::floor(m / ((p_bar + d_bar / 2.0) * (double)cm.kv_bytes));
+    if (n < 1) n = 1;
+    *n_out = n;
+    *c_out = (d_bar == 0.0) ? -1 : (int64_t)std::floor((double)n * p_bar / d_bar);
+  };
+  side(nd[L], info.m_l, &info.n_l, &info.c_l);
+  side(nd[R], info.m_r, &info.n_r, &info.c_r);
+  *out = info;
 }
 
 }  // namespace
@@ -611,30 +654,8 @@ int bs_builder_next_batch(bs_builder *b, int64_t prefill_budget, int64_t decode_
   *out = nullptr;
   if (!b->finalized) return fail(b, BS_EINVAL, "finalize the builder first");
   if (b->reqs.empty()) return fail(b, BS_EINVAL, "no requests");
-  const bs_cost_model &cm = b->cm;
-  const std::vector<Node> &nd = b->nodes;
-
-  // Algorithm 3 on the first branching node's leftmost and rightmost subtree
-  int32_t rt = 0;
-  while (nd[rt].req < 0 && nd[rt].kids.size() == 1) rt = nd[rt].kids[0];
-  int32_t L = rt, R = rt;
-  if (nd[rt].req < 0 && nd[rt].kids.size() >= 2) { L = nd[rt].kids.front(); R = nd[rt].kids.back(); }
   bs_scan_info info;
-  std::memset(&info, 0, sizeof info);
-  info.rho_rt = rho_of(cm, nd[rt].A, nd[rt].B);
-  info.rho_l = rho_of(cm, nd[L].A, nd[L].B);
-  info.rho_r = rho_of(cm, nd[R].A, nd[R].B);
-  partition(info.rho_rt, info.rho_l, info.rho_r, (double)cm.mem_bytes, &info.m_l, &info.m_r);
-  auto side = [&](const Node &s, double m, int64_t *n_out, int64_t *c_out) {
-    const double p_bar = (double)s.sum_p / (double)s.n_req;
-    const double d_bar = (double)s.sum_d / (double)s.n_req;
-    int64_t n = (int64_t)std::floor(m / ((p_bar + d_bar / 2.0) * (double)cm.kv_bytes));
-    if (n < 1) n = 1;
-    *n_out = n;
-    *c_out = (d_bar == 0.0) ? -1 : (int64_t)std::floor((double)n * p_bar / d_bar);
-  };
-  side(nd[L], info.m_l, &info.n_l, &info.c_l);
-  side(nd[R], info.m_r, &info.n_r, &info.c_r);
+  scan_budgets(b, &info);
 
   const int64_t INF = (int64_t)1 << 60;
   int64_t n_l = info.n_l, n_r = info.n_r;
@@ -685,6 +706,441 @@ int bs_builder_next_batch(bs_builder *b, int64_t prefill_budget, int64_t decode_
   int rc = emit(b, pre, dec_list, out);
   if (rc) return rc;
   (*out)->info = info;
+  return BS_OK;
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------------------
+// Multi-step driver (Section 3.2 and Appendix A.2, batch scheduler: the runtime batch is re-formed
+// every iteration; Section 5.3, dual scanner with the memory partition of Algorithm 3; Section 5.4,
+// adaptation to misjudged output lengths; Appendix A.2, runtime prefix tree): request state, the
+// memory account of the two partitions, the two scanners, and KV pages that keep their physical
+// number from the step that first writes them to the step that frees them.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+struct Live {
+  bool alive = false;
+  int32_t side = 0, cached = 0, generated = 0;
+  int64_t reserved = 0;
+  std::vector<int32_t> pages;  // private pages, logical page shared_hi + k
+};
+
+}  // namespace
+
+struct bs_sched {
+  const bs_builder *b = nullptr;
+  bs_sched_cfg cfg;
+  std::string err;
+  std::vector<int32_t> d_true, order, pos_in_leaf_order;
+  bool two_sided = true;
+  int64_t cap[2] = {0, 0}, used[2] = {0, 0}, pre_num = 1, pre_den = 1, p_side[2] = {0, 0};
+  int32_t lo = 0, hi = -1, n_live = 0;
+  std::vector<Live> live;                  // by request
+  std::vector<int32_t> admitted;           // admission order
+  std::vector<std::vector<int32_t>> path;  // by request: internal ancestors with a segment, top down
+  std::vector<int32_t> shared_hi;          // by request
+  // per tree node
+  std::vector<int32_t> page_lo, page_hi, ref, done, owner, nside;
+  std::vector<std::vector<int32_t>> node_pages;
+  std::vector<int32_t> free_pages;         // min-heap
+  bs_sched_stats st;
+};
+
+namespace {
+
+int sfail(bs_sched *s, int code, const char *fmt, ...) {
+  char buf[400];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (s) s->err = buf;
+  return code;
+}
+
+struct PoolExhausted {};
+
+int32_t take_page(bs_sched *s) {
+  if (s->free_pages.empty()) throw PoolExhausted();
+  std::pop_heap(s->free_pages.begin(), s->free_pages.end(), std::greater<int32_t>());
+  const int32_t p = s->free_pages.back();
+  s->free_pages.pop_back();
+  return p;
+}
+
+void give_page(bs_sched *s, int32_t p) {
+  s->free_pages.push_back(p);
+  std::push_heap(s->free_pages.begin(), s->free_pages.end(), std::greater<int32_t>());
+}
+
+int32_t prompt_len(const bs_sched *s, int32_t r) { return (int32_t)s->b->reqs[r].tok.size(); }
+
+// admission of request r from `side`; false = refused (it waits, or its side's memory is full)
+bool try_admit(bs_sched *s, int32_t r, int side, bool borrow) {
+  const std::vector<Node> &nd = s->b->nodes;
+  const int32_t p = prompt_len(s, r);
+  const std::vector<int32_t> &path = s->path[r];
+  int32_t cached_pages = 0;
+  bool chain = true;
+  std::vector<int32_t> mine;
+  for (int32_t n : path) {
+    const int32_t seg = nd[n].end - nd[n].start;
+    if (s->ref[n] > 0 && s->done[n] == seg) {
+      if (chain) cached_pages = s->page_hi[n];
+    } else if (s->ref[n] > 0 && s->owner[n] >= 0) {
+      return false;  // somebody is still computing this segment
+    } else {
+      mine.push_back(n);
+      chain = false;
+    }
+  }
+  const int64_t own = (int64_t)(p - nd[s->b->leaf_node[r]].start) + s->b->reqs[r].d_est;
+  int64_t need = own;
+  for (int32_t n : path)
+    if (s->ref[n] == 0) need += nd[n].end - nd[n].start;
+  const bool over = borrow ? (s->used[0] + s->used[1] + need > s->cfg.mem_tokens) : (s->used[side] + need > s->cap[side]);
+  if (over && s->n_live > 0) return false;
+  Live &lv = s->live[r];
+  lv = Live();
+  lv.alive = true;
+  lv.side = side;
+  lv.cached = std::min(16 * cached_pages, p - 1);
+  lv.reserved = own;
+  s->used[side] += own;
+  for (int32_t n : path) {
+    if (s->ref[n] == 0) {
+      s->used[side] += nd[n].end - nd[n].start;
+      s->nside[n] = side; s->done[n] = 0; s->owner[n] = -1;
+      s->node_pages[n].clear();
+    }
+    ++s->ref[n];
+  }
+  for (int32_t n : mine) s->owner[n] = r;
+  s->st.prompt_tokens_skipped += lv.cached;
+  ++s->n_live;
+  s->admitted.push_back(r);
+  return true;
+}
+
+void release(bs_sched *s, int32_t r) {
+  const std::vector<Node> &nd = s->b->nodes;
+  Live &lv = s->live[r];
+  s->used[lv.side] -= lv.reserved;
+  for (int32_t pg : lv.pages) give_page(s, pg);
+  for (int32_t n : s->path[r]) {
+    if (--s->ref[n] == 0) {
+      s->used[s->nside[n]] -= nd[n].end - nd[n].start;
+      s->done[n] = 0; s->owner[n] = -1;
+      for (int32_t pg : s->node_pages[n]) give_page(s, pg);
+      s->node_pages[n].clear();
+    }
+  }
+  lv = Live();
+  --s->n_live;
+}
+
+// physical page of logical page j of live request r; allocates up to it if asked
+int32_t page_of(bs_sched *s, int32_t r, int32_t j, bool may_allocate) {
+  const int32_t sh = s->shared_hi[r];
+  std::vector<int32_t> *pages;
+  int32_t k;
+  if (j < sh) {
+    pages = nullptr;
+    k = 0;
+    for (int32_t n : s->path[r])
+      if (s->page_lo[n] <= j && j < s->page_hi[n]) { pages = &s->node_pages[n]; k = j - s->page_lo[n]; break; }
+  } else {
+    pages = &s->live[r].pages;
+    k = j - sh;
+  }
+  while (may_allocate && (int32_t)pages->size() <= k) pages->push_back(take_page(s));
+  return (*pages)[k];
+}
+
+void plan(bs_sched *s, std::vector<Pre> &pre, std::vector<Dec> &dec) {
+  int64_t budget = s->cfg.token_budget;
+  const int32_t n_req = (int32_t)s->live.size();
+  for (int32_t k = 0; k < n_req; ++k) {  // leaf order: what the descriptor needs
+    const int32_t r = s->b->leaf_order[k];
+    const Live &lv = s->live[r];
+    if (lv.alive && lv.cached >= prompt_len(s, r)) dec.push_back({r, prompt_len(s, r) + lv.generated - 1});
+  }
+  budget -= (int64_t)dec.size();
+  {
+    std::vector<int32_t> keep;
+    for (int32_t r : s->admitted)
+      if (s->live[r].alive && s->live[r].cached < prompt_len(s, r)) keep.push_back(r);
+    s->admitted.swap(keep);
+  }
+  const int64_t b0 = std::max<int64_t>(0, budget);
+  int64_t share[2];
+  share[0] = b0 * s->pre_num / s->pre_den;
+  if (s->two_sided) {  // neither scanner is starved: room for one average request of its side
+    share[0] = std::max(share[0], std::min(s->p_side[0], b0 / 2));
+    share[0] = std::min(share[0], b0 - std::min(s->p_side[1], b0 / 2));
+  }
+  share[1] = b0 - share[0];
+  std::vector<int32_t> waiting;
+  for (int32_t r : s->admitted) {
+    Live &lv = s->live[r];
+    const int64_t chunk = std::min<int64_t>(prompt_len(s, r) - lv.cached, share[lv.side]);
+    if (chunk <= 0) { waiting.push_back(r); continue; }
+    pre.push_back({r, lv.cached, (int32_t)chunk});
+    budget -= chunk;
+    share[lv.side] -= chunk;
+  }
+  for (int pass = 0; pass < 2; ++pass) {
+    const bool borrow = pass == 1;
+    bool is_open[2] = {true, s->two_sided};
+    if (borrow) {
+      for (int32_t r : waiting) {
+        if (budget <= 0) break;
+        Live &lv = s->live[r];
+        const int64_t chunk = std::min<int64_t>(prompt_len(s, r) - lv.cached, budget);
+        pre.push_back({r, lv.cached, (int32_t)chunk});
+        budget -= chunk;
+      }
+      share[0] = share[1] = budget;
+    }
+    while (budget > 0 && s->lo <= s->hi && (is_open[0] || is_open[1])) {
+      bool progressed = false;
+      for (int side = 0; side < 2; ++side) {
+        if (!is_open[side] || s->lo > s->hi || budget <= 0) continue;
+        if (share[side] <= 0) { is_open[side] = false; continue; }
+        const int32_t r = side == 0 ? s->order[s->lo] : s->order[s->hi];
+        if (!try_admit(s, r, side, borrow)) { is_open[side] = false; continue; }
+        if (side == 0) ++s->lo; else --s->hi;
+        const Live &lv = s->live[r];
+        const int64_t chunk = std::min<int64_t>(std::min<int64_t>(prompt_len(s, r) - lv.cached, budget), share[side]);
+        pre.push_back({r, lv.cached, (int32_t)chunk});
+        budget -= chunk;
+        share[side] -= chunk;
+        progressed = true;
+      }
+      if (!progressed) break;
+    }
+  }
+  int64_t total = (int64_t)dec.size();
+  for (const Pre &x : pre) total += x.chunk;
+  int64_t extra = total > s->cfg.row_multiple ? total % s->cfg.row_multiple : 0;
+  while (extra > 0 && !pre.empty()) {
+    const int64_t cut = std::min<int64_t>(extra, pre.back().chunk);
+    if (cut == pre.back().chunk) pre.pop_back(); else pre.back().chunk -= (int32_t)cut;
+    extra -= cut;
+  }
+}
+
+bs_batch_owned *emit_step(bs_sched *s, const std::vector<Pre> &pre, const std::vector<Dec> &dec) {
+  const std::vector<Node> &nd = s->b->nodes;
+  const int32_t n_pre = (int32_t)pre.size(), n_dec = (int32_t)dec.size();
+  // pages that this step writes into come into being, in the order of the descriptor
+  for (const Pre &x : pre)
+    for (int32_t j = x.cached / 16; j <= (x.cached + x.chunk - 1) / 16; ++j) page_of(s, x.req, j, true);
+  for (const Dec &x : dec) page_of(s, x.req, x.ctx / 16, true);
+  std::vector<int32_t> row_start{0}, kv_len, page_start{0}, page_ids, seq_leaf, seq_req;
+  for (const Pre &x : pre) {
+    const int32_t kv = x.cached + x.chunk;
+    for (int32_t j = 0; j < (kv + 15) / 16; ++j) page_ids.push_back(page_of(s, x.req, j, false));
+    row_start.push_back(row_start.back() + x.chunk);
+    kv_len.push_back(kv); page_start.push_back((int32_t)page_ids.size()); seq_leaf.push_back(-1); seq_req.push_back(x.req);
+  }
+  // prefix nodes: segments with at least two decode members in this step and at least one page, in DFS order
+  const int32_t n_nodes = (int32_t)nd.size();
+  std::vector<int32_t> count(n_nodes, 0), first(n_nodes, -1), id(n_nodes, -1);
+  for (int32_t k = 0; k < n_dec; ++k)
+    for (int32_t n : s->path[dec[k].req]) {
+      if (count[n]++ == 0) first[n] = k;
+    }
+  std::vector<int32_t> o_parent, o_first, o_count, o_pstart{0}, o_pages;
+  for (int32_t n = 0; n < n_nodes; ++n) {  // the nodes are stored in DFS pre-order
+    if (nd[n].req >= 0 || count[n] < 2 || s->page_hi[n] <= s->page_lo[n]) continue;
+    int32_t anc = nd[n].parent;
+    while (anc >= 0 && id[anc] < 0) anc = nd[anc].parent;
+    id[n] = (int32_t)o_parent.size();
+    o_parent.push_back(anc >= 0 ? id[anc] : -1);
+    o_first.push_back(n_pre + first[n]);
+    o_count.push_back(count[n]);
+    o_pages.insert(o_pages.end(), s->node_pages[n].begin(), s->node_pages[n].end());
+    o_pstart.push_back((int32_t)o_pages.size());
+  }
+  for (const Dec &x : dec) {
+    const int32_t kv = x.ctx + 1;
+    for (int32_t j = 0; j < (kv + 15) / 16; ++j) page_ids.push_back(page_of(s, x.req, j, false));
+    row_start.push_back(row_start.back() + 1);
+    int32_t deepest = -1;
+    for (int32_t n : s->path[x.req])
+      if (id[n] >= 0) deepest = id[n];
+    kv_len.push_back(kv); page_start.push_back((int32_t)page_ids.size()); seq_leaf.push_back(deepest); seq_req.push_back(x.req);
+  }
+  return own_batch(n_pre, n_dec, row_start, kv_len, page_start, page_ids, o_parent, o_pstart, o_pages, o_first, o_count,
+                   seq_leaf, seq_req, s->cfg.n_pages);
+}
+
+void commit(bs_sched *s, const std::vector<Pre> &pre, const std::vector<Dec> &dec) {
+  const std::vector<Node> &nd = s->b->nodes;
+  bs_sched_stats &st = s->st;
+  int64_t pre_rows = 0;
+  for (const Pre &x : pre) pre_rows += x.chunk;
+  ++st.steps;
+  st.prefill_rows += pre_rows;
+  st.decode_rows += (int64_t)dec.size();
+  st.rows += pre_rows + (int64_t)dec.size();
+  st.peak_tokens = std::max(st.peak_tokens, s->used[0] + s->used[1]);
+  st.peak_pages = std::max<int64_t>(st.peak_pages, s->cfg.n_pages - (int64_t)s->free_pages.size());
+  for (const Pre &x : pre) {
+    Live &lv = s->live[x.req];
+    const int32_t lo = x.cached, hi = x.cached + x.chunk;
+    for (int32_t n : s->path[x.req]) {
+      const int32_t a = nd[n].start, e = nd[n].end;
+      if (hi <= a || lo >= e || s->owner[n] != x.req) continue;
+      s->done[n] = std::max(s->done[n], std::min(hi, e) - a);
+      if (s->done[n] == e - a) s->owner[n] = -1;
+    }
+    lv.cached = hi;
+    if (lv.cached == prompt_len(s, x.req)) {
+      lv.generated = 1;
+      ++st.tokens_out;
+      if (lv.generated >= s->d_true[x.req]) { ++st.finished; release(s, x.req); }
+    }
+  }
+  for (const Dec &x : dec) {
+    Live &lv = s->live[x.req];
+    ++lv.generated;
+    ++st.tokens_out;
+    const int64_t d_est = s->b->reqs[x.req].d_est;
+    if (lv.generated > d_est) {
+      ++lv.reserved;
+      ++s->used[lv.side];
+      if (s->two_sided && lv.side == 0 && s->cfg.relocate_pct > 0 && (int64_t)lv.generated * 100 >= (int64_t)s->cfg.relocate_pct * d_est) {
+        s->used[0] -= lv.reserved;
+        s->used[1] += lv.reserved;
+        lv.side = 1;
+        ++st.relocated;
+      }
+    }
+    if (lv.generated >= s->d_true[x.req]) { ++st.finished; release(s, x.req); }
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int bs_sched_create(const bs_builder *b, const bs_sched_cfg *cfg, const int32_t *d_true, const int32_t *order, bs_sched **out) {
+  if (!out) return BS_EINVAL;
+  *out = nullptr;
+  if (!b || !cfg || !d_true) return BS_EINVAL;
+  if (!b->finalized || b->reqs.empty()) return BS_EINVAL;
+  if (b->cm.page_size != 16 || cfg->mem_tokens < 1 || cfg->token_budget < 1 || cfg->n_pages < 1 || cfg->relocate_pct < 0 ||
+      cfg->row_multiple < 1)
+    return BS_EINVAL;
+  try {
+    bs_sched *s = new bs_sched();
+    s->b = b;
+    s->cfg = *cfg;
+    std::memset(&s->st, 0, sizeof s->st);
+    const std::vector<Node> &nd = b->nodes;
+    const int32_t n_req = (int32_t)b->reqs.size(), n_nodes = (int32_t)nd.size();
+    for (int32_t r = 0; r < n_req; ++r) {
+      if (d_true[r] < 1) { delete s; return BS_EINVAL; }
+      if (b->reqs[r].tok.empty()) { delete s; return BS_EINVAL; }
+    }
+    s->d_true.assign(d_true, d_true + n_req);
+    s->pos_in_leaf_order.assign(n_req, 0);
+    for (int32_t k = 0; k < n_req; ++k) s->pos_in_leaf_order[b->leaf_order[k]] = k;
+    s->two_sided = order == nullptr;
+    if (order) {
+      std::vector<char> seen(n_req, 0);
+      for (int32_t k = 0; k < n_req; ++k) {
+        if (order[k] < 0 || order[k] >= n_req || seen[order[k]]) { delete s; return BS_EINVAL; }
+        seen[order[k]] = 1;
+      }
+      s->order.assign(order, order + n_req);
+      s->cap[0] = cfg->mem_tokens; s->cap[1] = 0;
+      s->pre_num = s->pre_den = 1;
+    } else {
+      s->order = b->leaf_order;
+      bs_scan_info info;
+      scan_budgets(b, &info);
+      const double m = info.m_l + info.m_r;
+      const double frac_l = m > 0 ? info.m_l / m : 0.5;
+      s->cap[0] = (int64_t)std::floor((double)cfg->mem_tokens * frac_l);
+      s->cap[1] = cfg->mem_tokens - s->cap[0];
+      if (info.c_l < 0 || info.c_r < 0 || info.c_l + info.c_r == 0) { s->pre_num = 1; s->pre_den = 2; }
+      else { s->pre_num = info.c_l; s->pre_den = info.c_l + info.c_r; }
+      int32_t rt = 0;
+      while (nd[rt].req < 0 && nd[rt].kids.size() == 1) rt = nd[rt].kids[0];
+      int32_t L = rt, R = rt;
+      if (nd[rt].req < 0 && nd[rt].kids.size() >= 2) { L = nd[rt].kids.front(); R = nd[rt].kids.back(); }
+      s->p_side[0] = (nd[L].sum_p + nd[L].n_req - 1) / nd[L].n_req;
+      s->p_side[1] = (nd[R].sum_p + nd[R].n_req - 1) / nd[R].n_req;
+    }
+    s->lo = 0; s->hi = n_req - 1;
+    // shareable pages of every internal node (parents come before children in the node array)
+    s->page_lo.assign(n_nodes, 0); s->page_hi.assign(n_nodes, 0);
+    for (int32_t n = 0; n < n_nodes; ++n) {
+      if (nd[n].req >= 0) continue;
+      const int32_t above = nd[n].parent >= 0 ? s->page_hi[nd[n].parent] : 0;
+      bool ends_here = false;
+      for (int32_t c : nd[n].kids)
+        if (nd[c].req >= 0 && nd[c].end == nd[n].end) ends_here = true;
+      const int32_t hi = (ends_here && nd[n].end > 0) ? (nd[n].end - 1) / 16 : nd[n].end / 16;
+      s->page_lo[n] = above;
+      s->page_hi[n] = std::max(above, hi);
+    }
+    s->ref.assign(n_nodes, 0); s->done.assign(n_nodes, 0); s->owner.assign(n_nodes, -1); s->nside.assign(n_nodes, 0);
+    s->node_pages.assign(n_nodes, {});
+    s->live.assign(n_req, Live());
+    s->path.assign(n_req, {});
+    s->shared_hi.assign(n_req, 0);
+    for (int32_t r = 0; r < n_req; ++r) {
+      std::vector<int32_t> &p = s->path[r];
+      for (int32_t n = nd[b->leaf_node[r]].parent; n >= 0; n = nd[n].parent)
+        if (nd[n].end > nd[n].start) p.push_back(n);
+      std::reverse(p.begin(), p.end());
+      s->shared_hi[r] = p.empty() ? 0 : s->page_hi[p.back()];
+    }
+    s->free_pages.resize(cfg->n_pages);
+    for (int32_t i = 0; i < cfg->n_pages; ++i) s->free_pages[i] = i;  // ascending: already a min-heap
+    *out = s;
+    return BS_OK;
+  } catch (const std::bad_alloc &) {
+    return BS_ENOMEM;
+  }
+}
+
+void bs_sched_destroy(bs_sched *s) { delete s; }
+
+const char *bs_sched_last_error(const bs_sched *s) { return s ? s->err.c_str() : "scheduler is NULL"; }
+
+int bs_sched_next(bs_sched *s, bs_batch_owned **out) {
+  if (!s || !out) return BS_EINVAL;
+  *out = nullptr;
+  try {
+    if (s->n_live == 0 && s->lo > s->hi) return BS_SCHED_DONE;
+    std::vector<Pre> pre;
+    std::vector<Dec> dec;
+    plan(s, pre, dec);
+    if (pre.empty() && dec.empty()) return sfail(s, BS_EINVAL, "the driver is stuck: nothing fits the memory of either side");
+    bs_batch_owned *o = emit_step(s, pre, dec);
+    if (!o) return sfail(s, BS_ENOMEM, "out of memory");
+    commit(s, pre, dec);
+    *out = o;
+    return BS_OK;
+  } catch (const PoolExhausted &) {
+    return sfail(s, BS_ENOMEM, "the page pool of %d pages is exhausted", s->cfg.n_pages);
+  } catch (const std::bad_alloc &) {
+    return sfail(s, BS_ENOMEM, "out of memory");
+  }
+}
+
+int bs_sched_get_stats(const bs_sched *s, bs_sched_stats *out) {
+  if (!s || !out) return BS_EINVAL;
+  *out = s->st;
+  out->mem_left = s->cap[0];
+  out->mem_right = s->cap[1];
   return BS_OK;
 }
 

@@ -463,6 +463,57 @@ def work_of(shape: LayerShape, b: Batch) -> Dict[str, float]:
                 bytes_once=bytes_once, bytes_expanded=bytes_exp, table_pages=float(np.sum(n_tab)))
 
 
+# ----------------------------------------------------------------------------
+# a request pool for the multi-step driver
+# ----------------------------------------------------------------------------
+@dataclass
+class PoolRequest:
+    tokens: Sequence[int]
+    d_est: int      # the estimate that ordering, admission and reservation see
+    d_true: int     # the length after which the request ends
+
+
+def synthetic_pool(seed: int, n_groups: int = 24, per_group: int = 12, n_fresh: int = 96, est_noise: float = 0.25,
+                   templates: str = "by_kind") -> List[PoolRequest]:
+    """A pool with the structure of the paper's mixed workloads (Section 6.1): groups sharing a
+    long system prompt whose members generate short outputs (compute-intensive, benchmark-like),
+    groups with medium and with long outputs (memory-intensive), and unrelated prompt-heavy
+    requests.  Each kind comes from its own dataset, whose prompts start with the same template
+    token, so a prefix-DFS order serves one dataset after the other, as it would a concatenation
+    of traces.  templates="by_kind" numbers the template tokens so that the DFS order meets the
+    compute-intensive datasets first and the long-output one last (the case Section 3.1 describes
+    as hurting it); templates="shuffled" numbers them at random (a neutral order for that
+    baseline).  Output-length estimates are the true lengths with multiplicative noise."""
+    assert templates in ("by_kind", "shuffled")
+    rng = np.random.default_rng(seed)
+    tpl = [0, 1, 2, 3] if templates == "by_kind" else [int(t) for t in np.random.default_rng([seed, 7]).permutation(4)]
+    out: List[PoolRequest] = []
+    for g in range(n_groups):
+        kind = g % 3
+        prefix = [tpl[kind + 1]] + [int(t) for t in rng.integers(4, 128000, int(rng.integers(256, 1536)))]
+        for _ in range(per_group):
+            own = [int(t) for t in rng.integers(4, 128000, int(rng.integers(16, 256)))]
+            d = int(rng.integers(8, 48)) if kind == 0 else int(rng.integers(128, 512)) if kind == 1 else int(rng.integers(768, 2048))
+            out.append(PoolRequest(prefix + own, 0, d))
+    for _ in range(n_fresh):
+        toks = [tpl[0]] + [int(t) for t in rng.integers(4, 128000, int(rng.integers(512, 3072)))]
+        out.append(PoolRequest(toks, 0, int(rng.integers(4, 64))))
+    for r in out:
+        r.d_est = max(1, int(round(r.d_true * float(np.exp(est_noise * rng.standard_normal())))))
+    perm = rng.permutation(len(out))
+    return [out[i] for i in perm]
+
+
+def baseline_order(reqs: Sequence[PoolRequest], policy: str, seed: int = 0) -> List[int]:
+    """Request orders that the resource-aware order is compared with (Section 6.3): "dfs" = prompts in
+    lexicographic order, i.e. the DFS order of the plain prefix tree (best sharing); "random"."""
+    if policy == "dfs":
+        return sorted(range(len(reqs)), key=lambda i: (list(reqs[i].tokens), i))
+    if policy == "random":
+        return [int(i) for i in np.random.default_rng(seed).permutation(len(reqs))]
+    raise ValueError("unknown baseline order " + policy)
+
+
 CONFIGS = {
     "tiny": (TINY, batch_tiny),
     "decode_8b": (LLAMA3_8B, batch_decode_only),
