@@ -39,7 +39,7 @@ using namespace attn_dev;
 // -9 % with 1280 wide and 2048 narrow workgroups, +2 % with 390 and 1812, hence the rule).
 // The period is odd on purpose: workgroups go to the eight XCDs in turn, and a period of
 // four would send every wide workgroup to the same two of them.
-template <int DH>
+template <int DH, bool NT_NARROW>
 __device__ __forceinline__ void decode_workgroup(const DecodeArgs &a, int n_wide_units, int n_narrow_units, int b, int wave,
                                                  int lane, uint16_t *q_sh) {
   constexpr int WQB = 4;  // blocks of 16 query rows of a wide item
@@ -64,7 +64,7 @@ __device__ __forceinline__ void decode_workgroup(const DecodeArgs &a, int n_wide
   if (wide) {
     if (unit < n_wide_units) decode_unit<DH, WQB>(a, unit / hkv, unit % hkv, wave, lane, q_sh);
   } else {
-    if (unit < n_narrow_units) decode_unit<DH, 1>(a, n_wide_units / hkv + unit / hkv, unit % hkv, wave, lane, q_sh);
+    if (unit < n_narrow_units) decode_unit<DH, 1, NT_NARROW>(a, n_wide_units / hkv + unit / hkv, unit % hkv, wave, lane, q_sh);
   }
 }
 
@@ -74,7 +74,8 @@ template <int DH>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_attn_kernel(const DecodeArgs a, int n_wide_units, int n_narrow_units) {
   __shared__ __align__(16) uint16_t q_sh[DECODE_Q_LDS(DH)];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  decode_workgroup<DH>(a, n_wide_units, n_narrow_units, blockIdx.x, wave, threadIdx.x & 63, q_sh);
+  // a launch of decode units alone: non-temporal loads for the 16-row units (see ld16_kv)
+  decode_workgroup<DH, true>(a, n_wide_units, n_narrow_units, blockIdx.x, wave, threadIdx.x & 63, q_sh);
 }
 
 // ------------------------------------------------------------------------------
@@ -432,7 +433,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   if (prefill)
     prefill_workgroup<DH>(pf, 4, idx, wave, lane);
   else
-    decode_workgroup<DH>(d, n_wide_units, n_narrow_units, idx, wave, lane, q_sh);
+    decode_workgroup<DH, false>(d, n_wide_units, n_narrow_units, idx, wave, lane, q_sh);
 }
 
 // What the GEMM launches of a step have left of its queue of 16-row units, on the whole chip:

@@ -12,6 +12,24 @@ namespace attn_dev {
 constexpr float NEG_BIG = -1.0e30f;
 __device__ __forceinline__ u32x4_t ld16(const uint16_t *p) { return *reinterpret_cast<const u32x4_t *>(p); }
 __device__ __forceinline__ u32x2_t ld8(const uint16_t *p) { return *reinterpret_cast<const u32x2_t *>(p); }
+// KV pages of a 16-row unit are read once per step and by nobody else: their loads can be marked
+// non-temporal, so that the caches keep what is read again (GEMM operands of the tiles that run
+// beside an attention workgroup, page tables, queries) rather than pages nobody returns to.
+// Measured on MI355X: GEMM tiles beside attention workgroups 145 -> 107 us (output projection) and
+// 96 -> 83 us (gate/up), a launch of 16-row units alone 5.3 -> 6.0 TB/s; but the launch that mixes
+// prefill workgroups, 64-row units and 16-row units loses 3 to 7 % with it (8B and 70B blended
+// shapes), so the caller chooses: NT for launches of 16-row units alone and for units that ride
+// in a GEMM launch, ordinary loads otherwise.
+template <bool NT>
+__device__ __forceinline__ u32x4_t ld16_kv(const uint16_t *p) {
+  if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+  else return ld16(p);
+}
+template <bool NT>
+__device__ __forceinline__ u32x2_t ld8_kv(const uint16_t *p) {
+  if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x2_t *>(p));
+  else return ld8(p);
+}
 
 // zero the bf16 halves of `v` (tokens t0 .. t0+3) that lie at or beyond `limit`
 __device__ __forceinline__ u32x2_t mask_tokens(u32x2_t v, int t0, int limit) {
@@ -31,7 +49,7 @@ __device__ __forceinline__ u32x2_t mask_tokens(u32x2_t v, int t0, int limit) {
 // the accumulators are rescaled a few times per chunk instead of once per page.
 constexpr float TAU = 8.0f;
 
-template <int DH, int NQB>
+template <int DH, int NQB, bool NT = false>
 __device__ __forceinline__ void decode_unit(const DecodeArgs &a, int item, int kvh, int wave, int lane, uint16_t *q_sh) {
   constexpr int KC = DH / 32;  // 32-wide chunks of the head dimension (QK^T contraction)
   constexpr int DB = DH / 16;  // 16-row blocks of the head dimension (PV output rows)
@@ -115,13 +133,13 @@ __device__ __forceinline__ void decode_unit(const DecodeArgs &a, int item, int k
     const uint16_t *v1 = a.kv_pool + ((p1 * 2 + 1) * hkv + kvh) * tile + jq * 16 + 4 * g4;
 #pragma unroll
     for (int c = 0; c < KC; ++c) {
-      f.k[0][c] = ld16(k0 + 32 * c);
-      f.k[1][c] = ld16(k1 + 32 * c);
+      f.k[0][c] = ld16_kv<NT>(k0 + 32 * c);
+      f.k[1][c] = ld16_kv<NT>(k1 + 32 * c);
     }
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
-      f.v0[db] = ld8(v0 + db * 256);
-      f.v1[db] = ld8(v1 + db * 256);
+      f.v0[db] = ld8_kv<NT>(v0 + db * 256);
+      f.v1[db] = ld8_kv<NT>(v1 + db * 256);
     }
   };
   auto load = [&](int pr, Frags &f) {
@@ -259,7 +277,7 @@ __device__ __forceinline__ void decode_queue_worker(const DecodeQueue &q, int wa
     tk = (unsigned)__builtin_amdgcn_readfirstlane((int)tk);
     if (tk >= (unsigned)q.n_units) break;
     const int item = q.first_item + (int)tk / hkv;
-    decode_unit<DH, 1>(q.d, item, (int)tk % hkv, wave, lane, nullptr);
+    decode_unit<DH, 1, true>(q.d, item, (int)tk % hkv, wave, lane, nullptr);
     if (rec) {
       ++units;
       tokens += (unsigned)q.d.items[item].n_tokens;

@@ -393,6 +393,20 @@ int emit(bs_builder *b, const std::vector<Pre> &pre, std::vector<Dec> dec, bs_ba
 }
 
 // Algorithm 3 on the first branching node's leftmost and rightmost subtree
+// No exception crosses the C boundary (vectors and maps grow with the pool).
+template <class F>
+int guarded(bs_builder *b, F &&body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc &) {
+    return fail(b, BS_ENOMEM, "out of memory");
+  } catch (const std::exception &e) {
+    return fail(b, BS_EINVAL, "unexpected exception: %s", e.what());
+  } catch (...) {
+    return fail(b, BS_EINVAL, "unexpected exception");
+  }
+}
+
 void scan_budgets(const bs_builder *b, bs_scan_info *out) {
   const bs_cost_model &cm = b->cm;
   const std::vector<Node> &nd = b->nodes;
@@ -441,6 +455,7 @@ void bs_builder_destroy(bs_builder *b) { delete b; }
 const char *bs_builder_last_error(const bs_builder *b) { return b ? b->err.c_str() : "builder is NULL"; }
 
 int bs_builder_add(bs_builder *b, const int32_t *tokens, int32_t n_tokens, int32_t d_est, int32_t n_cached) {
+  return guarded(b, [&]() -> int {
   if (!b) return BS_EINVAL;
   if (b->finalized) return fail(b, BS_EINVAL, "requests cannot be added after finalize");
   if (n_tokens < 1 || !tokens) return fail(b, BS_EINVAL, "a request needs at least one prompt token");
@@ -451,6 +466,7 @@ int bs_builder_add(bs_builder *b, const int32_t *tokens, int32_t n_tokens, int32
   r.n_cached = n_cached;
   b->reqs.push_back(std::move(r));
   return (int)b->reqs.size() - 1;
+  });
 }
 
 int bs_builder_set_mem_model(bs_builder *b, int mem_model) {
@@ -489,14 +505,17 @@ int64_t bs_kv_bytes_per_token(int variant, int32_t n_layers, int32_t n_heads, in
 }
 
 int bs_builder_finalize(bs_builder *b) {
+  return guarded(b, [&]() -> int {
   if (!b) return BS_EINVAL;
   if (b->finalized) return BS_OK;
   rebuild(b);
   b->finalized = true;
   return BS_OK;
+  });
 }
 
 int bs_builder_split(bs_builder *b, int64_t t, int64_t budget_tokens, bs_split_info *info) {
+  return guarded(b, [&]() -> int {
   if (!b) return BS_EINVAL;
   if (!b->finalized) return fail(b, BS_EINVAL, "bs_builder_split before bs_builder_finalize");
   if (t < 0) return fail(b, BS_EINVAL, "threshold t must be >= 0");
@@ -580,6 +599,7 @@ int bs_builder_split(bs_builder *b, int64_t t, int64_t budget_tokens, bs_split_i
     info->n_split = n_split; info->rounds = rounds; info->monotone = mono; info->recompute_tokens = spent;
   }
   return BS_OK;
+  });
 }
 
 int bs_builder_tree_size(const bs_builder *b, int32_t *n_nodes, int32_t *n_requests) {
@@ -610,6 +630,7 @@ int bs_builder_tree(const bs_builder *b, int32_t *parent, int32_t *start, int32_
 int bs_builder_emit(bs_builder *b, int32_t n_pre, const int32_t *pre_req, const int32_t *pre_cached,
                     const int32_t *pre_chunk, int32_t n_dec, const int32_t *dec_req, const int32_t *dec_ctx,
                     bs_batch_owned **out) {
+  return guarded(b, [&]() -> int {
   if (!b || !out) return BS_EINVAL;
   *out = nullptr;
   if (!b->finalized) return fail(b, BS_EINVAL, "finalize the builder first");
@@ -638,6 +659,7 @@ int bs_builder_emit(bs_builder *b, int32_t n_pre, const int32_t *pre_req, const 
     dec.push_back({r, dec_ctx[i]});
   }
   return emit(b, pre, dec, out);
+  });
 }
 
 void bs_batch_free(bs_batch_owned *o) {
@@ -650,6 +672,7 @@ void bs_batch_free(bs_batch_owned *o) {
 }
 
 int bs_builder_next_batch(bs_builder *b, int64_t prefill_budget, int64_t decode_budget, bs_batch_owned **out) {
+  return guarded(b, [&]() -> int {
   if (!b || !out) return BS_EINVAL;
   *out = nullptr;
   if (!b->finalized) return fail(b, BS_EINVAL, "finalize the builder first");
@@ -707,6 +730,7 @@ int bs_builder_next_batch(bs_builder *b, int64_t prefill_budget, int64_t decode_
   if (rc) return rc;
   (*out)->info = info;
   return BS_OK;
+  });
 }
 
 }  // extern "C"
