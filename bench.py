@@ -332,7 +332,8 @@ def main():
         mfma("gemm_qkv (RMSNorm factor, RoPE, KV append)", "gemm_qkv", 2.0 * T * d * shape.n_qkv),
         mfma("gemm_o (residual, norm statistics)" + tag, "gemm_o", 2.0 * rows_g * hd * d, None, riding(0) if co else None),
         mfma("gemm_gate_up (SwiGLU epilogue)" + tag, "gemm_gate_up", 2.0 * rows_g * d * 2 * f,
-             "blended_8b_gemm_gate_up_hbm_traffic.txt" if args.workload == "blended_8b" and not co else None,
+             ("blended_8b_coscheduled_gate_up_hbm_traffic.txt" if co else "blended_8b_gemm_gate_up_hbm_traffic.txt")
+             if args.workload == "blended_8b" else None,
              riding(1) if co else None),
         mfma("gemm_down (residual)" + (tag if rows_dn != T else ""), "gemm_down", 2.0 * rows_dn * f * d, None,
              riding(2) if (co and rows_dn != T) else None),
