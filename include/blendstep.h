@@ -217,6 +217,10 @@ typedef struct bs_overlap_knobs {
   int32_t drain_in_last;    /* 1 (default): the last carrying launch goes on until the queue is empty;
                                0: it closes like the others and one more launch drains the queue */
   int32_t head_cus_max;
+  int32_t always;           /* 0 (default): a step takes the co-scheduled path only if the cost model behind
+                               these choices (whole rounds of tiles at measured per-CU rates, 36 GB/s of KV
+                               pages per attention CU, 5.3 TB/s for the whole chip) expects it to be shorter
+                               than the serial one; 1: whenever it has prefill rows and 16-row units */
 } bs_overlap_knobs;
 int bs_set_overlap(bs_ctx *ctx, const bs_overlap_knobs *knobs);
 int bs_get_overlap(const bs_ctx *ctx, bs_overlap_knobs *knobs);

@@ -46,7 +46,7 @@ class BatchDesc(C.Structure):
 
 class OverlapKnobs(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("head_cus_min", "tail_workgroups", "close_margin", "min_prefill_rows",
-                                         "ride_percent", "attention_waves", "carry_down", "drain_in_last", "head_cus_max")]
+                                         "ride_percent", "attention_waves", "carry_down", "drain_in_last", "head_cus_max", "always")]
 
 
 class SplitInfo(C.Structure):

@@ -79,7 +79,7 @@ struct bs_ctx {
   unsigned char *scratch_ptr = nullptr;  // this device's copy of the static scratch array
   // co-scheduling of decode attention with the prefill rows' GEMMs (BS_FLAG_OVERLAP)
   unsigned *sync_words = nullptr;  // [0..3] queue counters of the launches of a step, [4..6] finished tiles, [8..10] queue position at which each launch closed
-  bs_overlap_knobs ov = {0, 208, 8, 256, -1, 2, 0, 1, 96};
+  bs_overlap_knobs ov = {0, 208, 8, 256, -1, 2, 0, 1, 96, 0};
   int64_t ov_first_bytes = 0;      // KV bytes of the 16-row units that the last co-scheduled step gave to its first attention launch
   int ov_first_items = 0;          // and their number
   // optional timeline of the co-scheduled launches: TRACE_CAP workgroups of 8 wavefront records per launch
@@ -647,15 +647,39 @@ int run_down(bs_ctx *c, const bs_weights *w, uint16_t *y, int r0, int r1, hipStr
 // by attention workgroups inside the prefill rows' three GEMM launches, on CUs of their own,
 // and by one launch over the whole chip for what is left.  The decode rows' output
 // projection and FFN follow.  One stream, no events: what overlaps shares a launch.
-int run_coscheduled(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, uint16_t *y, uint16_t *pool,
-                    hipStream_t st) {
-  int rc;
+// Estimated duration of a GEMM launch of M rows on n_cu CUs by whole rounds of tiles (the cost model
+// behind the tile choice: a 256x256 tile sustains 5.8 TFLOP/s per CU, a 160x256 tile 4.5, and 128x128
+// tiles, two per CU, take three quarters of a 256x256 round for half its work).
+double est_gemm_s(int M, int b_rows, int K, int n_cu) {
+  if (M <= 0) return 0.0;
+  const double big = 2.0 * 256 * 256 * K / 5.8e12, tall = 2.0 * 160 * 256 * K / 4.5e12, small = 0.75 * big;
+  auto rounds = [](long tiles, long slots) { return (double)((tiles + slots - 1) / slots); };
+  const long tn = (b_rows + 255) / 256;
+  const double t_big = rounds((long)((M + 255) / 256) * tn, n_cu) * big;
+  const double t_tall = rounds((long)((M + 159) / 160) * tn, n_cu) * tall;
+  const double t_small = rounds((long)((M + 127) / 128) * ((b_rows + 127) / 128), 2L * n_cu) * small;
+  return std::min(t_big, std::min(t_tall, t_small));
+}
+
+// What the co-scheduled schedule would do with a planned step, and what it is expected to gain.
+struct CoPlan {
+  GemmArgs ga[3];
+  int n_carriers = 0, head[3] = {0, 0, 0}, margin[3] = {0, 0, 0}, n_first = 0;
+  int64_t first_bytes = 0;
+  double gain_s = 0.0;  // estimated time of the serial schedule minus that of this one
+};
+
+void plan_coscheduled(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, uint16_t *y, CoPlan &cp) {
   const bs_layer_cfg &g = c->cfg;
   const bs_overlap_knobs &k = c->ov;
-  const int T = p.n_rows, Tp = p.n_prefill_rows, d = g.d_model;
-  const DecodeArgs dargs = decode_args(c, p, c->qbuf, pool);
+  const int T = p.n_rows, Tp = p.n_prefill_rows;
   const bool carry_down = k.carry_down != 0;
   const int n_carriers = carry_down ? 3 : 2;
+  cp.n_carriers = n_carriers;
+  GemmArgs (&ga)[3] = cp.ga;
+  int (&head)[3] = cp.head;
+  int (&margin)[3] = cp.margin;
+  double carriers_s = 0.0;
 
   // The carrying launches: for each, the tile shape and the number of CUs that go to attention for
   // its whole duration.  Measured on MI355X: a CU reads 36 GB/s of KV pages whatever its
@@ -665,18 +689,16 @@ int run_coscheduled(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_
   //   rounds(tiles, CUs - head) * tile time  -  head * 36 GB/s * that time / 5.3 TB/s
   // over both tile shapes and head = head_cus_min, +8, ... (a 256x256 tile sustains 5.8 TFLOP/s
   // per CU, a 160x256 tile 4.5), never hiding more than the queue still holds.
-  GemmArgs ga[3] = {o_proj_args(c, w, x, 0, Tp), gate_up_args(c, w, 0, Tp), down_args(c, w, y, 0, Tp)};
+  ga[0] = o_proj_args(c, w, x, 0, Tp); ga[1] = gate_up_args(c, w, 0, Tp); ga[2] = down_args(c, w, y, 0, Tp);
   const int epi[3] = {EPI_RESID_NORM, EPI_SWIGLU, EPI_RESID};
-  const int kclass[3] = {BS_K_GEMM_O, BS_K_GEMM_GATE_UP, BS_K_GEMM_DOWN};
   const size_t per_token = (size_t)2 * g.head_dim * 2 * g.n_kv_heads;
   int64_t narrow_bytes = 0;
   for (const DecodeItem &it : c->items) narrow_bytes += (int64_t)it.n_tokens * per_token;
   const double cu_stream = 36e9, chip_stream = 5.3e12;
-  int head[3], margin[3];
   double ride_bytes = 0;
   double left = k.ride_percent >= 0 ? narrow_bytes * (k.ride_percent / 100.0) : (double)narrow_bytes;
   for (int l = 0; l < n_carriers; ++l) {
-    double best = 1e300, best_hidden = 0;
+    double best = 1e300, best_hidden = 0, best_t = 0;
     for (int v = 1; v <= 2; ++v) {  // 256x256, 160x256
       ga[l].tile_variant = v;
       const long tiles = gemm_ride_tiles(ga[l], epi[l]);
@@ -687,12 +709,13 @@ int run_coscheduled(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_
         const double t = (double)((tiles + cus - 1) / cus) * tile_s;
         const double hidden = std::min(left, h * cu_stream * t);
         const double net = t - hidden / chip_stream;
-        if (net < best) { best = net; best_hidden = hidden; head[l] = h; margin[l] = v; }
+        if (net < best) { best = net; best_hidden = hidden; best_t = t; head[l] = h; margin[l] = v; }
       }
     }
     ga[l].tile_variant = margin[l];
     left -= best_hidden;
     ride_bytes += best_hidden;
+    carriers_s += best_t;
     // When to stop handing out units.  Tiles of one round end within a few microseconds of each
     // other, and a unit once begun is finished: where the last round is (nearly) full, the queue
     // closes as soon as the first tile of that round is done, so the workgroups behind the tiles
@@ -712,7 +735,37 @@ int run_coscheduled(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_
     first_bytes += (int64_t)c->items[n_first].n_tokens * per_token;
     ++n_first;
   }
-  c->ov_first_bytes = first_bytes;
+  cp.n_first = n_first;
+  cp.first_bytes = first_bytes;
+  // Serial: the three GEMMs over all rows and every 16-row unit on the whole chip.  Co-scheduled: the
+  // carrying launches, the decode rows' GEMMs after them, the units that do not ride on the whole chip,
+  // and about 30 us for the extra launches and the units that outlast their tiles.
+  const int hd = g.n_q_heads * g.head_dim, dm = g.d_model, f = g.d_ffn, n_cu = c->n_cu;
+  double serial_s = est_gemm_s(T, dm, hd, n_cu) + est_gemm_s(T, 2 * f, dm, n_cu) + (double)narrow_bytes / chip_stream;
+  double co_s = carriers_s + est_gemm_s(T - Tp, dm, hd, n_cu) + est_gemm_s(T - Tp, 2 * f, dm, n_cu) +
+                ((double)narrow_bytes - ride_bytes) / chip_stream + 30e-6;
+  if (carry_down) {
+    serial_s += est_gemm_s(T, dm, f, n_cu);
+    co_s += est_gemm_s(T - Tp, dm, f, n_cu);
+  }
+  cp.gain_s = serial_s - co_s;
+}
+
+int run_coscheduled(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, uint16_t *y, uint16_t *pool,
+                    hipStream_t st, CoPlan &cp) {
+  int rc;
+  const bs_layer_cfg &g = c->cfg;
+  const bs_overlap_knobs &k = c->ov;
+  const int T = p.n_rows, Tp = p.n_prefill_rows, d = g.d_model;
+  const DecodeArgs dargs = decode_args(c, p, c->qbuf, pool);
+  const bool carry_down = k.carry_down != 0;
+  const int n_carriers = cp.n_carriers, n_first = cp.n_first;
+  GemmArgs (&ga)[3] = cp.ga;
+  const int (&head)[3] = cp.head;
+  const int (&margin)[3] = cp.margin;
+  const int epi[3] = {EPI_RESID_NORM, EPI_SWIGLU, EPI_RESID};
+  const int kclass[3] = {BS_K_GEMM_O, BS_K_GEMM_GATE_UP, BS_K_GEMM_DOWN};
+  c->ov_first_bytes = cp.first_bytes;
   c->ov_first_items = n_first;
 
   // attention of the prefill rows, of the wide decode items and of the 16-row units that do not ride
@@ -953,8 +1006,12 @@ int run_layer(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, 
 
   // co-scheduling pays where there are GEMM rows that do not wait for decode attention (the
   // prefill rows) and 16-row decode units to run beside them
-  const bool blend = (flags & BS_FLAG_OVERLAP) && p.n_narrow > 0 && p.n_prefill_rows >= c->ov.min_prefill_rows;
-  if (blend) return run_coscheduled(c, p, w, x, y, pool, st);
+  // and where its cost model expects the step to come out shorter than the serial one (knob `always`: regardless)
+  if ((flags & BS_FLAG_OVERLAP) && p.n_narrow > 0 && p.n_prefill_rows >= c->ov.min_prefill_rows) {
+    CoPlan cp;
+    plan_coscheduled(c, p, w, x, y, cp);
+    if (c->ov.always || cp.gain_s > 0.0) return run_coscheduled(c, p, w, x, y, pool, st, cp);
+  }
   if ((rc = run_attention(c, p, c->qbuf, c->attn, pool, st))) return rc;
   if ((rc = run_o_gate_up(c, w, x, 0, T, st))) return rc;
   return run_down(c, w, y, 0, T, st);
@@ -1227,6 +1284,7 @@ int bs_set_overlap(bs_ctx *c, const bs_overlap_knobs *k) {
   c->ov = *k;
   c->ov.carry_down = k->carry_down != 0;
   c->ov.drain_in_last = k->drain_in_last != 0;
+  c->ov.always = k->always != 0;
   return BS_OK;
 }
 

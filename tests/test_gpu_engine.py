@@ -55,7 +55,7 @@ def test_pool_outputs_match_the_oracle_chain_step_by_step(lib, seed, flags):
     vp = np.zeros_like(kp)
     layer = lib.Layer(shape, device=0)
     if flags:
-        layer.set_overlap(head_cus_min=8, head_cus_max=16, tail_workgroups=8, min_prefill_rows=1)
+        layer.set_overlap(head_cus_min=8, head_cus_max=16, tail_workgroups=8, min_prefill_rows=1, always=1)
     weights, keep = layer.upload_weights(tens0)
     dev = lib.binding_device_state(weights, keep, torch.from_numpy(x_all).cuda().to(torch.bfloat16),
                                    layer.pack_pool(W.f32_to_bf16_bits(kp.astype(np.float32)), W.f32_to_bf16_bits(vp.astype(np.float32))), pages)

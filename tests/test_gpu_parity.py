@@ -344,8 +344,10 @@ def run_coscheduled(lib, shape, batch, tens, knobs, chunk_pages=0):
     if chunk_pages:
         layer.set_chunk_pages(chunk_pages)
     dev = layer.upload(tens, batch)
+    layer.profile(True)
     y = layer.blend_step(dev, batch, flags=lib.FLAG_OVERLAP)
     torch.cuda.synchronize()
+    run_coscheduled.taken = layer.profile_read()["gemm_decode_rows"][1] > 0   # the decode rows' GEMMs ran apart
     k, v = layer.unpack_pool(dev.kv_pool, dev.n_pages)
     return to_np(y), to_np(k), to_np(v)
 
@@ -364,12 +366,13 @@ def test_coscheduled_step_matches_the_oracle(lib, shape, knobs):
     # (margin beyond the tile count) with everything left to a launch of its own; all units,
     # some or none of them waiting for the carrying launches; two or three carrying launches;
     # several chunks per tail, so the queue is longer than the workers are many
-    knobs = dict(knobs, min_prefill_rows=1)
+    knobs = dict(knobs, min_prefill_rows=1, always=1)
     batch = W.batch_random(17, n_prefill=4, n_decode=60, max_q=150, max_ctx=700, n_roots=3)
     tens = W.make_tensors(shape, batch, 17, gains="random")
     ref = O.layer_step(shape, tens, batch)
     diag = O.layer_step(shape, tens, batch, storage="bf16")
     y, k, v = run_coscheduled(lib, shape, batch, tens, knobs, chunk_pages=4)
+    assert run_coscheduled.taken, "the step did not take the co-scheduled path"
     check(y, ref["y"], diag["y"], "co-scheduled %s" % knobs)
     kn = k[ref["dest"][:, 0], ref["dest"][:, 1]]
     assert errs(kn, ref["k_new"])[0] <= MAXREL
@@ -381,7 +384,7 @@ def test_coscheduled_step_agrees_with_the_serial_one(lib):
     batch = W.batch_random(4, n_prefill=4, n_decode=30, max_q=120, max_ctx=500)
     tens = W.make_tensors(W.TINY, batch, 4)
     y0, _, _, _ = run_step(lib, W.TINY, batch, tens, 0)
-    y1, _, _ = run_coscheduled(lib, W.TINY, batch, tens, dict(head_cus_min=8, tail_workgroups=16, min_prefill_rows=1))
+    y1, _, _ = run_coscheduled(lib, W.TINY, batch, tens, dict(head_cus_min=8, tail_workgroups=16, min_prefill_rows=1, always=1))
     assert np.max(np.abs(y0 - y1)) <= 2.0 ** -7 * np.max(np.abs(y0))
     assert np.mean(np.abs(y0 - y1)) <= 1e-4
 
@@ -391,8 +394,18 @@ def test_coscheduled_flag_falls_back_where_nothing_can_overlap(lib):
     for batch in (W.batch_decode_only(33, 130, seed=2), W.batch_prefill_only(3, 75, seed=2)):
         tens = W.make_tensors(W.TINY, batch, 2)
         y0, _, _, _ = run_step(lib, W.TINY, batch, tens, 0)
-        y1, _, _ = run_coscheduled(lib, W.TINY, batch, tens, dict(head_cus_min=8, tail_workgroups=16, min_prefill_rows=1))
+        y1, _, _ = run_coscheduled(lib, W.TINY, batch, tens, dict(head_cus_min=8, tail_workgroups=16, min_prefill_rows=1, always=1))
+        assert not run_coscheduled.taken
         assert np.array_equal(y0, y1)
+
+
+def test_cost_model_keeps_small_steps_serial(lib):
+    # without `always` a tiny step is not expected to gain anything and runs the serial schedule
+    batch = W.batch_random(4, n_prefill=4, n_decode=30, max_q=120, max_ctx=500)
+    tens = W.make_tensors(W.TINY, batch, 4)
+    y0, _, _, _ = run_step(lib, W.TINY, batch, tens, 0)
+    y1, _, _ = run_coscheduled(lib, W.TINY, batch, tens, dict(min_prefill_rows=1))
+    assert not run_coscheduled.taken and np.array_equal(y0, y1)
 
 
 def test_repeated_calls_and_growing_workspace(lib):
