@@ -351,6 +351,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int bid) {
   }
   // drain the look-ahead loads (zeros or clamped rows) before the LDS is released
   __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
+  // the value heads of the fused projection pass through LDS on their way out: nobody may
+  // still be reading panels there
+  if (EPI == EPI_QKV) __syncthreads();
 
   // ---- epilogues ---------------------------------------------------------------
   // accumulator element e of block (ni, mi): m = m0 + wm0 + mi*16 + lr,
@@ -478,6 +481,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int bid) {
 
     if (EPI == EPI_QKV) {
       constexpr int HB = DH / 16, PB = HB / 2, HALF = DH / 2;
+      constexpr int FS = (WTM + 4) * 2;  // bytes per feature of a wavefront's transposed block
+      static_assert(NW * WTN * FS <= NU * UNIT, "the transposed blocks fit the panel ring");
       const size_t tile_elems = (size_t)16 * DH;  // one K or V tile of a (page, head)
   #pragma unroll
       for (int hh = 0; hh < WTN / DH; ++hh) {
@@ -518,17 +523,63 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int bid) {
               store_bf16x4(dst + HALF + i, hi[0], hi[1], hi[2], hi[3]);
             }
           } else {
-            const size_t page = a.row_page[m];
-            const int slot = a.row_slot[m];
-            uint16_t *dst = a.kv_pool +
-                            ((page * 2 + 1) * a.n_kv_heads + (head - a.n_q_heads - a.n_kv_heads)) * tile_elems + slot;
+            // V^T tiles hold, per feature, the 16 slots of a page side by side, while a lane
+            // holds four features of one row: the wavefront turns its block round in LDS
+            // (feature-major, FS bytes per feature: the row count padded so that neither the
+            // 2-byte writes nor the 8-byte reads below collide on banks)
+            unsigned char *vt = smem + wave * (WTN * FS) + hh * (DH * FS);
   #pragma unroll
             for (int b = 0; b < HB; ++b)
   #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const int ei = b * 16 + 4 * lg + e;
-                dst[ei * 16] = f32_to_bf16(acc[hh * HB + b][mi][e] * s);
+              for (int e = 0; e < 4; ++e)
+                *reinterpret_cast<uint16_t *>(vt + (b * 16 + 4 * lg + e) * FS + (mi * 16 + lr) * 2) =
+                    f32_to_bf16(acc[hh * HB + b][mi][e] * s);
+          }
+        }
+        if (!is_q && !is_k) {
+          // back out of LDS (written and read by this wavefront only): lane = 4 * feature + quad
+          // reads rows 4 quad .. 4 quad + 3 of a 16-row block for one feature.  Inside a prefill
+          // segment these are four adjacent slots of one page, and the 64 lanes then cover 512
+          // contiguous bytes of the page's V^T tile; they go out as one 8-byte store (or two
+          // 4-byte ones) where the address allows.  Rows of different sequences, or on either
+          // side of a page boundary, take a 2-byte store each.
+          __builtin_amdgcn_wave_barrier();  // the LDS operations of a wavefront complete in order
+          const unsigned char *vt = smem + wave * (WTN * FS) + hh * (DH * FS);
+          const int vh = head - a.n_q_heads - a.n_kv_heads;
+          const int fl = lane >> 2, rq = lane & 3;
+  #pragma unroll
+          for (int mi = 0; mi < MI; ++mi) {
+            const int ml = mi * 16 + rq * 4, mb = m0 + wm0 + ml;
+            size_t pg[4];
+            int sl[4];
+  #pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int m = (!CK || mb + e < a.M) ? mb + e : a.M - 1;
+              pg[e] = a.row_page[m];
+              sl[e] = a.row_slot[m];
+            }
+            bool run = !CK || mb + 3 < a.M;
+  #pragma unroll
+            for (int e = 1; e < 4; ++e) run = run && pg[e] == pg[0] && sl[e] == sl[0] + e;
+  #pragma unroll
+            for (int b = 0; b < HB; ++b) {
+              const int ei = b * 16 + fl;
+              const u32x2_t v = *reinterpret_cast<const u32x2_t *>(vt + ei * FS + ml * 2);
+              uint16_t *d0 = a.kv_pool + ((pg[0] * 2 + 1) * a.n_kv_heads + vh) * tile_elems + ei * 16 + sl[0];
+              if (run && (reinterpret_cast<uintptr_t>(d0) & 7) == 0) {
+                *reinterpret_cast<u32x2_t *>(d0) = v;
+              } else if (run && (reinterpret_cast<uintptr_t>(d0) & 3) == 0) {
+                reinterpret_cast<uint32_t *>(d0)[0] = v.x;
+                reinterpret_cast<uint32_t *>(d0)[1] = v.y;
+              } else {
+                const uint16_t ve[4] = {(uint16_t)(v.x & 0xFFFFu), (uint16_t)(v.x >> 16), (uint16_t)(v.y & 0xFFFFu),
+                                        (uint16_t)(v.y >> 16)};
+  #pragma unroll
+                for (int e = 0; e < 4; ++e)
+                  if (!CK || mb + e < a.M)
+                    a.kv_pool[((pg[e] * 2 + 1) * a.n_kv_heads + vh) * tile_elems + ei * 16 + sl[e]] = ve[e];
               }
+            }
           }
         }
       }
