@@ -248,7 +248,8 @@ int bs_overlap_trace(bs_ctx *ctx, int on);
 int bs_overlap_trace_read(bs_ctx *ctx, int32_t launch, uint64_t *out, int64_t cap_records, int64_t *n_records);
 
 /* Tuning knob: GEMM tile shape for the calls on this context: 0 = chosen per problem (default), 1 = 256x256,
- * 2 = 160x256 (not for the QKV GEMM), 3 = 128x128.  With 0, GEMMs of at most 256 rows run as one
+ * 2 = 160x256 (not for the QKV GEMM), 3 = 128x128, 6 = 256x256 tiles shared between workgroups (one persistent
+ * workgroup per CU; the tiles that do not fill a whole round are cut along K into equal ranges).  With 0, GEMMs of at most 256 rows run as one
  * row of 128x256 or 256x128 tiles on a pipeline with its own look-ahead for the weight panel; a
  * forced shape switches that off. */
 int bs_set_gemm_tiles(bs_ctx *ctx, int32_t variant);

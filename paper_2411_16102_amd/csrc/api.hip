@@ -78,6 +78,8 @@ struct bs_ctx {
   std::vector<std::pair<int, std::pair<int, int>>> pf_order;
   unsigned char *scratch_ptr = nullptr;  // this device's copy of the static scratch array
   // co-scheduling of decode attention with the prefill rows' GEMMs (BS_FLAG_OVERLAP)
+  float *sk_ws = nullptr;       // partial tiles of the GEMM launches whose workgroups share tiles
+  unsigned *sk_cnt = nullptr;   // their arrival counters (zero between launches)
   unsigned *sync_words = nullptr;  // [0..3] queue counters of the launches of a step, [4..6] finished tiles, [8..10] queue position at which each launch closed
   bs_overlap_knobs ov = {0, 208, 8, 256, -1, 2, 0, 1, 96, 0};
   int64_t ov_first_bytes = 0;      // KV bytes of the 16-row units that the last co-scheduled step gave to its first attention launch
@@ -569,6 +571,7 @@ GemmArgs o_proj_args(bs_ctx *c, const bs_weights *w, const uint16_t *x, int r0, 
   o.C32 = c->x1 + (size_t)r0 * d; o.ldc = d; o.resid = x + (size_t)r0 * d; o.ldr = d;
   o.gain = (const uint16_t *)w->g_ffn; o.C_gain = c->xg2 + (size_t)r0 * d;
   o.ss_out = c->ss2 + r0; o.ss_stride = c->cap_rows;
+  o.sk_ws = c->sk_ws; o.sk_cnt = c->sk_cnt;
   return o;
 }
 
@@ -580,6 +583,7 @@ GemmArgs gate_up_args(bs_ctx *c, const bs_weights *w, int r0, int r1) {
   u.M = r1 - r0; u.N = f; u.K = d;
   u.C = c->act + (size_t)r0 * f; u.ldc = f;
   u.rstd = c->rstd2 + r0;
+  u.sk_ws = c->sk_ws; u.sk_cnt = c->sk_cnt;
   return u;
 }
 
@@ -590,6 +594,7 @@ GemmArgs down_args(bs_ctx *c, const bs_weights *w, uint16_t *y, int r0, int r1) 
   dn.A = c->act + (size_t)r0 * f; dn.lda = f; dn.B = (const uint16_t *)w->w_down; dn.ldb = f;
   dn.M = r1 - r0; dn.N = d; dn.K = f;
   dn.C = y + (size_t)r0 * d; dn.ldc = d; dn.resid32 = c->x1 + (size_t)r0 * d; dn.ldr = d;
+  dn.sk_ws = c->sk_ws; dn.sk_cnt = c->sk_cnt;
   return dn;
 }
 
@@ -890,6 +895,9 @@ int bs_create(const bs_layer_cfg *cfg, int device, bs_ctx **out) {
   } catch (const std::bad_alloc &) { c->err = "out of host memory"; return bail(BS_ENOMEM); }
   if ((rc = dev_alloc(c, &c->sync_words, 16))) return bail(rc);
   if (hipMemset(c->sync_words, 0, 16 * sizeof(unsigned)) != hipSuccess) { c->err = "hipMemset failed"; return bail(BS_EHIP); }
+  if ((rc = dev_alloc(c, &c->sk_ws, gemm_sk_workspace_floats()))) return bail(rc);
+  if ((rc = dev_alloc(c, &c->sk_cnt, (size_t)gemm_sk_counters()))) return bail(rc);
+  if (hipMemset(c->sk_cnt, 0, gemm_sk_counters() * sizeof(unsigned)) != hipSuccess) { c->err = "hipMemset failed"; return bail(BS_EHIP); }
   {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) { c->err = "hipGetDeviceProperties failed"; return bail(BS_EHIP); }
@@ -906,7 +914,7 @@ void bs_destroy(bs_ctx *c) {
   (void)hipDeviceSynchronize();
   for (void *p : {(void *)c->rope_cos, (void *)c->rope_sin, (void *)c->xg, (void *)c->qbuf, (void *)c->attn, (void *)c->x1,
                   (void *)c->xg2, (void *)c->act, (void *)c->rstd1, (void *)c->rstd2, (void *)c->ss2, (void *)c->part_acc, (void *)c->part_m,
-                  (void *)c->part_l, (void *)c->d_blob, (void *)c->splitk_ws, (void *)c->hid[0], (void *)c->hid[1], (void *)c->sync_words, (void *)c->trace_buf})
+                  (void *)c->part_l, (void *)c->d_blob, (void *)c->splitk_ws, (void *)c->hid[0], (void *)c->hid[1], (void *)c->sync_words, (void *)c->trace_buf, (void *)c->sk_ws, (void *)c->sk_cnt})
     if (p) (void)hipFree(p);
   for (int i = 0; i < RING; ++i) {
     if (c->h_blob[i]) (void)hipHostFree(c->h_blob[i]);
@@ -997,6 +1005,7 @@ int run_layer(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, 
   q.rope_cos = c->rope_cos; q.rope_sin = c->rope_sin;
   q.row_pos = c->d_blob + p.off_row_pos; q.row_page = c->d_blob + p.off_row_page; q.row_slot = c->d_blob + p.off_row_slot;
   q.q_out = c->qbuf; q.kv_pool = pool;
+  q.sk_ws = c->sk_ws; q.sk_cnt = c->sk_cnt;
   q.k_splits = gemm_splitk_choice(q.M, q.N, q.K, EPI_QKV, 0);
   if (q.k_splits > 1) {
     if ((rc = ensure_splitk(c, (size_t)q.k_splits * q.M * q.N))) return rc;
@@ -1155,6 +1164,7 @@ int bs_gemm_nt(bs_ctx *c, const void *a, const void *b, void *out, int32_t m, in
   GemmArgs g{};
   g.A = (const uint16_t *)a; g.lda = k; g.B = (const uint16_t *)b; g.ldb = k;
   g.M = m; g.N = n; g.K = k; g.C = (uint16_t *)out; g.ldc = n;
+  g.sk_ws = c->sk_ws; g.sk_cnt = c->sk_cnt;
   HIP_TRY(c, launch_gemm(g, EPI_PLAIN, c->cfg.head_dim, (hipStream_t)stream));
   return BS_OK;
   });
@@ -1205,7 +1215,7 @@ int bs_profile_read(bs_ctx *c, int which, double *total_ms, int64_t *launches) {
 
 int bs_set_gemm_tiles(bs_ctx *c, int32_t variant) {
   if (!c) return BS_EINVAL;
-  if (variant < 0 || variant > 3) return fail(c, BS_EINVAL, "gemm tile variant %d (0..3)", variant);
+  if (variant < 0 || (variant > 3 && variant != 6)) return fail(c, BS_EINVAL, "gemm tile variant %d (0..3 or 6)", variant);
   c->forced_tiles = variant;
   return BS_OK;
 }

@@ -78,9 +78,55 @@ constexpr int waitcnt_imm(int vm, bool lgkm0) {
   return (vm & 0xF) | ((vm >> 4) << 14) | 0x70 | (lgkm0 ? 0 : 0xF00);
 }
 
-// One workgroup's tile; `bid` is the workgroup's number among the GEMM workgroups of the launch.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH, int DEEP = 0>
-__device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int bid) {
+// Shared tiles.  A launch of G persistent workgroups takes the tiles [0, n_dp) of the launch's
+// tile order whole, workgroup w the tiles w, w + G, ...; the k-tiles of the other n_sk tiles
+// form one line of n_sk * nk iterations that the first g_sk workgroups cut into equal
+// consecutive ranges, so a tile at a cut is computed by two or more workgroups, each over a
+// part of K.  Every such workgroup leaves its partial tile in the workspace and counts itself
+// in; the one that arrives last adds the parts up (always in the order of their k-ranges,
+// its own part re-read like the others, so the sum does not depend on who was last) and runs
+// the epilogue.  Nobody waits for anybody.
+struct SkPlan {
+  int n_dp, n_sk, g_sk, nk;
+  float *ws;      // [2 * G][BM * BN]: slot 2 w of workgroup w for its first segment, 2 w + 1 for its last
+  unsigned *cnt;  // [n_sk] arrivals at each shared tile; zero between launches
+};
+struct SkSeg {
+  int pid, kt0, kt1;  // tile, k-tiles [kt0, kt1)
+  int j;              // index of the tile among the shared ones
+  int parts;          // workgroups that hold a part of the tile (1: this one has all of it)
+  int w_first;        // the first of them; they are consecutive
+  int my_slot;
+};
+constexpr int SK_SNAP = 4;      // a cut this close to a tile boundary moves onto it
+constexpr int SK_MIN_ITERS = 16;  // shortest range worth a workgroup of its own
+
+// first iteration of workgroup w's range (w = g_sk: the end of the line)
+__device__ __forceinline__ int sk_bound(const SkPlan &p, int w) {
+  const int total = p.n_sk * p.nk;
+  int b = (int)((long)total * w / p.g_sk);
+  const int r = b % p.nk;
+  if (r < SK_SNAP) b -= r;
+  else if (p.nk - r < SK_SNAP) b += p.nk - r;
+  return b;
+}
+// the workgroups whose ranges meet shared tile j
+__device__ __forceinline__ void sk_tile_span(const SkPlan &p, int j, int *w_first, int *parts) {
+  const int lo = j * p.nk, hi = lo + p.nk;
+  int w = (int)((long)lo * p.g_sk / (p.n_sk * p.nk));
+  while (w + 1 < p.g_sk && sk_bound(p, w + 1) <= lo) ++w;
+  while (w > 0 && sk_bound(p, w) > lo) --w;
+  int n = 1;
+  while (w + n < p.g_sk && sk_bound(p, w + n) < hi) ++n;
+  *w_first = w;
+  *parts = n;
+}
+
+// One workgroup's tile; `bid` is the workgroup's number among the GEMM workgroups of the launch
+// (SK: the tile and the k-range come from `seg` instead).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH, int DEEP = 0, bool SK = false>
+__device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int bid, const SkPlan *sp = nullptr, const SkSeg seg = SkSeg{}) {
+  static_assert(!SK || (!DEEP && EPI != EPI_PARTIAL), "shared tiles use the five-panel ring and a real epilogue");
   constexpr int NW = WAVES_M * WAVES_N;
   // DEEP: the pipeline for one round of tiles over few rows, where every CU streams a weight
   // panel of its own from HBM; the first half of the wavefronts requests the activation
@@ -106,7 +152,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int bid) {
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (n_lim - a.n_begin + OUT_BN - 1) / OUT_BN;
   // split-K: consecutive workgroups are the k-ranges of one tile
   const int split = (EPI == EPI_PARTIAL) ? bid % a.k_splits : 0;
-  const int tile_id = (EPI == EPI_PARTIAL) ? bid / a.k_splits : bid;
+  const int tile_id = SK ? seg.pid : (EPI == EPI_PARTIAL) ? bid / a.k_splits : bid;
   const TileCoord tc = map_tile(tile_id, tiles_m * tiles_n, tiles_m, tiles_n);
   const int m0 = tc.tm * BM, n0 = a.n_begin + tc.tn * OUT_BN;
 
@@ -189,8 +235,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int bid) {
 
   const int nk_all = (a.K + BK - 1) / BK;
   // this workgroup's k-tiles [kt0, kt1): all of them, or one of k_splits nearly equal ranges
-  const int kt0 = (EPI == EPI_PARTIAL) ? (int)((long)nk_all * split / a.k_splits) : 0;
-  const int kt1 = (EPI == EPI_PARTIAL) ? (int)((long)nk_all * (split + 1) / a.k_splits) : nk_all;
+  const int kt0 = SK ? seg.kt0 : (EPI == EPI_PARTIAL) ? (int)((long)nk_all * split / a.k_splits) : 0;
+  const int kt1 = SK ? seg.kt1 : (EPI == EPI_PARTIAL) ? (int)((long)nk_all * (split + 1) / a.k_splits) : nk_all;
   constexpr int NF = MI + NI;   // fragment reads per 32-wide k-step
   constexpr int NMF = MI * NI;  // MFMAs per 32-wide k-step
   // read number o of k-step ks (32 wide, two per tile) of the panels in ring slots sa, sb
@@ -354,6 +400,65 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int bid) {
   // the value heads of the fused projection pass through LDS on their way out: nobody may
   // still be reading panels there
   if (EPI == EPI_QKV) __syncthreads();
+
+  if constexpr (SK) {
+    if (seg.parts > 1) {
+      constexpr int NT = NW * 64;
+      constexpr size_t TILE = (size_t)BM * BN;
+      // The register image of the accumulators, 16 bytes per thread and block (whoever adds the
+      // parts up has the same layout).  The eight XCDs keep L2 caches of their own, so parts
+      // written and read with ordinary accesses would need the whole-cache write-back and
+      // invalidation of a device-wide fence at every cut (measured: a quarter of a millisecond
+      // per launch); the parts travel with the device-scope cache policy instead (sc1: to and
+      // from the point where all XCDs agree), which touches nothing else.
+      typedef unsigned int u4_t __attribute__((ext_vector_type(4)));
+      constexpr int SC1 = 16;
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(sp->ws, 0, 0x7fffffff, 0x00020000);
+      const unsigned voff = (unsigned)t * 16u;
+      {
+        const unsigned soff = (unsigned)seg.my_slot * (unsigned)(TILE * 4);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int mi = 0; mi < MI; ++mi) {
+            const f32x4_t c = acc[ni][mi];
+            const u4_t v = {__float_as_uint(c[0]), __float_as_uint(c[1]), __float_as_uint(c[2]), __float_as_uint(c[3])};
+            __builtin_amdgcn_raw_buffer_store_b128(v, rs, voff + (unsigned)((ni * MI + mi) * NT * 16), soff, SC1);
+          }
+      }
+      __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));  // the part has arrived there before the workgroup counts itself in
+      __syncthreads();
+      volatile unsigned *flag = reinterpret_cast<volatile unsigned *>(smem + NU * UNIT - 16);
+      if (t == 0) *flag = atomicAdd(sp->cnt + seg.j, 1u);
+      __syncthreads();
+      if (*flag + 1u != (unsigned)seg.parts) return;
+      if (t == 0) atomicExch(sp->cnt + seg.j, 0u);  // as the next launch expects it
+      for (int q = 0; q < seg.parts; ++q) {
+        const int w2 = seg.w_first + q;
+        const int slot = 2 * w2 + (sk_bound(*sp, w2) / sp->nk == seg.j ? 0 : 1);
+        const unsigned soff = (unsigned)slot * (unsigned)(TILE * 4);
+        // sixteen blocks at a time: the loads of a batch are all in flight before the first is
+        // used (each is a round trip past the L2; the registers of the fragments are free now)
+        constexpr int NB = NI * MI, BATCH = NB < 16 ? NB : 16;
+        static_assert(NB % BATCH == 0, "whole batches");
+#pragma unroll
+        for (int b0 = 0; b0 < NB; b0 += BATCH) {
+          u4_t v[BATCH];
+#pragma unroll
+          for (int b = 0; b < BATCH; ++b)
+            v[b] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + (unsigned)((b0 + b) * NT * 16), soff, SC1);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int b = 0; b < BATCH; ++b) {
+            const int ni = (b0 + b) / MI, mi = (b0 + b) % MI;
+            const f32x4_t c = {__uint_as_float(v[b].x), __uint_as_float(v[b].y), __uint_as_float(v[b].z), __uint_as_float(v[b].w)};
+            acc[ni][mi] = q == 0 ? c : acc[ni][mi] + c;
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+  }
 
   // ---- epilogues ---------------------------------------------------------------
   // accumulator element e of block (ni, mi): m = m0 + wm0 + mi*16 + lr,
@@ -596,6 +701,40 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_kernel(const GemmA
   gemm_tile<BM, BN, WAVES_M, WAVES_N, EPI, DH, DEEP>(a, (int)blockIdx.x);
 }
 
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_sk_kernel(const GemmArgs a, const SkPlan p) {
+  const int w = (int)blockIdx.x, G = (int)gridDim.x;
+  int pid = w;
+  int i = 0, i1 = 0, j0 = 0;
+  if (w < p.g_sk) {
+    i = sk_bound(p, w);
+    i1 = sk_bound(p, w + 1);
+    j0 = i / p.nk;
+  }
+  bool again = false;
+  for (;;) {
+    SkSeg s;
+    if (pid < p.n_dp) {
+      s = SkSeg{pid, 0, p.nk, 0, 1, 0, 0};
+      pid += G;
+    } else if (i < i1) {
+      const int j = i / p.nk, kt0 = i - j * p.nk;
+      const int kt1 = (i1 - j * p.nk) < p.nk ? (i1 - j * p.nk) : p.nk;
+      s = SkSeg{p.n_dp + j, kt0, kt1, j, 1, 0, 0};
+      if (kt0 > 0 || kt1 < p.nk) {
+        sk_tile_span(p, j, &s.w_first, &s.parts);
+        s.my_slot = 2 * w + (j == j0 ? 0 : 1);
+      }
+      i = j * p.nk + kt1;
+    } else {
+      break;
+    }
+    if (again) __syncthreads();  // the panel ring and the flag word change hands
+    again = true;
+    gemm_tile<BM, BN, WAVES_M, WAVES_N, EPI, DH, 0, true>(a, 0, &p, s);
+  }
+}
+
 // A GEMM launch that carries decode attention (Section 3.3: a step whose compute-bound and
 // memory-bound operators overlap costs the larger of their times; Section 2.2, operator-level
 // overlapping).  Grid: `head` attention workgroups, the GEMM tiles, `tail` attention
@@ -746,6 +885,45 @@ hipError_t launch_one(const GemmArgs &a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+constexpr int SK_MAX_G = 256;  // workgroups of a shared-tile launch at most: one per CU
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int DH>
+hipError_t launch_sk(const GemmArgs &a, hipStream_t stream) {
+  constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  constexpr int LDS = NU * (BM > BN ? BM : BN) * BK * 2;
+  static_assert(BM == 256 && BN == 256, "the workspace slots are sized for 256x256 tiles");
+  if (!a.sk_ws || !a.sk_cnt || a.n_count || a.k_splits > 1) return hipErrorInvalidValue;
+  auto kern = gemm_sk_kernel<BM, BN, WAVES_M, WAVES_N, EPI, DH>;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const long tiles = (long)((a.M + BM - 1) / BM) * ((a.N + OUT_BN - 1) / OUT_BN);
+  if (tiles <= 0) return hipSuccess;
+  const int G = a.n_cu > 0 && a.n_cu < SK_MAX_G ? a.n_cu : SK_MAX_G;
+  SkPlan p{};
+  p.nk = (a.K + BK - 1) / BK;
+  p.ws = a.sk_ws;
+  p.cnt = a.sk_cnt;
+  if (tiles % G == 0) {
+    p.n_dp = (int)tiles;
+  } else {
+    // (with more than one round the last whole round is shared too: every workgroup then has more
+    // than a tile's worth of iterations and at most two cuts)
+    p.n_sk = tiles > G ? (int)(tiles % G) + G : (int)tiles;
+    p.n_dp = (int)tiles - p.n_sk;
+    const long total = (long)p.n_sk * p.nk;
+    p.g_sk = (int)std::min<long>(G, std::max<long>(1, total / SK_MIN_ITERS));
+    if (total * p.g_sk >= (1L << 31)) return hipErrorInvalidValue;
+  }
+  const int grid = (int)std::min<long>(G, std::max<long>(p.g_sk, p.n_dp));
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES_M * WAVES_N * 64), LDS, stream, a, p);
+  return hipGetLastError();
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int ADH>
 hipError_t launch_ride(const GemmArgs &a, const GemmRide &r, hipStream_t stream) {
   constexpr int OUT_BN = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
@@ -776,7 +954,7 @@ hipError_t launch_ride(const GemmArgs &a, const GemmRide &r, hipStream_t stream)
 // (256x128) or three of 32 KB (128x256); measured against two slots (six / four weight slots) on the
 // 256-row gate/up GEMM of the 8B layer: 0.075 against 0.078 ms, the other GEMMs the same
 constexpr int DEEP_X = 2;
-enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3, V_S128 = 4, V_S256 = 5 };
+enum { V_AUTO = 0, V_BIG = 1, V_TALL = 2, V_SMALL = 3, V_S128 = 4, V_S256 = 5, V_SHARED = 6 };
 constexpr int N_CU = 256;
 
 thread_local int g_forced_variant = V_AUTO;  // set by the calling entry point from its context, for the launches of that call
@@ -795,7 +973,9 @@ int short_variant(int m) {
   return m <= 128 ? V_S128 : V_S256;
 }
 
-int choose_variant(int m, int n_b_rows, int epilogue, int dh, int n_cu) {
+// share_k: the contraction length if the launch may share tiles between workgroups (it has the
+// workspace for it and covers all columns), else 0
+int choose_variant(int m, int n_b_rows, int epilogue, int dh, int n_cu, int share_k = 0) {
   if (n_cu <= 0) n_cu = N_CU;
   if (g_forced_variant != V_AUTO && !(g_forced_variant == V_TALL && epilogue == EPI_QKV)) return g_forced_variant;
   (void)dh;
@@ -815,12 +995,26 @@ int choose_variant(int m, int n_b_rows, int epilogue, int dh, int n_cu) {
     const double t = (double)full * c.T + (rem ? c.T * (c.a + (1.0 - c.a) * (double)rem / (double)slots) : 0.0);
     if (t < best_t) { best_t = t; best = c.v; }
   }
+  // Shared 256x256 tiles: the chip's worth of k-tile iterations with nothing idle, 3 % for the
+  // persistent loop, and what the cuts cost: a workgroup passes up to two partial tiles through
+  // memory, about 0.08 ms per launch whatever its size (measured on the GEMMs of the 8B and 70B
+  // layers), i.e. 53 k-tiles' worth of a round.  It pays only where K is long: the down
+  // projection of the 70B layer at 5120 rows, 2.5 rounds of 448 k-tiles, 1.92 against 2.11 ms.
+  if (share_k >= 4096 && m > 256) {
+    const long tiles = n_tiles(m, n_b_rows, 256, 256);
+    const long g = std::min<long>(n_cu, N_CU);
+    if (tiles % g) {
+      const double t = (double)tiles / (double)g * 1.03 + 53.0 / (double)((share_k + BK - 1) / BK);
+      if (t < best_t) { best_t = t; best = V_SHARED; }
+    }
+  }
   return best;
 }
 
 template <int EPI, int DH_BIG_M, int DH_BIG_N>
 hipError_t launch_variant(const GemmArgs &a, int v, hipStream_t stream) {
   if (v == V_BIG) return launch_one<256, 256, DH_BIG_M, DH_BIG_N, EPI, (DH_BIG_M == 4 ? 128 : 64)>(a, stream);
+  if (v == V_SHARED) return launch_sk<256, 256, DH_BIG_M, DH_BIG_N, EPI, (DH_BIG_M == 4 ? 128 : 64)>(a, stream);
   if (v == V_TALL) return launch_one<160, 256, 2, 4, EPI, 64>(a, stream);
   if constexpr (EPI == EPI_SWIGLU || EPI == EPI_PLAIN) {
     if (v == V_S128) return launch_one<128, 256, 2, 4, EPI, 64, DEEP_X>(a, stream);
@@ -832,6 +1026,8 @@ hipError_t launch_variant(const GemmArgs &a, int v, hipStream_t stream) {
 }  // namespace
 
 void gemm_force_variant(int v) { g_forced_variant = v; }
+size_t gemm_sk_workspace_floats() { return (size_t)2 * SK_MAX_G * 256 * 256; }
+int gemm_sk_counters() { return 2 * SK_MAX_G; }
 
 bool gemm_round_split(const GemmArgs &a, int epilogue, int dh, GemmArgs *head, GemmArgs *tail) {
   if (epilogue != EPI_SWIGLU || g_forced_variant != V_AUTO || a.k_splits > 1) return false;
@@ -870,7 +1066,8 @@ int gemm_splitk_choice(int M, int N, int K, int epilogue, int n_cu) {
 
 int gemm_ss_parts(const GemmArgs &a, int epilogue, int dh) {
   if (a.k_splits > 1) return 1;  // the split-K reduction leaves whole row sums
-  const int v = a.tile_variant ? a.tile_variant : choose_variant(a.M, a.N, epilogue, dh, a.n_cu);
+  const int v = a.tile_variant ? a.tile_variant
+                               : choose_variant(a.M, a.N, epilogue, dh, a.n_cu, a.sk_ws && a.sk_cnt && !a.n_count ? a.K : 0);
   // partial row sums: one per (column tile, wavefront column)
   return v == V_SMALL ? ((a.N + 127) / 128) * 2 : ((a.N + 255) / 256) * 4;
 }
@@ -947,7 +1144,8 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stre
   if (a.n_count && epilogue != EPI_SWIGLU && epilogue != EPI_PLAIN) return hipErrorInvalidValue;
   const int n_cols = a.n_count ? a.n_count : a.N;
   const int v = a.tile_variant ? a.tile_variant
-                               : choose_variant(a.M, (epilogue == EPI_SWIGLU) ? 2 * n_cols : n_cols, epilogue, dh, a.n_cu);
+                               : choose_variant(a.M, (epilogue == EPI_SWIGLU) ? 2 * n_cols : n_cols, epilogue, dh, a.n_cu,
+                                                a.sk_ws && a.sk_cnt && !a.n_count ? a.K : 0);
   switch (epilogue) {
     case EPI_PLAIN: return launch_variant<EPI_PLAIN, 2, 4>(a, v, stream);
     case EPI_RESID: return launch_variant<EPI_RESID, 2, 4>(a, v, stream);
@@ -955,11 +1153,13 @@ hipError_t launch_gemm(const GemmArgs &a, int epilogue, int dh, hipStream_t stre
     case EPI_SWIGLU: return launch_variant<EPI_SWIGLU, 2, 4>(a, v, stream);
     case EPI_QKV:
       if (dh == 128)
-        return v == V_BIG ? launch_one<256, 256, 4, 2, EPI_QKV, 128>(a, stream)
-                          : launch_one<128, 128, 4, 1, EPI_QKV, 128>(a, stream);
+        return v == V_SHARED ? launch_sk<256, 256, 4, 2, EPI_QKV, 128>(a, stream)
+               : v == V_BIG  ? launch_one<256, 256, 4, 2, EPI_QKV, 128>(a, stream)
+                             : launch_one<128, 128, 4, 1, EPI_QKV, 128>(a, stream);
       if (dh == 64)
-        return v == V_BIG ? launch_one<256, 256, 2, 4, EPI_QKV, 64>(a, stream)
-                          : launch_one<128, 128, 2, 2, EPI_QKV, 64>(a, stream);
+        return v == V_SHARED ? launch_sk<256, 256, 2, 4, EPI_QKV, 64>(a, stream)
+               : v == V_BIG  ? launch_one<256, 256, 2, 4, EPI_QKV, 64>(a, stream)
+                             : launch_one<128, 128, 2, 2, EPI_QKV, 64>(a, stream);
       return hipErrorInvalidValue;
     default:
       return hipErrorInvalidValue;

@@ -45,6 +45,11 @@ struct GemmArgs {
   // The caller takes k_splits from gemm_splitk_choice and provides the workspace.
   int k_splits;
   float *splitk_ws;
+  // Shared tiles (tile_variant 6, see gemm_sk_kernel): room for the partial tiles, at least
+  // gemm_sk_workspace_floats() floats, and gemm_sk_counters() counters that are zero between launches.
+  // Launches that use them must not overlap in time.
+  float *sk_ws;
+  unsigned *sk_cnt;
   // SWIGLU: B holds F gate rows then F up rows; N = F
   // QKV extras
   int n_q_heads, n_kv_heads;
@@ -85,6 +90,8 @@ bool gemm_round_split(const GemmArgs &a, int epilogue, int dh, GemmArgs *head, G
 // Number of k-ranges worth using for this problem (1 = no split): only when the tiles would
 // leave most of the chip idle and every range keeps at least eight k-tiles.
 int gemm_splitk_choice(int M, int N, int K, int epilogue, int n_cu);
-void gemm_force_variant(int v);  // 0 = choose by shape, 1 = 256x256, 2 = 160x256, 3 = 128x128 tiles (tuning)
+void gemm_force_variant(int v);  // 0 = choose by shape, 1 = 256x256, 2 = 160x256, 3 = 128x128 tiles, 6 = shared 256x256 tiles (tuning)
+size_t gemm_sk_workspace_floats();
+int gemm_sk_counters();
 
 }  // namespace bs

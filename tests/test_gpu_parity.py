@@ -73,6 +73,55 @@ def test_gemm_nt(lib, m, n, k):
     assert maxrel < 4e-3
 
 
+@pytest.mark.parametrize("m,n,k", [(2600, 4104, 520),    # 187 tiles for 256 workgroups: every tile cut along K
+                                   (4096, 4096, 192),    # 256 tiles: one whole round, nothing shared
+                                   (4100, 5000, 328),    # 340 tiles: all shared, more than a tile's worth each
+                                   (5000, 7000, 200),    # 560 tiles: a round of whole tiles, then 304 shared ones
+                                   (300, 704, 8200),     # 6 tiles, 129 k-tiles each: dozens of parts per tile
+                                   (256, 256, 64), (1, 8, 8)])
+def test_gemm_nt_on_shared_tiles(lib, m, n, k):
+    # tile shape 6: persistent workgroups, the tiles of the last rounds cut along K; whoever arrives
+    # last at a tile adds its parts up in a fixed order, so two runs agree bit for bit
+    import torch
+    rng = np.random.default_rng(m + n + k)
+    a = W.round_to_bf16(rng.standard_normal((m, k), dtype=np.float32))
+    b = W.round_to_bf16(rng.standard_normal((n, k), dtype=np.float32) * 0.05)
+    layer = lib.Layer(W.TINY, device=0)
+    layer.set_gemm_tiles(6)
+    ta = torch.from_numpy(a).cuda().to(torch.bfloat16)
+    tb = torch.from_numpy(b).cuda().to(torch.bfloat16)
+    c1 = layer.gemm_nt(ta, tb)
+    c2 = layer.gemm_nt(ta, tb)       # also: the arrival counters were left at zero
+    torch.cuda.synchronize()
+    assert torch.equal(c1, c2)
+    c = to_np(c1)
+    ref = a.astype(np.float64) @ b.astype(np.float64).T
+    maxrel, mae = errs(c, ref)
+    assert np.max(np.abs(c - ref) / (np.abs(ref) + 1e-3 * np.max(np.abs(ref)))) < 6e-3
+    assert maxrel < 4e-3
+
+
+@pytest.mark.parametrize("shape", [W.LayerShape(1024, 8, 2, 128, 2056), W.LayerShape(512, 8, 2, 64, 33024)])
+def test_layer_step_on_shared_tiles(lib, shape):
+    # every GEMM of the step, with its fused epilogue, on shared tiles (ragged in every dimension)
+    import torch
+    batch = W.assemble_batch(16, [(700, 700, -1), (391, 500, -1)] + [(1, 200 + 7 * i, -1) for i in range(50)], 2,
+                             [], np.random.default_rng(5))
+    tens = W.make_tensors(shape, batch, 5, gains="random")
+    ref = O.layer_step(shape, tens, batch)
+    diag = O.layer_step(shape, tens, batch, storage="bf16")
+    layer = lib.Layer(shape, device=0)
+    layer.set_gemm_tiles(6)
+    dev = layer.upload(tens, batch)
+    y = layer.blend_step(dev, batch)
+    torch.cuda.synchronize()
+    check(to_np(y), ref["y"], diag["y"], "shared tiles")
+    k, v = layer.unpack_pool(dev.kv_pool, dev.n_pages)
+    k, v = to_np(k), to_np(v)
+    check(k[ref["dest"][:, 0], ref["dest"][:, 1]], ref["k_new"], diag["k_new"], "appended keys")
+    check(v[ref["dest"][:, 0], ref["dest"][:, 1]], ref["v_new"], diag["v_new"], "appended values")
+
+
 def attention_reference(shape, batch, q, k_pool, v_pool, storage="exact"):
     out = np.zeros((batch.n_rows, shape.n_q_heads * shape.head_dim))
     for s in range(batch.n_seq):

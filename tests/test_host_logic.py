@@ -144,6 +144,7 @@ def test_tuning_knobs_reject_values_outside_their_range(host_layer):
     for ok in (2, 32, 64):
         assert host_layer.lib.bs_set_chunk_pages(host_layer.h, ok) == 0
     assert host_layer.lib.bs_set_gemm_tiles(host_layer.h, 4) == -1
+    assert host_layer.lib.bs_set_gemm_tiles(host_layer.h, 7) == -1
     assert host_layer.lib.bs_set_gemm_tiles(host_layer.h, 0) == 0
     good = host_layer.get_overlap()
     for bad in (dict(head_cus_min=4), dict(head_cus_min=200), dict(head_cus_min=-8), dict(tail_workgroups=257),
