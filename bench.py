@@ -302,7 +302,7 @@ def main():
     rows_dn = Tp if (co and layer.get_overlap()["carry_down"]) else T
     kv_bytes = work["kv_tokens_once"] * shape.kv_bytes_per_token
 
-    def mfma(name, cls, flops, traffic_file=None, extra=None):
+    def mfma(name, cls, flops, traffic_file=None, extra=None, operand_bytes=0.0):
         ms = kernels[cls]["ms"]
         if ms <= 0:
             return None
@@ -311,7 +311,17 @@ def main():
                                             if traffic_file else None)}
         r["frac"] = r["achieved"] / r["peak"]
         if extra:
+            # A launch that carries decode attention does two kinds of algorithmic work at once: the GEMM's
+            # flops on the tile CUs and the KV bytes (plus the GEMM's own operands, each once) on the memory
+            # system.  Its roofline time is the larger of the two, and that side names the bound.
             r.update(extra)
+            nbytes = extra["carried_kv_bytes"] + operand_bytes
+            r["mfma_frac"] = r["frac"]
+            r["hbm_frac"] = nbytes / (ms * 1e-3) / PEAK_HBM
+            r["algorithmic_flops"], r["algorithmic_bytes"] = flops, nbytes
+            if r["hbm_frac"] > r["mfma_frac"]:
+                r.update({"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                          "frac": r["hbm_frac"]})
         return r
 
     def hbm(name, cls, nbytes, traffic_file=None):
@@ -330,13 +340,16 @@ def main():
     tag = " of the prefill rows, carrying decode attention" if co else ""
     per_kernel = [
         mfma("gemm_qkv (RMSNorm factor, RoPE, KV append)", "gemm_qkv", 2.0 * T * d * shape.n_qkv),
-        mfma("gemm_o (residual, norm statistics)" + tag, "gemm_o", 2.0 * rows_g * hd * d, None, riding(0) if co else None),
+        # (operand bytes of a carrying launch: activations in, weights, result out, each once; x1 leaves the
+        # output projection in fp32 and as bf16(x1 * gain), and the down projection reads it back in fp32)
+        mfma("gemm_o (residual, norm statistics)" + tag, "gemm_o", 2.0 * rows_g * hd * d, None, riding(0) if co else None,
+             2.0 * rows_g * hd + 2.0 * hd * d + rows_g * d * (2.0 + 4.0 + 2.0)),
         mfma("gemm_gate_up (SwiGLU epilogue)" + tag, "gemm_gate_up", 2.0 * rows_g * d * 2 * f,
              ("blended_8b_coscheduled_gate_up_hbm_traffic.txt" if co else "blended_8b_gemm_gate_up_hbm_traffic.txt")
              if args.workload == "blended_8b" else None,
-             riding(1) if co else None),
+             riding(1) if co else None, 2.0 * rows_g * d + 2.0 * d * 2 * f + 2.0 * rows_g * f),
         mfma("gemm_down (residual)" + (tag if rows_dn != T else ""), "gemm_down", 2.0 * rows_dn * f * d, None,
-             riding(2) if (co and rows_dn != T) else None),
+             riding(2) if (co and rows_dn != T) else None, 2.0 * rows_dn * f + 2.0 * f * d + rows_dn * d * (4.0 + 2.0)),
         mfma("output projection, gate/up and down of the decode rows", "gemm_decode_rows",
              2.0 * (T - Tp) * (hd * d + 2 * d * f) + 2.0 * (T - rows_dn) * f * d) if co else None,
     ]
@@ -354,7 +367,13 @@ def main():
     # the dominant kernel = the longest launch of the step; the bound-side kernel = the longest one of the
     # kind that bounds the whole step (a GEMM where the step is MFMA-bound, attention where it is HBM-bound)
     roofline = max(per_kernel, key=lambda r: r["ms"])
-    side = [r for r in per_kernel if r["bound"] == bound]
+    def as_mfma(r):   # a carrying launch seen from its GEMM side
+        if r["bound"] == "mfma" or "mfma_frac" not in r:
+            return r
+        return dict(r, bound="mfma", achieved=r["algorithmic_flops"] / (r["ms"] * 1e-3) / 1e12, peak=PEAK_MFMA_BF16 / 1e12,
+                    unit="TFLOP/s", frac=r["mfma_frac"])
+    side = [as_mfma(r) if bound == "mfma" else r for r in per_kernel]
+    side = [r for r in side if r["bound"] == bound]
     roofline_bound_side = max(side, key=lambda r: r["ms"]) if side else None
 
     out = {
