@@ -6,7 +6,7 @@ QKV GEMM with RoPE and KV append, prefill and prefix-aware decode attention,
 output projection, SwiGLU FFN and both residuals, over one seeded synthetic batch
 already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--flags 0|1]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--flags 0|1|3]
 """
 import argparse
 import json
@@ -160,7 +160,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="blended_8b")
-    ap.add_argument("--flags", type=int, default=-1, help="0 serial, 1 overlap, -1 pick the faster in warm-up")
+    ap.add_argument("--flags", type=int, default=-1, help="0 serial, 1 overlap, 3 overlap with the layers of a --layers call pipelined, -1 pick the faster of 0 and 1 in warm-up")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk-pages", type=int, default=0)

@@ -119,6 +119,12 @@ typedef struct bs_ctx bs_ctx;
                                and FFN follow.  Still one stream and no events.  Steps without prefill
                                rows or without such units run the serial schedule.  Results differ from
                                the serial schedule by GEMM tile shapes only (same arithmetic per element). */
+#define BS_FLAG_PIPELINE 2u /* bs_blend_layers with BS_FLAG_OVERLAP: the two parts of the batch run one stage
+                               apart across the layer boundary (Section 2.2, nano-batches; Appendix A.2):
+                               the decode rows finish layer l and enter layer l+1 (norm, QKV, KV append)
+                               before the prefill rows' down projection of layer l is launched, and that
+                               launch carries the first part of their attention of layer l+1.  Ignored by
+                               bs_blend_step and wherever BS_FLAG_OVERLAP would run the serial schedule. */
 
 /* Create a context on `device`; allocates the RoPE table and workspace that
  * grows on demand.  *out is NULL on failure; bs_last_error(NULL) then returns

@@ -23,7 +23,7 @@ _i32p = C.POINTER(C.c_int32)
 
 K_NAMES = ["prep", "gemm_qkv", "attn_prefill", "attn_decode", "attn_merge", "gemm_o", "gemm_gate_up", "gemm_down",
            "attn_queue_rest", "gemm_decode_rows"]
-FLAG_SERIAL, FLAG_OVERLAP = 0, 1
+FLAG_SERIAL, FLAG_OVERLAP, FLAG_PIPELINE = 0, 1, 2
 
 
 class LayerCfg(C.Structure):
@@ -556,6 +556,7 @@ class _Api:
     BlendStepError = BlendStepError
     FLAG_SERIAL = FLAG_SERIAL
     FLAG_OVERLAP = FLAG_OVERLAP
+    FLAG_PIPELINE = FLAG_PIPELINE
     K_NAMES = K_NAMES
     marshal_batch = staticmethod(marshal_batch)
     raw = staticmethod(raw)

@@ -668,19 +668,24 @@ double est_gemm_s(int M, int b_rows, int K, int n_cu) {
 
 // What the co-scheduled schedule would do with a planned step, and what it is expected to gain.
 struct CoPlan {
-  GemmArgs ga[3];
+  GemmArgs ga[3];   // output projection, gate/up, down of the prefill rows
+  int order[3] = {0, 1, 2};  // the carrying launches in the order of their launch, as indices into ga
   int n_carriers = 0, head[3] = {0, 0, 0}, margin[3] = {0, 0, 0}, n_first = 0;
   int64_t first_bytes = 0;
   double gain_s = 0.0;  // estimated time of the serial schedule minus that of this one
 };
 
-void plan_coscheduled(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, uint16_t *y, CoPlan &cp) {
+// `down_first`: the schedule of a layer after the first in a pipelined chain of layers, where the down
+// projection of the previous layer's prefill rows is the first launch that carries this layer's queue.
+void plan_coscheduled(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, uint16_t *y, CoPlan &cp,
+                      bool down_first = false) {
   const bs_layer_cfg &g = c->cfg;
   const bs_overlap_knobs &k = c->ov;
   const int T = p.n_rows, Tp = p.n_prefill_rows;
-  const bool carry_down = k.carry_down != 0;
+  const bool carry_down = k.carry_down != 0 || down_first;
   const int n_carriers = carry_down ? 3 : 2;
   cp.n_carriers = n_carriers;
+  if (down_first) { cp.order[0] = 2; cp.order[1] = 0; cp.order[2] = 1; }
   GemmArgs (&ga)[3] = cp.ga;
   int (&head)[3] = cp.head;
   int (&margin)[3] = cp.margin;
@@ -702,7 +707,8 @@ void plan_coscheduled(bs_ctx *c, const Plan &p, const bs_weights *w, const uint1
   const double cu_stream = 36e9, chip_stream = 5.3e12;
   double ride_bytes = 0;
   double left = k.ride_percent >= 0 ? narrow_bytes * (k.ride_percent / 100.0) : (double)narrow_bytes;
-  for (int l = 0; l < n_carriers; ++l) {
+  for (int i = 0; i < n_carriers; ++i) {
+    const int l = cp.order[i];
     double best = 1e300, best_hidden = 0, best_t = 0;
     for (int v = 1; v <= 2; ++v) {  // 256x256, 160x256
       ga[l].tile_variant = v;
@@ -989,22 +995,24 @@ int bs_resolve_rows(bs_ctx *c, const bs_batch *b, int32_t *page_out, int32_t *sl
 
 namespace {
 
-// every kernel of one layer for the planned batch: x -> y, appending to `pool`
-int run_layer(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, uint16_t *y, uint16_t *pool, hipStream_t st,
-              uint32_t flags) {
+// First norm and fused QKV projection (RoPE, KV append into `pool`) of rows [r0, r1) of x.
+// `clear_sync`: the prep kernel also clears the counters of the co-scheduled launches.
+int run_prep_qkv(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, uint16_t *pool, int r0, int r1,
+                 bool clear_sync, hipStream_t st) {
   int rc;
   const bs_layer_cfg &g = c->cfg;
-  const int T = p.n_rows, d = g.d_model;
-  // (the prep kernel also clears the counters of the co-scheduled launches)
-  SPAN(c, BS_K_PREP, st, HIP_TRY(c, launch_norm_prep(x, (const uint16_t *)w->g_attn, c->xg, c->rstd1, T, d, g.rms_eps, c->sync_words, 16, st)));
+  const int d = g.d_model, rows = r1 - r0, hd = g.n_q_heads * g.head_dim;
+  if (rows <= 0) return BS_OK;
+  SPAN(c, BS_K_PREP, st, HIP_TRY(c, launch_norm_prep(x + (size_t)r0 * d, (const uint16_t *)w->g_attn, c->xg + (size_t)r0 * d,
+                                                     c->rstd1 + r0, rows, d, g.rms_eps, clear_sync ? c->sync_words : nullptr, 16, st)));
   GemmArgs q{};
-  q.A = c->xg; q.lda = d; q.B = (const uint16_t *)w->w_qkv; q.ldb = d;
-  q.M = T; q.N = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim; q.K = d;
-  q.rstd = c->rstd1;
+  q.A = c->xg + (size_t)r0 * d; q.lda = d; q.B = (const uint16_t *)w->w_qkv; q.ldb = d;
+  q.M = rows; q.N = (g.n_q_heads + 2 * g.n_kv_heads) * g.head_dim; q.K = d;
+  q.rstd = c->rstd1 + r0;
   q.n_q_heads = g.n_q_heads; q.n_kv_heads = g.n_kv_heads;
   q.rope_cos = c->rope_cos; q.rope_sin = c->rope_sin;
-  q.row_pos = c->d_blob + p.off_row_pos; q.row_page = c->d_blob + p.off_row_page; q.row_slot = c->d_blob + p.off_row_slot;
-  q.q_out = c->qbuf; q.kv_pool = pool;
+  q.row_pos = c->d_blob + p.off_row_pos + r0; q.row_page = c->d_blob + p.off_row_page + r0; q.row_slot = c->d_blob + p.off_row_slot + r0;
+  q.q_out = c->qbuf + (size_t)r0 * hd; q.kv_pool = pool;
   q.sk_ws = c->sk_ws; q.sk_cnt = c->sk_cnt;
   q.k_splits = gemm_splitk_choice(q.M, q.N, q.K, EPI_QKV, 0);
   if (q.k_splits > 1) {
@@ -1012,6 +1020,15 @@ int run_layer(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, 
     q.splitk_ws = c->splitk_ws;
   }
   SPAN(c, BS_K_GEMM_QKV, st, HIP_TRY(c, launch_gemm(q, EPI_QKV, g.head_dim, st)));
+  return BS_OK;
+}
+
+// every kernel of one layer for the planned batch: x -> y, appending to `pool`
+int run_layer(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, uint16_t *y, uint16_t *pool, hipStream_t st,
+              uint32_t flags) {
+  int rc;
+  const int T = p.n_rows;
+  if ((rc = run_prep_qkv(c, p, w, x, pool, 0, T, true, st))) return rc;
 
   // co-scheduling pays where there are GEMM rows that do not wait for decode attention (the
   // prefill rows) and 16-row decode units to run beside them
@@ -1024,6 +1041,89 @@ int run_layer(bs_ctx *c, const Plan &p, const bs_weights *w, const uint16_t *x, 
   if ((rc = run_attention(c, p, c->qbuf, c->attn, pool, st))) return rc;
   if ((rc = run_o_gate_up(c, w, x, 0, T, st))) return rc;
   return run_down(c, w, y, 0, T, st);
+}
+
+// Layers back to back with the two parts of the batch one stage apart (BS_FLAG_PIPELINE; Section 2.2,
+// nano-batches: operators of different parts of a batch overlap across the layer boundary;
+// Appendix A.2).  The decode rows run ahead of the prefill rows: they finish layer l (their output
+// projection, FFN) and enter layer l+1 (norm, QKV, KV append) BEFORE the prefill rows' down projection
+// of layer l is launched, so that launch, whose tiles leave CUs idle, already carries the decode
+// attention of layer l+1 with its whole queue still to draw from; the prefill rows' output projection
+// and gate/up of layer l+1 carry the rest, as in a single co-scheduled layer.  The two parts touch
+// disjoint rows of every workspace buffer, and a part is never more than one layer ahead, so the two
+// alternating hidden-state buffers suffice.  Same kernels, same arithmetic per row as run_layer.
+int run_layers_pipelined(bs_ctx *c, const Plan &p, int n_layers, const bs_weights *w, const uint16_t *x, uint16_t *y,
+                         void *const *pools, hipStream_t st, CoPlan &first, CoPlan &later) {
+  int rc;
+  const bs_layer_cfg &g = c->cfg;
+  const bs_overlap_knobs &k = c->ov;
+  const int T = p.n_rows, Tp = p.n_prefill_rows, d = g.d_model;
+  const int epi[3] = {EPI_RESID_NORM, EPI_SWIGLU, EPI_RESID};
+  const int kclass[3] = {BS_K_GEMM_O, BS_K_GEMM_GATE_UP, BS_K_GEMM_DOWN};
+  for (long &n : c->trace_wgs) n = 0;
+
+  // launch number `slot` of a layer's carrying launches: GEMM `gi` of `cp` with arguments `a`
+  auto carry = [&](const CoPlan &cp, int slot, int gi, GemmArgs a, const DecodeArgs &dargs, bool last) -> int {
+    GemmRide ride{};
+    ride.q.d = dargs;
+    ride.q.first_item = p.n_wide + cp.n_first;
+    ride.q.n_units = (p.n_narrow - cp.n_first) * g.n_kv_heads;
+    ride.q.waves = k.attention_waves;
+    ride.head = cp.head[gi];
+    ride.tail = last ? std::max(k.tail_workgroups, c->n_cu - ride.head) : k.tail_workgroups;
+    ride.close_margin = last ? -1 : cp.margin[gi];  // the last carrying launch of a layer drains the queue
+    ride.q.ticket = c->sync_words + slot;
+    ride.ticket_next = c->sync_words + slot + 1;
+    ride.done = c->sync_words + 4 + slot;
+    ride.closed_at = c->sync_words + 8 + slot;
+    a.tile_variant = cp.ga[gi].tile_variant;
+    if (gi == 0) {
+      const int parts = gemm_ss_parts(a, EPI_RESID_NORM, g.head_dim);
+      SPAN(c, kclass[0], st, {
+        HIP_TRY(c, launch_gemm_with_attention(a, epi[0], g.head_dim, ride, st));
+        HIP_TRY(c, launch_rstd_finalize(c->ss2, parts, c->cap_rows, c->rstd2, Tp, d, g.rms_eps, st));
+      });
+    } else {
+      SPAN(c, kclass[gi], st, HIP_TRY(c, launch_gemm_with_attention(a, epi[gi], g.head_dim, ride, st)));
+    }
+    return BS_OK;
+  };
+
+  const uint16_t *in = x;
+  if ((rc = run_prep_qkv(c, p, &w[0], in, (uint16_t *)pools[0], 0, T, true, st))) return rc;
+  for (int l = 0; l < n_layers; ++l) {
+    const CoPlan &cp = l == 0 ? first : later;
+    uint16_t *out = (l == n_layers - 1) ? y : c->hid[l & 1];
+    uint16_t *pool = (uint16_t *)pools[l];
+    const DecodeArgs dargs = decode_args(c, p, c->qbuf, pool);
+    c->ov_first_bytes = cp.first_bytes;
+    c->ov_first_items = cp.n_first;
+    // attention of the prefill rows, of the wide decode items and of the 16-row units that do not ride
+    if ((p.n_wide > 0 || cp.n_first > 0) && p.n_pf_work > 0 && blended_attn_possible(attn_shape(c))) {
+      const PrefillArgs pf = prefill_args(c, p, c->qbuf, c->attn, pool);
+      SPAN(c, BS_K_ATTN_DECODE, st, HIP_TRY(c, launch_blended_attn(dargs, p.n_wide, cp.n_first, pf, st)));
+    } else {
+      if ((rc = run_prefill_attn(c, p, c->qbuf, c->attn, pool, st))) return rc;
+      if (p.n_wide > 0 || cp.n_first > 0)
+        SPAN(c, BS_K_ATTN_DECODE, st, HIP_TRY(c, launch_decode_attn(dargs, p.n_wide, cp.n_first, st)));
+    }
+    // (in a later layer launch 0 was the previous layer's down projection)
+    const int s0 = l == 0 ? 0 : 1;
+    if ((rc = carry(cp, s0, 0, o_proj_args(c, &w[l], in, 0, Tp), dargs, false))) return rc;
+    if ((rc = carry(cp, s0 + 1, 1, gate_up_args(c, &w[l], 0, Tp), dargs, true))) return rc;
+    if ((rc = run_decode_merge(c, p, c->attn, st))) return rc;
+    if ((rc = run_o_gate_up(c, &w[l], in, Tp, T, st, BS_K_GEMM_DECODE_ROWS, BS_K_GEMM_DECODE_ROWS))) return rc;
+    if (l == n_layers - 1) return run_down(c, &w[l], out, 0, T, st);
+    // the decode rows leave this layer and enter the next ...
+    if ((rc = run_down(c, &w[l], out, Tp, T, st, BS_K_GEMM_DECODE_ROWS))) return rc;
+    if ((rc = run_prep_qkv(c, p, &w[l + 1], out, (uint16_t *)pools[l + 1], Tp, T, true, st))) return rc;
+    // ... whose attention starts beside the prefill rows' down projection of this one
+    const DecodeArgs next = decode_args(c, p, c->qbuf, (uint16_t *)pools[l + 1]);
+    if ((rc = carry(later, 0, 2, down_args(c, &w[l], out, 0, Tp), next, false))) return rc;
+    if ((rc = run_prep_qkv(c, p, &w[l + 1], out, (uint16_t *)pools[l + 1], 0, Tp, false, st))) return rc;
+    in = out;
+  }
+  return BS_OK;
 }
 
 bool weights_ok(const bs_weights *w) {
@@ -1079,6 +1179,14 @@ int bs_blend_layers(bs_ctx *c, int32_t n_layers, const bs_weights *w, const bs_b
   // one descriptor, validated, planned and uploaded once; activations alternate between two
   // workspace buffers so that neither x nor y is touched before / after its own layer
   const uint16_t *in = (const uint16_t *)x_;
+  if ((flags & BS_FLAG_OVERLAP) && (flags & BS_FLAG_PIPELINE) && n_layers > 1 && p.n_narrow > 0 &&
+      p.n_prefill_rows >= c->ov.min_prefill_rows && p.n_prefill_rows < p.n_rows) {
+    CoPlan first, later;
+    plan_coscheduled(c, p, &w[0], in, (uint16_t *)y_, first);
+    plan_coscheduled(c, p, &w[0], in, (uint16_t *)y_, later, true);
+    if (c->ov.always || first.gain_s > 0.0)
+      return run_layers_pipelined(c, p, n_layers, w, in, (uint16_t *)y_, pools, st, first, later);
+  }
   for (int l = 0; l < n_layers; ++l) {
     uint16_t *out = (l == n_layers - 1) ? (uint16_t *)y_ : c->hid[l & 1];
     if ((rc = run_layer(c, p, &w[l], in, out, (uint16_t *)pools[l], st, flags))) return rc;

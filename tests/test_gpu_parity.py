@@ -386,6 +386,55 @@ def test_layers_back_to_back(lib):
     assert torch.equal(y0, y1)
 
 
+@pytest.mark.parametrize("shape,n_layers", [(W.TINY, 4), (W.LayerShape(512, 8, 2, 128, 1288), 3)])
+@pytest.mark.parametrize("knobs", [
+    dict(head_cus_min=8, tail_workgroups=16, close_margin=2, ride_percent=100),
+    dict(head_cus_min=48, tail_workgroups=208, close_margin=8, ride_percent=-1, attention_waves=4),
+    dict(head_cus_min=0, tail_workgroups=24, close_margin=0, ride_percent=60),
+])
+def test_pipelined_layers_match_the_oracle_chain(lib, shape, n_layers, knobs):
+    # BS_FLAG_PIPELINE: the decode rows run one stage ahead of the prefill rows across the layer
+    # boundary, and the prefill rows' down projection of layer l carries decode attention of
+    # layer l+1.  Every layer's appended keys and values and the final output against the oracle
+    # chain (activations between layers are bf16, so the chain rounds them too).
+    import dataclasses
+    import torch
+    rng = np.random.default_rng(31)
+    seqs = [(130, 130, -1), (70, 200, -1), (45, 45, -1)] + [(1, 40 + 37 * i, -1) for i in range(40)]
+    batch = W.assemble_batch(16, seqs, 3, [], rng)
+    tens = [W.make_tensors(shape, batch, 40 + l, gains="random") for l in range(n_layers)]
+    layer = lib.Layer(shape, device=0)
+    layer.set_overlap(always=1, min_prefill_rows=1, **knobs)
+    devs = [layer.upload(t, batch) for t in tens]
+    layer.profile(True)
+    y = layer.blend_layers(devs, batch, flags=lib.FLAG_OVERLAP | lib.FLAG_PIPELINE)
+    torch.cuda.synchronize()
+    prof = layer.profile_read()
+    # the path was taken: the decode rows' GEMMs ran apart in every layer, and n_layers - 1 down
+    # projections of the prefill rows were launches of their own
+    assert prof["gemm_decode_rows"][1] > 0 and prof["gemm_down"][1] == n_layers
+    x = xd = tens[0].x
+    for l, t in enumerate(tens):
+        ref = O.layer_step(shape, dataclasses.replace(t, x=x), batch)
+        diag = O.layer_step(shape, dataclasses.replace(t, x=xd), batch, storage="bf16")
+        x = W.round_to_bf16(ref["y"].astype(np.float32))
+        xd = diag["y"].astype(np.float32)
+        k, v = layer.unpack_pool(devs[l].kv_pool, devs[l].n_pages)
+        k, v = to_np(k), to_np(v)
+        assert errs(k[ref["dest"][:, 0], ref["dest"][:, 1]], ref["k_new"])[0] <= MAXREL, "layer %d keys" % l
+        assert errs(v[ref["dest"][:, 0], ref["dest"][:, 1]], ref["v_new"])[0] <= MAXREL, "layer %d values" % l
+        k0 = W.bf16_bits_to_f32(t.k_pool).astype(np.float64)
+        written = np.zeros(k0.shape[:2], dtype=bool)
+        written[ref["dest"][:, 0], ref["dest"][:, 1]] = True
+        assert np.array_equal(k[~written], k0[~written]), "layer %d: a slot outside the append destinations changed" % l
+    check(to_np(y), ref["y"], diag["y"], "%d pipelined layers" % n_layers)
+    # and against the same layers co-scheduled one after the other (different tile shapes at most)
+    devs2 = [layer.upload(t, batch) for t in tens]
+    y2 = layer.blend_layers(devs2, batch, flags=lib.FLAG_OVERLAP)
+    torch.cuda.synchronize()
+    assert errs(to_np(y), to_np(y2))[0] <= MAXREL
+
+
 def run_coscheduled(lib, shape, batch, tens, knobs, chunk_pages=0):
     import torch
     layer = lib.Layer(shape, device=0)
