@@ -15,7 +15,7 @@ import pytest
 
 from oracle import layer as O
 from paper_2411_16102_amd import workloads as W
-from parity_rule import check
+from parity_rule import MAXREL, check, errs
 
 pytestmark = pytest.mark.gpu
 
@@ -76,3 +76,40 @@ def test_full_size_config(lib, name):
         check(kn, ref["k_new"][have_kv], diag["k_new"][have_kv], "%s flags=%d appended keys" % (name, flags))
         check(vn, ref["v_new"][have_kv], diag["v_new"][have_kv], "%s flags=%d appended values" % (name, flags))
         del k1, v1, k0, v0, pool0, dev
+
+
+def test_full_size_two_pipelined_layers(lib):
+    """blended_8b through two layers with the parts of the batch pipelined across the layer boundary
+    (the down projection of the first layer's prefill rows carries decode attention of the second): the
+    second layer's output, every element, and its KV append against the oracle chain."""
+    import dataclasses
+    import torch
+    shape, make = W.CONFIGS["blended_8b"]
+    batch = make(seed=0)
+    tens = [W.make_tensors(shape, batch, l) for l in range(2)]
+    layer = lib.Layer(shape, device=0)
+    layer.set_overlap(always=1)
+    devs = [layer.upload(t, batch) for t in tens]
+    layer.profile(True)
+    y = layer.blend_layers(devs, batch, flags=lib.FLAG_OVERLAP | lib.FLAG_PIPELINE)
+    torch.cuda.synchronize()
+    prof = layer.profile_read()
+    assert prof["gemm_decode_rows"][1] > 0 and prof["gemm_down"][1] == 2    # the pipelined path ran
+    got = y.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    print("oracle: layer 1 of 2", flush=True)
+    ref1 = O.layer_step(shape, tens[0], batch)
+    diag1 = O.layer_step(shape, tens[0], batch, storage="bf16")
+    x2 = W.round_to_bf16(ref1["y"].astype(np.float32))     # the activations between layers are bf16
+    print("oracle: layer 2 of 2", flush=True)
+    ref2 = O.layer_step(shape, dataclasses.replace(tens[1], x=x2), batch)
+    # the storage error of two layers: the diagnostic chain carries its own first-layer output
+    diag2 = O.layer_step(shape, dataclasses.replace(tens[1], x=diag1["y"].astype(np.float32)), batch, storage="bf16")
+    check(got, ref2["y"], diag2["y"], "two pipelined layers, y")
+    for l, ref in ((0, ref1), (1, ref2)):
+        k1, v1 = layer.unpack_pool(devs[l].kv_pool, devs[l].n_pages)
+        dest = torch.from_numpy(ref["dest"].astype(np.int64)).cuda()
+        kn = k1[dest[:, 0], dest[:, 1]].float().cpu().numpy().astype(np.float64)
+        vn = v1[dest[:, 0], dest[:, 1]].float().cpu().numpy().astype(np.float64)
+        assert errs(kn, ref["k_new"])[0] <= MAXREL and errs(vn, ref["v_new"])[0] <= MAXREL, "layer %d KV append" % l
+        del k1, v1
