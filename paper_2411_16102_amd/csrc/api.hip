@@ -611,11 +611,14 @@ int run_o_gate_up(bs_ctx *c, const bs_weights *w, const uint16_t *x, int r0, int
     int rc = ensure_splitk(c, (size_t)o.k_splits * rows * d);
     if (rc) return rc;
     o.splitk_ws = c->splitk_ws;
+    o.rstd_out = c->rstd2 + r0;  // the reduction closes the second norm's statistics itself
+    o.rstd_eps = g.rms_eps;
   }
   const int parts = gemm_ss_parts(o, EPI_RESID_NORM, g.head_dim);
   SPAN(c, k_o, st, {
     HIP_TRY(c, launch_gemm(o, EPI_RESID_NORM, g.head_dim, st));
-    HIP_TRY(c, launch_rstd_finalize(c->ss2 + r0, parts, c->cap_rows, c->rstd2 + r0, rows, d, g.rms_eps, st));
+    if (o.k_splits <= 1)
+      HIP_TRY(c, launch_rstd_finalize(c->ss2 + r0, parts, c->cap_rows, c->rstd2 + r0, rows, d, g.rms_eps, st));
   });
   const GemmArgs u = gate_up_args(c, w, r0, r1);
   GemmArgs head, tail;

@@ -828,7 +828,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_resid_norm_kernel(const Gem
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
   __syncthreads();
-  if (threadIdx.x == 0) a.ss_out[m] = (part[0] + part[1]) + (part[2] + part[3]);
+  if (threadIdx.x == 0) {
+    const float row = (part[0] + part[1]) + (part[2] + part[3]);
+    a.ss_out[m] = row;
+    if (a.rstd_out) a.rstd_out[m] = rsqrtf(row / (float)a.N + a.rstd_eps);
+  }
 }
 
 // QKV: scale by the row's RMSNorm factor, rotate the q and k heads (pairs i, i + dh/2), store q

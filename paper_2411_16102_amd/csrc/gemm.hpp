@@ -39,6 +39,8 @@ struct GemmArgs {
   float *C32;            // [M, ldc] x1 in fp32
   uint16_t *C_gain;      // [M, ldc] bf16(x1 * gain)
   float *ss_out;         // [tiles_n * waves_n][ss_stride] partial row sums of x1^2
+  float *rstd_out;       // split-K only (may be NULL): the reduction, which sees whole rows, leaves
+  float rstd_eps;        //   1 / sqrt(mean(x1^2) + rstd_eps) of each row here, and no pass over ss_out is needed
   // Split-K (QKV, RESID and RESID_NORM with few tiles): k_splits > 1 cuts K into that many ranges,
   // each (tile, range) is one workgroup that leaves fp32 partial products in splitk_ws
   // [k_splits][M][N]; a second kernel adds them up in a fixed order and applies the epilogue.
