@@ -188,8 +188,8 @@ def main():
                     help="also run a plain 1 GiB elementwise copy (for scaling HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the path shards by independent replicas, "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path shards by independent replicas, one "
+              "process and one request pool per GPU); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
